@@ -1,0 +1,103 @@
+"""Pins for the oracle's Algorithm 3 (Section V-D) and shuffle pairing: brute force on tiny inputs,
+hand-worked cases, the FIFO special case, and the defect of the listing as printed."""
+import itertools
+import os
+
+import numpy as np
+import pytest
+
+from oracle import oracle as orc
+import flover_synth as synth
+
+GOLD = os.path.join(os.path.dirname(__file__), "golden")
+
+
+def brute_force(arr):
+    """Definition: among all windows of size (#valid), the lowest offset leaving the fewest valid slots outside."""
+    n1 = int(sum(1 for a in arr if a))
+    if n1 == 0:
+        return 0, 0
+    best = None
+    for off in range(len(arr) - n1 + 1):
+        cost = n1 - sum(1 for a in arr[off:off + n1] if a)
+        if best is None or cost < best[1]:
+            best = (off, cost)
+    return best
+
+
+def test_all_binary_arrays_up_to_14():
+    for n in range(1, 15):
+        for bits in itertools.product((0, 1), repeat=n):
+            off, cost, nz = orc.find_window(bits)
+            assert nz == sum(bits)
+            assert (off, cost) == brute_force(bits), bits
+
+
+def test_hand_cases():
+    for line in open(os.path.join(GOLD, "alg3_hand_cases.txt")):
+        if line.startswith("#") or not line.strip():
+            continue
+        a, off, cost = line.split("|")
+        arr = [int(x) for x in a.split()]
+        got = orc.find_window(arr)
+        assert got[:2] == (int(off), int(cost)), arr
+
+
+def test_fifo_needs_no_move():
+    # Section V-D: when requests finish in arrival order the live region stays contiguous.
+    for n in range(1, 20):
+        for k in range(0, n + 1):
+            for arr in ([0] * k + [1] * (n - k), [1] * (n - k) + [0] * k):
+                off, cost, nz = orc.find_window(arr)
+                assert cost == 0
+                assert orc.plan_moves(arr, off, nz) == []
+
+
+def test_listing_as_printed_is_not_minimal():
+    # The printed listing starts window_cost at 0 and its loop at i = non_zero, so the window at offset 0 is never
+    # scored (and the running window_cost is not a window sum): [1,1,0] -> offset 1, which needs one move where
+    # offset 0 needs none.
+    assert orc.find_window_as_printed([1, 1, 0])[0] == 1
+    assert orc.find_window([1, 1, 0])[:2] == (0, 0)
+    worse = 0
+    for n in range(1, 11):
+        for bits in itertools.product((0, 1), repeat=n):
+            off_p, _ = orc.find_window_as_printed(bits)
+            _, c_fixed, nz = orc.find_window(bits)
+            if nz == 0 or nz == n:
+                continue    # the printed loop body never runs
+            c_printed = nz - sum(bits[off_p:off_p + nz])    # moves the printed offset really needs
+            assert c_printed >= c_fixed
+            worse += c_printed > c_fixed
+    assert worse > 0
+
+
+def test_moves_are_a_valid_minimal_compaction():
+    for arr in synth.occupancy_arrays(7, 300, 64):
+        arr = arr.tolist()
+        off, cost, nz = orc.find_window(arr)
+        moves = orc.plan_moves(arr, off, nz)
+        assert len(moves) == cost
+        srcs = [s for s, _ in moves]
+        dsts = [d for _, d in moves]
+        assert srcs == sorted(srcs) and dsts == sorted(dsts)
+        assert all(arr[s] == 1 and not (off <= s < off + nz) for s in srcs)
+        assert all(arr[d] == 0 and (off <= d < off + nz) for d in dsts)
+        after = list(arr)
+        for s, d in moves:
+            after[d], after[s] = 1, 0
+        assert after == [0] * off + [1] * nz + [0] * (len(arr) - off - nz)
+
+
+def test_weighted_entries_follow_the_listing():
+    # The listing sums arr[i] itself, so non-0/1 weights minimise the weight left outside the window.
+    rng = np.random.default_rng(3)
+    for _ in range(200):
+        n = int(rng.integers(1, 12))
+        arr = (rng.integers(0, 5, size=n) * (rng.random(n) < 0.6)).astype(int).tolist()
+        nz = sum(1 for a in arr if a)
+        off, cost, _ = orc.find_window(arr)
+        if nz == 0:
+            continue
+        costs = [sum(arr) - sum(arr[o:o + nz]) for o in range(n - nz + 1)]
+        assert cost == min(costs) and off == costs.index(min(costs))
