@@ -1,0 +1,208 @@
+/*
+ * flover.h -- C ABI of the fused decoder step of temporal fusion (Flover) on one MI355X.
+ *
+ * The library owns no device memory of its own: flover_init carves every buffer it will ever use
+ * out of a caller-provided device arena (the paper's Buffer Manager pre-allocates all buffers once,
+ * sized from max_concurrency, and never allocates during inference -- Section V-A).  All work is
+ * enqueued on the caller's HIP stream.  One caller thread per context (the paper's token
+ * generation thread T_I); calls are synchronous with respect to the host unless stated.
+ *
+ * Every function returns 0 on success or a negative FLOVER_E_* code; nothing throws or aborts
+ * across this boundary.  flover_last_error() gives the text of the most recent failure.
+ *
+ * Pointer arguments are marked [host] or [device].  "dtype" elements are 4-byte IEEE fp32,
+ * 2-byte IEEE fp16 or 2-byte bfloat16 according to flover_config.dtype.
+ */
+#ifndef FLOVER_H
+#define FLOVER_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum { FLOVER_OK = 0, FLOVER_E_INVAL = -1, FLOVER_E_FULL = -2, FLOVER_E_NOMEM = -3, FLOVER_E_STATE = -4, FLOVER_E_HIP = -5 };
+enum { FLOVER_ARCH_GPT = 0, FLOVER_ARCH_LLAMA = 1 };
+enum { FLOVER_F32 = 0, FLOVER_F16 = 1, FLOVER_BF16 = 2 };
+/* slot states reported by flover_get_state */
+enum { FLOVER_SLOT_EMPTY = 0, FLOVER_SLOT_READY = 1, FLOVER_SLOT_LIVE = 2, FLOVER_SLOT_DEAD = 3 };
+
+typedef struct flover_ctx flover_ctx;
+
+/* Model type, inference data type and request meta-specification read at launch (Section V-A). */
+typedef struct flover_config {
+  int32_t arch;            /* FLOVER_ARCH_*: GPT = LayerNorm, learned positions, biases, tanh-GELU;
+                              LLAMA = RMSNorm, rotary embedding (rotate-half, pairs (i, i+d/2)), SwiGLU, no biases */
+  int32_t dtype;           /* FLOVER_F32 | FLOVER_F16 | FLOVER_BF16: weights, KV cache and GEMM inputs */
+  int32_t n_layer, hidden, n_head, head_dim, ffn, vocab;   /* hidden == n_head * head_dim; head_dim in {64,128};
+                                                               n_head % 4 == 0; hidden, ffn multiples of 32 */
+  int32_t max_seq;         /* slot capacity in tokens */
+  int32_t max_concurrency; /* number of slots = most requests generating at once (Section V-A) */
+  int32_t eos_id;          /* token that ends a request; -1 = none (Section IV) */
+  int32_t shuffle_off;     /* non-zero: the variant without memory shuffle (Section VI-D): finished slots stay
+                              inside the window as holes that the kernels still cover */
+  float norm_eps;
+  float rope_theta;
+  void* stream;            /* hipStream_t the library enqueues on; NULL = the null stream */
+  void* arena;             /* [device] 256-byte aligned; owned by the caller, must outlive the context */
+  uint64_t arena_bytes;    /* >= flover_query_arena_bytes() */
+} flover_config;
+
+/* [device] pointers, dtype elements, every linear weight [out][in] with the input index contiguous,
+ * per-layer tensors stacked over layers in the leading dimension.  Unused entries (by arch) may be NULL.
+ * flover_init copies (and re-tiles) all of them into the arena; the caller may free them afterwards. */
+typedef struct flover_weights {
+  const void* wte;    /* [vocab][hidden] token embedding (GPT: also the output projection) */
+  const void* wpe;    /* GPT [max_seq][hidden] learned positions */
+  const void* ln1_g;  /* [L][hidden] */
+  const void* ln1_b;  /* GPT [L][hidden] */
+  const void* wqkv;   /* [L][3*hidden][hidden], rows: q heads, k heads, v heads */
+  const void* bqkv;   /* GPT [L][3*hidden] */
+  const void* wo;     /* [L][hidden][hidden] */
+  const void* bo;     /* GPT [L][hidden] */
+  const void* ln2_g;  /* [L][hidden] */
+  const void* ln2_b;  /* GPT [L][hidden] */
+  const void* w1;     /* [L][ffn][hidden]  GPT: first MLP matrix; LLAMA: gate */
+  const void* b1;     /* GPT [L][ffn] */
+  const void* wu;     /* LLAMA [L][ffn][hidden] up */
+  const void* w2;     /* [L][hidden][ffn]  second MLP matrix / down */
+  const void* b2;     /* GPT [L][hidden] */
+  const void* lnf_g;  /* [hidden] */
+  const void* lnf_b;  /* GPT [hidden] */
+  const void* wlm;    /* LLAMA [vocab][hidden] output projection */
+} flover_weights;
+
+/* Upper bound of device memory for this configuration (Buffer Manager's calculation, Section V-A).
+ * Only the shape fields of cfg are read. */
+int32_t flover_query_arena_bytes(const flover_config* cfg, uint64_t* out_bytes);
+
+/* Launcher + Buffer Manager + scheduler start (Section V-A, Algorithm 1's first lines): lays out the arena
+ * (re-tiled weights, KV cache [L][K|V][slot][head][max_seq][head_dim], per-iteration buffers), copies the
+ * weights in, creates the request and inference queues.  Blocks until the copies are done.
+ * Errors: INVAL (bad shape / NULL required weight / misaligned arena), NOMEM (arena too small), HIP. */
+int32_t flover_init(const flover_config* cfg, const flover_weights* w, flover_ctx** out_ctx);
+
+/* Waits for the stream, releases host resources.  The arena is the caller's. */
+int32_t flover_destroy(flover_ctx* ctx);
+
+/* Text of the last error on ctx (ctx == NULL: of the last failed flover_init / query / kernel-level call).
+ * Owned by the library, valid until the next failing call. */
+const char* flover_last_error(const flover_ctx* ctx);
+
+/* Body of Algorithm 1 for one request (Section V-B): assign the slot adjacent to the live region
+ * (hi if hi < max_concurrency, else lo-1; an empty region restarts at slot 0), copy the prompt [host] to
+ * the device, run pre-processing -- the context decoder fills the slot's KV cache for prompt positions
+ * 0..prompt_len-2 -- and put the request into the inference queue.  It joins the fused stream at the next
+ * flover_step, which feeds prompt[prompt_len-1].  If no adjacent slot is free the request waits in the
+ * request queue (FIFO) and is pre-processed by a later flover_step; *out_slot = -1 then.
+ * The prompt is copied before return.  Errors: INVAL (prompt_len < 1, max_new_tokens < 1,
+ * prompt_len + max_new_tokens > max_seq, token out of range, req_id already waiting or live). */
+int32_t flover_add_request(flover_ctx* ctx, uint64_t req_id, const int32_t* prompt, int32_t prompt_len,
+                           int32_t max_new_tokens, int32_t* out_slot);
+
+typedef struct flover_step_out {
+  int32_t capacity;     /* in: entries each [host] array below can hold (>= max_concurrency is always enough) */
+  int32_t n_live;       /* out: requests advanced in this iteration */
+  uint64_t* req_id;     /* [host] out, ascending slot order */
+  int32_t* slot;        /* [host] out */
+  int32_t* token;       /* [host] out: the greedy token (argmax of the fp32 logits, lowest index on ties) */
+  int32_t* finished;    /* [host] out: 1 if the request ended with this token (EOS or length limit, Section IV) */
+  float* logits;        /* [device] optional, caller-owned [capacity][vocab] fp32: row i = logits of entry i */
+} flover_step_out;
+
+/* One iteration of Algorithm 2 (Section V-C) up to and including the detection of finished requests:
+ * waiting requests take free adjacent slots and are pre-processed; every ready request is admitted
+ * (Update(offset,size)); ONE launch per operation covers all live requests -- embedding, norms, the weight
+ * GEMMs, rotary + KV append, ragged attention over each request's own cache length, MLP, output projection,
+ * argmax.  Returns after the tokens are on the host.  n_live == 0 is not an error.  Finished requests keep
+ * their slot (state DEAD) until flover_reorder_evict.  Errors: INVAL (capacity too small), HIP. */
+int32_t flover_step(flover_ctx* ctx, flover_step_out* out);
+
+typedef struct flover_reorder_out {
+  int32_t capacity;        /* in: entries each [host] array can hold; must be >= max_concurrency */
+  int32_t n_evicted;       /* out */
+  uint64_t* evicted_req_id;/* [host] out, ascending slot order */
+  int32_t mem_offset;      /* out: Algorithm 3's result, relative to the old window start */
+  int32_t new_lo;          /* out: window start after the call (buffer offset, in slots) */
+  int32_t new_size;        /* out: window size after the call (buffer size, in slots) */
+  int32_t min_cost;        /* out: Algorithm 3's cost = number of slots that had to move */
+  int32_t n_moves;         /* out */
+  int32_t* move_src;       /* [host] out, absolute slot indices */
+  int32_t* move_dst;       /* [host] out */
+  int64_t bytes_moved;     /* out: read + written bytes of KV rows [0,len) of the moved slots */
+} flover_reorder_out;
+
+/* FindAndEvict's removal, Algorithm 3 and the memory shuffle (Algorithm 2's last lines, Section V-D).
+ * Frees DEAD slots; over the 0/1 occupancy of the old window finds, with the sliding window of Algorithm 3
+ * (first window scored too, lowest offset on ties), the region of size #valid that leaves the fewest valid
+ * slots outside; copies, in one launch, the KV rows [0,len) of each outside slot into a hole inside (i-th hole
+ * ascending <- i-th outside slot ascending) and moves the scheduler's record with it.  Waits for the copy.
+ * With shuffle_off only the empty ends of the window are dropped.  Safe to call after every step. */
+int32_t flover_reorder_evict(flover_ctx* ctx, flover_reorder_out* out);
+
+/* Test / benchmark hooks (not in the paper): end a request as if it had produced EOS; overwrite the token a
+ * live request feeds in the next iteration (teacher forcing, to re-synchronise a comparison after a near tie). */
+int32_t flover_mark_finished(flover_ctx* ctx, uint64_t req_id);
+int32_t flover_set_next_token(flover_ctx* ctx, uint64_t req_id, int32_t token);
+
+/* Read-only snapshot.  lo_hi_wait [host][3] = window start, window end, requests waiting for a slot;
+ * the other [host] arrays hold max_concurrency entries (any may be NULL). */
+int32_t flover_get_state(const flover_ctx* ctx, int32_t* lo_hi_wait, int32_t* state, uint64_t* req_id, int32_t* len,
+                         int32_t* next_token, int32_t* generated);
+
+/* [device] address and byte strides of the KV cache inside the arena, for inspection by tests:
+ * element (layer, k_or_v, slot, head, pos, i) lives at base + ((((layer*2+k_or_v)*C + slot)*n_head + head)*max_seq
+ * + pos)*head_dim + i elements. */
+int32_t flover_get_kv_cache(const flover_ctx* ctx, void** base, uint64_t* bytes);
+
+/* Kernel launches issued by the most recent flover_step (Table I: one launch per operation however many
+ * requests are live). */
+int32_t flover_last_step_launches(const flover_ctx* ctx, int32_t* n);
+
+/* ------------------------------------------------------------------ operation-level entry points
+ * The same kernels the step uses, callable on caller-owned buffers (micro-benchmarks, unit parity).
+ * All enqueue on `stream` and return without waiting unless stated. */
+
+/* Algorithm 3 on a [host] occupancy array (0 = empty); host only. */
+int32_t flover_k_find_window(const int32_t* arr, int32_t n, int32_t* mem_offset, int32_t* min_cost, int32_t* non_zero);
+
+/* Bytes of [device] workspace flover_k_decode_attention needs for up to M rows of length <= max_len. */
+int32_t flover_k_attention_workspace_bytes(int32_t M, int32_t n_head, int32_t head_dim, int32_t max_len, uint64_t* out);
+
+/* Ragged masked self-attention of one decode iteration (the attention inside Algorithm 2's "..."):
+ * for every row m and head h:  out[m][h] = softmax(q[m][h] . K[slot[m]][h][0..len[m]) / sqrt(head_dim)) V[...],
+ * fp32 scores, softmax and accumulation, result rounded to dtype.
+ * q, out [device][M][n_head][head_dim]; kcache, vcache [device][C][n_head][S][head_dim]; slot, len [host][M]
+ * (1 <= len[m] <= S, 0 <= slot[m] < C); workspace [device].  The host arrays are consumed before return
+ * (this call waits for its small host-to-device copy, not for the kernels). */
+int32_t flover_k_decode_attention(int32_t dtype, const void* q, const void* kcache, const void* vcache,
+                                  const int32_t* slot, const int32_t* len, int32_t M, int32_t C, int32_t n_head,
+                                  int32_t head_dim, int32_t S, void* out, void* workspace, uint64_t workspace_bytes,
+                                  void* stream);
+
+/* Bytes of [device] workspace flover_k_compact needs for n_moves moves. */
+int32_t flover_k_compact_workspace_bytes(int32_t n_moves, uint64_t* out);
+
+/* The memory-shuffle copy (Section V-D): for every move i and every (layer, K|V, head), copy rows [0,len[i]) of slot
+ * src[i] to slot dst[i] in cache [device][L][2][C][n_head][S][head_dim] (elem_bytes per element), all in one launch.
+ * src, dst, len [host][n_moves]; source and destination slot sets must be disjoint (INVAL otherwise). */
+int32_t flover_k_compact(void* cache, int32_t L, int32_t C, int32_t n_head, int32_t S, int32_t head_dim,
+                         int32_t elem_bytes, const int32_t* src, const int32_t* dst, const int32_t* len,
+                         int32_t n_moves, void* workspace, uint64_t workspace_bytes, void* stream);
+
+/* Weight GEMM of the fused rows: y[M][N] (fp32) = x[M][K] . W[N][K]^T, fp32 accumulation (MFMA for the 16-bit
+ * dtypes).  W is first re-tiled into `w_tiled` (flover_k_gemm_tiled_bytes bytes, [device]) by flover_k_gemm_retile;
+ * flover_k_gemm then streams the tiled copy.  x [device][Mpad][K]: rows up to M rounded up to a multiple of 128 must be
+ * readable (their contents do not matter);
+ * workspace holds the split-K partial sums.  K % 32 == 0. */
+int32_t flover_k_gemm_tiled_bytes(int32_t dtype, int32_t N, int32_t K, uint64_t* out);
+int32_t flover_k_gemm_workspace_bytes(int32_t dtype, int32_t M, int32_t N, int32_t K, uint64_t* out);
+int32_t flover_k_gemm_retile(int32_t dtype, const void* W, int32_t N, int32_t K, void* w_tiled, void* stream);
+int32_t flover_k_gemm(int32_t dtype, const void* x, const void* w_tiled, int32_t M, int32_t N, int32_t K, float* y,
+                      void* workspace, uint64_t workspace_bytes, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* FLOVER_H */

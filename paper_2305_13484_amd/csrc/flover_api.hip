@@ -1,0 +1,826 @@
+// C ABI of the fused decoder step: Buffer Manager (arena layout), Inference Scheduler (queues, slot window,
+// Algorithm 3) and the per-iteration launch sequence.  See include/flover.h for the contract of every call.
+//
+// Paper mapping: flover_init = Launcher + Buffer Manager + scheduler start (Section V-A); flover_add_request =
+// body of Algorithm 1 (Section V-B); flover_step = Algorithm 2 up to FindAndEvict's detection (Section V-C);
+// flover_reorder_evict = eviction, Algorithm 3 and the memory shuffle (Section V-D).
+#include "../../include/flover.h"
+
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <cmath>
+#include <cstdio>
+#include <cstring>
+#include <deque>
+#include <string>
+#include <vector>
+
+#include "flover_kernels.h"
+
+namespace {
+
+std::string g_err;   // last error of calls that have no context
+
+struct Slot {
+  int state = FLOVER_SLOT_EMPTY;
+  uint64_t req_id = 0;
+  int len = 0;          // cached KV rows = position of the next token fed
+  int next_token = 0;
+  int generated = 0;
+  int max_new = 0;
+};
+struct Waiting {
+  uint64_t req_id;
+  std::vector<int32_t> prompt;
+  int max_new;
+};
+struct LayerW {
+  void *ln1_g, *ln1_b, *wqkv, *bqkv, *wo, *bo, *ln2_g, *ln2_b, *w1, *b1, *w2, *b2;
+};
+struct Row {
+  int slot, tok, pos;
+};
+
+size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+int esize(int dtype) { return dtype == FLOVER_F32 ? 4 : 2; }
+
+// Bump allocator over the arena; with base == nullptr it only measures.
+struct Bump {
+  char* base;
+  size_t off = 0;
+  void* take(size_t bytes) {
+    off = align_up(off, 256);
+    void* p = base ? base + off : nullptr;
+    off += bytes;
+    return p;
+  }
+};
+
+}  // namespace
+
+struct flover_ctx {
+  flover_config cfg;
+  hipStream_t st;
+  std::string err;
+  // weights in the arena
+  std::vector<LayerW> lw;
+  void *wte, *wpe, *lnf_g, *lnf_b, *wlm;
+  float* rope_cs;
+  flk::GemmPlan p_qkv, p_o, p_1, p_2, p_lm;
+  // KV cache [L][2][C][nh][S][d]
+  char* kv;
+  size_t kv_bytes, slot_bytes, plane_bytes;
+  // per-iteration buffers
+  int rows_cap, max_items;
+  float* x;
+  void *h, *q, *att, *act;
+  float* part;
+  float* logits;
+  int* tok_out;
+  int* d_stage;   // tok | pos | slot | len | item0 | nchunk | items(2x)
+  float *pml, *po;
+  int4* d_moves;
+  // pinned host staging
+  int* h_stage;
+  int* h_tok;
+  int4* h_moves;
+  size_t stage_ints;
+  // scheduler
+  std::vector<Slot> slots;
+  std::deque<Waiting> reque;   // Q_R
+  int lo = 0, hi = 0;          // window [lo,hi): buffer offset and size in slots
+  int last_launches = 0;
+  int launches = 0;
+};
+
+namespace {
+
+int fail(flover_ctx* c, int code, const std::string& msg) {
+  if (c) c->err = msg;
+  else g_err = msg;
+  return code;
+}
+#define HIPCHK(ctx, expr)                                                                        \
+  do {                                                                                           \
+    hipError_t e_ = (expr);                                                                      \
+    if (e_ != hipSuccess)                                                                        \
+      return fail(ctx, FLOVER_E_HIP, std::string(#expr) + ": " + hipGetErrorString(e_));          \
+  } while (0)
+
+int check_shape(const flover_config* c, std::string* why) {
+  auto bad = [&](const char* m) { *why = m; return FLOVER_E_INVAL; };
+  if (!c) return bad("null config");
+  if (c->arch != FLOVER_ARCH_GPT && c->arch != FLOVER_ARCH_LLAMA) return bad("arch");
+  if (c->dtype < FLOVER_F32 || c->dtype > FLOVER_BF16) return bad("dtype");
+  if (c->n_layer < 1 || c->hidden < 32 || c->n_head < 4 || c->ffn < 32 || c->vocab < 2) return bad("shape");
+  if (c->head_dim != 64 && c->head_dim != 128) return bad("head_dim must be 64 or 128");
+  if (c->hidden != c->n_head * c->head_dim) return bad("hidden != n_head * head_dim");
+  if (c->n_head % 4) return bad("n_head must be a multiple of 4");
+  if (c->hidden % 32 || c->ffn % 32) return bad("hidden and ffn must be multiples of 32");
+  if (c->hidden > 8192) return bad("hidden > 8192");
+  if (c->max_seq < 2 || c->max_concurrency < 1) return bad("max_seq / max_concurrency");
+  return FLOVER_OK;
+}
+
+// Lays the arena out; fills ctx pointers when base != nullptr.  Returns bytes used.
+size_t layout(flover_ctx* c, char* base) {
+  const flover_config& f = c->cfg;
+  const int e = esize(f.dtype), L = f.n_layer, H = f.hidden, F = f.ffn, V = f.vocab, C = f.max_concurrency, S = f.max_seq;
+  const bool gpt = f.arch == FLOVER_ARCH_GPT;
+  Bump b{base};
+  c->p_qkv = flk::gemm_plan(f.dtype, 3 * H, H);
+  c->p_o = flk::gemm_plan(f.dtype, H, H);
+  c->p_1 = flk::gemm_plan(f.dtype, gpt ? F : 2 * F, H);
+  c->p_2 = flk::gemm_plan(f.dtype, H, F);
+  c->p_lm = flk::gemm_plan(f.dtype, V, H);
+  c->lw.resize(L);
+  for (int l = 0; l < L; ++l) {
+    LayerW& w = c->lw[l];
+    w.ln1_g = b.take((size_t)H * e);
+    w.ln1_b = gpt ? b.take((size_t)H * e) : nullptr;
+    w.wqkv = b.take(flk::gemm_tiled_bytes(f.dtype, 3 * H, H));
+    w.bqkv = gpt ? b.take((size_t)3 * H * e) : nullptr;
+    w.wo = b.take(flk::gemm_tiled_bytes(f.dtype, H, H));
+    w.bo = gpt ? b.take((size_t)H * e) : nullptr;
+    w.ln2_g = b.take((size_t)H * e);
+    w.ln2_b = gpt ? b.take((size_t)H * e) : nullptr;
+    w.w1 = b.take(flk::gemm_tiled_bytes(f.dtype, gpt ? F : 2 * F, H));
+    w.b1 = gpt ? b.take((size_t)F * e) : nullptr;
+    w.w2 = b.take(flk::gemm_tiled_bytes(f.dtype, H, F));
+    w.b2 = gpt ? b.take((size_t)H * e) : nullptr;
+  }
+  c->wte = b.take((size_t)V * H * e);
+  c->wpe = gpt ? b.take((size_t)S * H * e) : nullptr;
+  c->lnf_g = b.take((size_t)H * e);
+  c->lnf_b = gpt ? b.take((size_t)H * e) : nullptr;
+  c->wlm = b.take(flk::gemm_tiled_bytes(f.dtype, V, H));
+  c->rope_cs = gpt ? nullptr : (float*)b.take((size_t)S * (f.head_dim / 2) * 2 * sizeof(float));
+  c->slot_bytes = (size_t)f.n_head * S * f.head_dim * e;
+  c->plane_bytes = c->slot_bytes * C;
+  c->kv_bytes = c->plane_bytes * 2 * L;
+  c->kv = (char*)b.take(c->kv_bytes);
+  const int R = (std::max(C, 128) + 127) / 128 * 128;
+  c->rows_cap = R;
+  const int chunks = (S + flk::kAttnChunk - 1) / flk::kAttnChunk;
+  c->max_items = R * chunks;
+  c->x = (float*)b.take((size_t)R * H * 4);
+  c->h = b.take((size_t)R * H * e);
+  c->q = b.take((size_t)R * H * e);
+  c->att = b.take((size_t)R * H * e);
+  c->act = b.take((size_t)R * F * e);
+  size_t pw = 0;
+  for (const flk::GemmPlan* p : {&c->p_qkv, &c->p_o, &c->p_1, &c->p_2, &c->p_lm}) pw = std::max(pw, (size_t)p->S * p->N);
+  c->part = (float*)b.take(pw * R * 4);
+  c->logits = (float*)b.take((size_t)R * V * 4);
+  c->tok_out = (int*)b.take((size_t)R * 4);
+  c->stage_ints = (size_t)6 * R + (size_t)2 * c->max_items;
+  c->d_stage = (int*)b.take(c->stage_ints * 4);
+  c->pml = (float*)b.take((size_t)c->max_items * f.n_head * 2 * 4);
+  c->po = (float*)b.take((size_t)c->max_items * f.n_head * f.head_dim * 4);
+  c->d_moves = (int4*)b.take((size_t)C * sizeof(int4));
+  return align_up(b.off, 256);
+}
+
+// AssignMemId: the slot adjacent to the live region, or -1 if none is free.
+int place(flover_ctx* c) {
+  if (c->lo == c->hi) {
+    c->lo = 0;
+    c->hi = 1;
+    return 0;
+  }
+  if (c->hi < c->cfg.max_concurrency) return c->hi++;
+  if (c->lo > 0) return --c->lo;
+  return -1;
+}
+
+// One pass of the decoder over n rows: a single launch per operation covers all of them.
+// With want_tokens the final norm, output projection and argmax run and tok_out (device) holds the choices.
+int run_rows(flover_ctx* c, const Row* rows, int n, bool want_tokens, float* logits_out) {
+  const flover_config& f = c->cfg;
+  const int H = f.hidden, F = f.ffn, V = f.vocab, nh = f.n_head, d = f.head_dim, L = f.n_layer, R = c->rows_cap;
+  const bool gpt = f.arch == FLOVER_ARCH_GPT;
+  hipStream_t st = c->st;
+  if (n <= 0) return FLOVER_OK;
+  // row descriptors and the attention work list, one host-to-device copy
+  int* hs = c->h_stage;
+  int *tok = hs, *pos = hs + R, *slot = hs + 2 * R, *len = hs + 3 * R, *item0 = hs + 4 * R, *nchunk = hs + 5 * R;
+  int* items = hs + 6 * R;
+  int n_items = 0;
+  for (int i = 0; i < n; ++i) {
+    tok[i] = rows[i].tok;
+    pos[i] = rows[i].pos;
+    slot[i] = rows[i].slot;
+    len[i] = rows[i].pos + 1;
+    item0[i] = n_items;
+    const int nc = (len[i] + flk::kAttnChunk - 1) / flk::kAttnChunk;
+    nchunk[i] = nc;
+    for (int ch = 0; ch < nc; ++ch) {
+      items[2 * n_items] = i;
+      items[2 * n_items + 1] = ch;
+      ++n_items;
+    }
+  }
+  HIPCHK(c, hipMemcpyAsync(c->d_stage, hs, ((size_t)6 * R + (size_t)2 * n_items) * 4, hipMemcpyHostToDevice, st));
+  int* ds = c->d_stage;
+  const int *d_tok = ds, *d_pos = ds + R, *d_slot = ds + 2 * R, *d_len = ds + 3 * R, *d_item0 = ds + 4 * R,
+            *d_nchunk = ds + 5 * R;
+  flk::AttnWork aw{(const int2*)(ds + 6 * R), d_slot, d_len, d_item0, d_nchunk, c->pml, c->po, n_items, flk::kAttnChunk};
+
+  int launches = 0;
+  const size_t ss_qkv = (size_t)n * 3 * H, ss_h = (size_t)n * H, ss_1 = (size_t)n * c->p_1.N, ss_v = (size_t)n * V;
+  HIPCHK(c, flk::embed(f.dtype, c->wte, c->wpe, d_tok, d_pos, c->x, n, H, st));
+  ++launches;
+  for (int l = 0; l < L; ++l) {
+    const LayerW& w = c->lw[l];
+    const bool first = l == 0;
+    HIPCHK(c, flk::add_norm(f.dtype, !gpt, c->x, first ? nullptr : c->part, c->p_2.S, ss_h, first ? nullptr : c->lw[l - 1].b2,
+                            w.ln1_g, w.ln1_b, c->h, n, H, f.norm_eps, st));
+    HIPCHK(c, flk::gemm(f.dtype, c->h, w.wqkv, n, c->p_qkv, c->part, ss_qkv, 3 * H, st));
+    char* kl = c->kv + (size_t)(2 * l) * c->plane_bytes;
+    char* vl = kl + c->plane_bytes;
+    HIPCHK(c, flk::qkv_post(f.dtype, c->part, c->p_qkv.S, ss_qkv, w.bqkv, c->rope_cs, d_slot, d_pos, c->q, kl, vl, n, H, nh,
+                            d, f.max_seq, st));
+    HIPCHK(c, flk::decode_attention(f.dtype, d, c->q, kl, vl, aw, n, nh, f.max_seq, c->att, st));
+    HIPCHK(c, flk::gemm(f.dtype, c->att, w.wo, n, c->p_o, c->part, ss_h, H, st));
+    HIPCHK(c, flk::add_norm(f.dtype, !gpt, c->x, c->part, c->p_o.S, ss_h, w.bo, w.ln2_g, w.ln2_b, c->h, n, H, f.norm_eps, st));
+    HIPCHK(c, flk::gemm(f.dtype, c->h, w.w1, n, c->p_1, c->part, ss_1, c->p_1.N, st));
+    HIPCHK(c, flk::activation(f.dtype, !gpt, c->part, c->p_1.S, ss_1, w.b1, c->act, n, F, st));
+    HIPCHK(c, flk::gemm(f.dtype, c->act, w.w2, n, c->p_2, c->part, ss_h, H, st));
+    launches += 10;
+  }
+  if (want_tokens) {
+    HIPCHK(c, flk::add_norm(f.dtype, !gpt, c->x, c->part, c->p_2.S, ss_h, c->lw[L - 1].b2, c->lnf_g, c->lnf_b, c->h, n, H,
+                            f.norm_eps, st));
+    HIPCHK(c, flk::gemm(f.dtype, c->h, c->wlm, n, c->p_lm, c->part, ss_v, V, st));
+    HIPCHK(c, flk::logits_argmax(c->part, c->p_lm.S, ss_v, logits_out, c->tok_out, n, V, st));
+    HIPCHK(c, hipMemcpyAsync(c->h_tok, c->tok_out, (size_t)n * 4, hipMemcpyDeviceToHost, st));
+    launches += 3;
+  }
+  HIPCHK(c, hipStreamSynchronize(st));   // staging buffers are reused by the next call
+  c->launches += launches;
+  return FLOVER_OK;
+}
+
+// Pre-processing (Section V-B): the context decoder caches K/V of prompt positions 0..P-2 in the assigned slot.
+int preprocess(flover_ctx* c, int slot, const Waiting& r) {
+  Slot& s = c->slots[slot];
+  s.state = FLOVER_SLOT_READY;
+  s.req_id = r.req_id;
+  s.generated = 0;
+  s.max_new = r.max_new;
+  const int P = (int)r.prompt.size();
+  std::vector<Row> rows;
+  for (int p0 = 0; p0 + 1 < P; p0 += c->rows_cap) {
+    const int n = std::min(c->rows_cap, P - 1 - p0);
+    rows.resize(n);
+    for (int i = 0; i < n; ++i) rows[i] = Row{slot, r.prompt[p0 + i], p0 + i};
+    int rc = run_rows(c, rows.data(), n, false, nullptr);
+    if (rc != FLOVER_OK) return rc;
+  }
+  s.len = P - 1;
+  s.next_token = r.prompt[P - 1];
+  return FLOVER_OK;
+}
+
+bool known(const flover_ctx* c, uint64_t id) {
+  for (const Slot& s : c->slots)
+    if ((s.state == FLOVER_SLOT_READY || s.state == FLOVER_SLOT_LIVE) && s.req_id == id) return true;
+  for (const Waiting& r : c->reque)
+    if (r.req_id == id) return true;
+  return false;
+}
+
+// Algorithm 3 with the first window scored before the loop (as printed the listing never scores offset 0).
+int find_window(const int32_t* arr, int n, int* min_cost, int* non_zero) {
+  long total_cost = 0;
+  int nz = 0;
+  for (int i = 0; i < n; ++i)
+    if (arr[i] != 0) {
+      ++nz;
+      total_cost += arr[i];
+    }
+  long window_cost = 0;
+  for (int i = 0; i < nz; ++i) window_cost += arr[i];
+  long best = total_cost - window_cost;
+  int off = 0;
+  for (int i = nz; i < n; ++i) {
+    window_cost += arr[i] - arr[i - nz];
+    const long cur = total_cost - window_cost;
+    if (cur < best) {
+      best = cur;
+      off = i - nz + 1;
+    }
+  }
+  *min_cost = (int)best;
+  *non_zero = nz;
+  return off;
+}
+
+int copy_in(flover_ctx* c, void* dst, const void* src, size_t bytes, const char* name) {
+  if (!src) return fail(c, FLOVER_E_INVAL, std::string("missing weight: ") + name);
+  HIPCHK(c, hipMemcpyAsync(dst, src, bytes, hipMemcpyDeviceToDevice, c->st));
+  return FLOVER_OK;
+}
+
+}  // namespace
+
+// ===================================================================== public API
+
+extern "C" {
+
+const char* flover_last_error(const flover_ctx* ctx) { return ctx ? ctx->err.c_str() : g_err.c_str(); }
+
+int32_t flover_query_arena_bytes(const flover_config* cfg, uint64_t* out_bytes) {
+  std::string why;
+  if (!out_bytes) return fail(nullptr, FLOVER_E_INVAL, "null out_bytes");
+  int rc = check_shape(cfg, &why);
+  if (rc != FLOVER_OK) return fail(nullptr, rc, why);
+  flover_ctx tmp{};
+  tmp.cfg = *cfg;
+  *out_bytes = layout(&tmp, nullptr);
+  return FLOVER_OK;
+}
+
+int32_t flover_init(const flover_config* cfg, const flover_weights* w, flover_ctx** out_ctx) {
+  std::string why;
+  if (!out_ctx || !w) return fail(nullptr, FLOVER_E_INVAL, "null argument");
+  *out_ctx = nullptr;
+  int rc = check_shape(cfg, &why);
+  if (rc != FLOVER_OK) return fail(nullptr, rc, why);
+  if (!cfg->arena || ((uintptr_t)cfg->arena & 255)) return fail(nullptr, FLOVER_E_INVAL, "arena null or not 256-byte aligned");
+  flover_ctx* c = new flover_ctx();
+  c->cfg = *cfg;
+  c->st = (hipStream_t)cfg->stream;
+  const size_t need = layout(c, (char*)cfg->arena);
+  if (need > cfg->arena_bytes) {
+    delete c;
+    return fail(nullptr, FLOVER_E_NOMEM, "arena too small: need " + std::to_string(need) + " bytes");
+  }
+  auto bail = [&](int code) {
+    g_err = c->err;
+    if (c->h_stage) (void)hipHostFree(c->h_stage);
+    if (c->h_tok) (void)hipHostFree(c->h_tok);
+    if (c->h_moves) (void)hipHostFree(c->h_moves);
+    delete c;
+    return code;
+  };
+#define TRY(expr)                  \
+  do {                             \
+    int rc_ = (expr);              \
+    if (rc_ != FLOVER_OK) return bail(rc_); \
+  } while (0)
+#define HIPTRY(expr)                                                                  \
+  do {                                                                                \
+    hipError_t e_ = (expr);                                                           \
+    if (e_ != hipSuccess) {                                                           \
+      c->err = std::string(#expr) + ": " + hipGetErrorString(e_);                     \
+      return bail(FLOVER_E_HIP);                                                      \
+    }                                                                                 \
+  } while (0)
+  c->h_stage = nullptr;
+  c->h_tok = nullptr;
+  c->h_moves = nullptr;
+  HIPTRY(hipHostMalloc((void**)&c->h_stage, c->stage_ints * 4, hipHostMallocDefault));
+  HIPTRY(hipHostMalloc((void**)&c->h_tok, (size_t)c->rows_cap * 4, hipHostMallocDefault));
+  HIPTRY(hipHostMalloc((void**)&c->h_moves, (size_t)cfg->max_concurrency * sizeof(int4), hipHostMallocDefault));
+
+  const flover_config& f = c->cfg;
+  const int e = esize(f.dtype), L = f.n_layer, H = f.hidden, F = f.ffn, V = f.vocab, S = f.max_seq;
+  const bool gpt = f.arch == FLOVER_ARCH_GPT;
+  hipStream_t st = c->st;
+  // everything the kernels may read before it is written starts at zero (padding tiles, cache, row buffers)
+  const size_t act_off = (char*)c->x - (char*)cfg->arena;
+  HIPTRY(flk::zero_fill(c->x, need - act_off, st));
+  for (int l = 0; l < L; ++l) {
+    LayerW& lw = c->lw[l];
+    const size_t o1 = (size_t)l * H * e;
+    TRY(copy_in(c, lw.ln1_g, w->ln1_g ? (const char*)w->ln1_g + o1 : nullptr, (size_t)H * e, "ln1_g"));
+    TRY(copy_in(c, lw.ln2_g, w->ln2_g ? (const char*)w->ln2_g + o1 : nullptr, (size_t)H * e, "ln2_g"));
+    if (!w->wqkv || !w->wo || !w->w1 || !w->w2 || (!gpt && !w->wu)) {
+      c->err = "missing weight matrix";
+      return bail(FLOVER_E_INVAL);
+    }
+    if (f.dtype != FLOVER_F32) {
+      HIPTRY(flk::zero_fill(lw.wqkv, flk::gemm_tiled_bytes(f.dtype, 3 * H, H), st));
+      HIPTRY(flk::zero_fill(lw.wo, flk::gemm_tiled_bytes(f.dtype, H, H), st));
+      HIPTRY(flk::zero_fill(lw.w1, flk::gemm_tiled_bytes(f.dtype, gpt ? F : 2 * F, H), st));
+      HIPTRY(flk::zero_fill(lw.w2, flk::gemm_tiled_bytes(f.dtype, H, F), st));
+    }
+    HIPTRY(flk::retile(f.dtype, (const char*)w->wqkv + (size_t)l * 3 * H * H * e, 3 * H, H, lw.wqkv, 0, st));
+    HIPTRY(flk::retile(f.dtype, (const char*)w->wo + (size_t)l * H * H * e, H, H, lw.wo, 0, st));
+    HIPTRY(flk::retile(f.dtype, (const char*)w->w1 + (size_t)l * F * H * e, F, H, lw.w1, 0, st));
+    if (!gpt) HIPTRY(flk::retile(f.dtype, (const char*)w->wu + (size_t)l * F * H * e, F, H, lw.w1, F, st));
+    HIPTRY(flk::retile(f.dtype, (const char*)w->w2 + (size_t)l * H * F * e, H, F, lw.w2, 0, st));
+    if (gpt) {
+      TRY(copy_in(c, lw.ln1_b, w->ln1_b ? (const char*)w->ln1_b + o1 : nullptr, (size_t)H * e, "ln1_b"));
+      TRY(copy_in(c, lw.ln2_b, w->ln2_b ? (const char*)w->ln2_b + o1 : nullptr, (size_t)H * e, "ln2_b"));
+      TRY(copy_in(c, lw.bqkv, w->bqkv ? (const char*)w->bqkv + (size_t)l * 3 * H * e : nullptr, (size_t)3 * H * e, "bqkv"));
+      TRY(copy_in(c, lw.bo, w->bo ? (const char*)w->bo + o1 : nullptr, (size_t)H * e, "bo"));
+      TRY(copy_in(c, lw.b1, w->b1 ? (const char*)w->b1 + (size_t)l * F * e : nullptr, (size_t)F * e, "b1"));
+      TRY(copy_in(c, lw.b2, w->b2 ? (const char*)w->b2 + o1 : nullptr, (size_t)H * e, "b2"));
+    }
+  }
+  TRY(copy_in(c, c->wte, w->wte, (size_t)V * H * e, "wte"));
+  TRY(copy_in(c, c->lnf_g, w->lnf_g, (size_t)H * e, "lnf_g"));
+  if (gpt) {
+    TRY(copy_in(c, c->wpe, w->wpe, (size_t)S * H * e, "wpe"));
+    TRY(copy_in(c, c->lnf_b, w->lnf_b, (size_t)H * e, "lnf_b"));
+  }
+  const void* lm = gpt ? w->wte : w->wlm;
+  if (!lm) {
+    c->err = "missing output projection";
+    return bail(FLOVER_E_INVAL);
+  }
+  if (f.dtype != FLOVER_F32) HIPTRY(flk::zero_fill(c->wlm, flk::gemm_tiled_bytes(f.dtype, V, H), st));
+  HIPTRY(flk::retile(f.dtype, lm, V, H, c->wlm, 0, st));
+  if (!gpt) {
+    // cos/sin of pos * theta^(-2i/d), evaluated in double and rounded once to fp32
+    const int half = f.head_dim / 2;
+    std::vector<float> cs((size_t)S * half * 2);
+    for (int p = 0; p < S; ++p)
+      for (int i = 0; i < half; ++i) {
+        const double ang = (double)p * std::pow((double)f.rope_theta, -2.0 * i / f.head_dim);
+        cs[((size_t)p * half + i) * 2] = (float)std::cos(ang);
+        cs[((size_t)p * half + i) * 2 + 1] = (float)std::sin(ang);
+      }
+    HIPTRY(hipMemcpy(c->rope_cs, cs.data(), cs.size() * 4, hipMemcpyHostToDevice));
+  }
+  HIPTRY(hipStreamSynchronize(st));
+  c->slots.assign(f.max_concurrency, Slot());
+  *out_ctx = c;
+  return FLOVER_OK;
+#undef TRY
+#undef HIPTRY
+}
+
+int32_t flover_destroy(flover_ctx* ctx) {
+  if (!ctx) return FLOVER_OK;
+  (void)hipStreamSynchronize(ctx->st);
+  (void)hipHostFree(ctx->h_stage);
+  (void)hipHostFree(ctx->h_tok);
+  (void)hipHostFree(ctx->h_moves);
+  delete ctx;
+  return FLOVER_OK;
+}
+
+int32_t flover_add_request(flover_ctx* c, uint64_t req_id, const int32_t* prompt, int32_t P, int32_t max_new,
+                           int32_t* out_slot) {
+  if (!c || !prompt) return fail(c, FLOVER_E_INVAL, "null argument");
+  const flover_config& f = c->cfg;
+  if (P < 1 || max_new < 1 || P + max_new > f.max_seq) return fail(c, FLOVER_E_INVAL, "prompt_len / max_new_tokens out of range");
+  for (int i = 0; i < P; ++i)
+    if (prompt[i] < 0 || prompt[i] >= f.vocab) return fail(c, FLOVER_E_INVAL, "prompt token out of range");
+  if (known(c, req_id)) return fail(c, FLOVER_E_INVAL, "req_id already waiting or live");
+  Waiting r{req_id, std::vector<int32_t>(prompt, prompt + P), max_new};
+  int slot = -1;
+  if (c->reque.empty()) slot = place(c);
+  if (slot >= 0) {
+    int rc = preprocess(c, slot, r);
+    if (rc != FLOVER_OK) return rc;
+  } else {
+    c->reque.push_back(std::move(r));
+  }
+  if (out_slot) *out_slot = slot;
+  return FLOVER_OK;
+}
+
+int32_t flover_step(flover_ctx* c, flover_step_out* out) {
+  if (!c || !out) return fail(c, FLOVER_E_INVAL, "null argument");
+  c->launches = 0;
+  while (!c->reque.empty()) {        // waiting requests take freed adjacent slots in arrival order
+    int slot = place(c);
+    if (slot < 0) break;
+    int rc = preprocess(c, slot, c->reque.front());
+    if (rc != FLOVER_OK) return rc;
+    c->reque.pop_front();
+  }
+  c->launches = 0;                   // pre-processing is not part of the fused iteration's count
+  std::vector<Row> rows;
+  std::vector<int> live;
+  for (int i = c->lo; i < c->hi; ++i) {   // Update(offset,size): every ready request joins
+    Slot& s = c->slots[i];
+    if (s.state == FLOVER_SLOT_READY) s.state = FLOVER_SLOT_LIVE;
+    if (s.state == FLOVER_SLOT_LIVE) {
+      live.push_back(i);
+      rows.push_back(Row{i, s.next_token, s.len});
+    }
+  }
+  const int n = (int)live.size();
+  if (out->capacity < n) return fail(c, FLOVER_E_INVAL, "flover_step_out.capacity too small");
+  if (c->cfg.shuffle_off)            // holes inside the window are still covered by the kernels (and ignored)
+    for (int i = c->lo; i < c->hi; ++i)
+      if (c->slots[i].state == FLOVER_SLOT_EMPTY || c->slots[i].state == FLOVER_SLOT_DEAD) rows.push_back(Row{i, 0, 0});
+  out->n_live = n;
+  c->last_launches = 0;
+  if (n == 0) return FLOVER_OK;
+  int rc = run_rows(c, rows.data(), (int)rows.size(), true, out->logits);
+  if (rc != FLOVER_OK) return rc;
+  c->last_launches = c->launches;
+  for (int j = 0; j < n; ++j) {
+    Slot& s = c->slots[live[j]];
+    const int t = c->h_tok[j];
+    s.len += 1;
+    s.generated += 1;
+    s.next_token = t;
+    const bool fin = (t == c->cfg.eos_id) || (s.generated >= s.max_new);
+    if (out->req_id) out->req_id[j] = s.req_id;
+    if (out->slot) out->slot[j] = live[j];
+    if (out->token) out->token[j] = t;
+    if (out->finished) out->finished[j] = fin ? 1 : 0;
+    if (fin) s.state = FLOVER_SLOT_DEAD;
+  }
+  return FLOVER_OK;
+}
+
+int32_t flover_mark_finished(flover_ctx* c, uint64_t req_id) {
+  if (!c) return FLOVER_E_INVAL;
+  for (Slot& s : c->slots)
+    if ((s.state == FLOVER_SLOT_LIVE || s.state == FLOVER_SLOT_READY) && s.req_id == req_id) {
+      s.state = FLOVER_SLOT_DEAD;
+      return FLOVER_OK;
+    }
+  return fail(c, FLOVER_E_INVAL, "no such live request");
+}
+
+int32_t flover_set_next_token(flover_ctx* c, uint64_t req_id, int32_t token) {
+  if (!c) return FLOVER_E_INVAL;
+  if (token < 0 || token >= c->cfg.vocab) return fail(c, FLOVER_E_INVAL, "token out of range");
+  for (Slot& s : c->slots)
+    if ((s.state == FLOVER_SLOT_LIVE || s.state == FLOVER_SLOT_READY) && s.req_id == req_id) {
+      s.next_token = token;
+      return FLOVER_OK;
+    }
+  return fail(c, FLOVER_E_INVAL, "no such live request");
+}
+
+int32_t flover_reorder_evict(flover_ctx* c, flover_reorder_out* out) {
+  if (!c || !out) return fail(c, FLOVER_E_INVAL, "null argument");
+  const flover_config& f = c->cfg;
+  const int C = f.max_concurrency;
+  if (out->capacity < C) return fail(c, FLOVER_E_INVAL, "flover_reorder_out.capacity must be >= max_concurrency");
+  int n_ev = 0;
+  for (int i = 0; i < C; ++i)
+    if (c->slots[i].state == FLOVER_SLOT_DEAD) {
+      if (out->evicted_req_id) out->evicted_req_id[n_ev] = c->slots[i].req_id;
+      ++n_ev;
+      c->slots[i] = Slot();
+    }
+  const int old_lo = c->lo, n_old = c->hi - c->lo;
+  int off = 0, min_cost = 0, n1 = 0, n_moves = 0;
+  int64_t bytes = 0;
+  if (!f.shuffle_off) {
+    std::vector<int32_t> arr(std::max(n_old, 1), 0);
+    for (int i = 0; i < n_old; ++i) arr[i] = c->slots[old_lo + i].state != FLOVER_SLOT_EMPTY ? 1 : 0;
+    off = find_window(arr.data(), n_old, &min_cost, &n1);
+    if (n1 == 0) {
+      off = 0;
+      c->lo = c->hi = 0;
+    } else {
+      std::vector<int> holes, outside;
+      for (int i = 0; i < n_old; ++i) {
+        const bool inside = i >= off && i < off + n1;
+        if (inside && !arr[i]) holes.push_back(old_lo + i);
+        if (!inside && arr[i]) outside.push_back(old_lo + i);
+      }
+      n_moves = (int)holes.size();
+      const int row_bytes = f.head_dim * esize(f.dtype);
+      const int nseg = 2 * f.n_layer * f.n_head;
+      int n_dev = 0, blocks = 0;
+      for (int i = 0; i < n_moves; ++i) {
+        const int a = outside[i], b = holes[i];
+        if (out->move_src) out->move_src[i] = a;
+        if (out->move_dst) out->move_dst[i] = b;
+        const int len = c->slots[a].len;
+        bytes += 2LL * len * 2 * f.n_layer * f.hidden * esize(f.dtype);
+        if (len > 0) {
+          const int seg_bytes = len * row_bytes;
+          c->h_moves[n_dev] = make_int4(a, b, seg_bytes, blocks);
+          blocks += nseg * ((seg_bytes + flk::kCompactPiece - 1) / flk::kCompactPiece);
+          ++n_dev;
+        }
+        c->slots[b] = c->slots[a];
+        c->slots[a] = Slot();
+      }
+      if (n_dev > 0) {
+        HIPCHK(c, hipMemcpyAsync(c->d_moves, c->h_moves, (size_t)n_dev * sizeof(int4), hipMemcpyHostToDevice, c->st));
+        HIPCHK(c, flk::compact(c->kv, 2 * f.n_layer, C, f.n_head, c->slot_bytes, c->d_moves, n_dev, blocks,
+                               flk::kCompactPiece, c->st));
+        HIPCHK(c, hipStreamSynchronize(c->st));   // following iterations wait until memory is in order (Section V-D)
+      }
+      c->lo = old_lo + off;
+      c->hi = c->lo + n1;
+    }
+  } else {
+    while (c->lo < c->hi && c->slots[c->lo].state == FLOVER_SLOT_EMPTY) c->lo++;
+    while (c->hi > c->lo && c->slots[c->hi - 1].state == FLOVER_SLOT_EMPTY) c->hi--;
+    if (c->lo == c->hi) c->lo = c->hi = 0;
+    off = c->lo == c->hi ? 0 : c->lo - old_lo;
+  }
+  out->n_evicted = n_ev;
+  out->mem_offset = off;
+  out->new_lo = c->lo;
+  out->new_size = c->hi - c->lo;
+  out->min_cost = min_cost;
+  out->n_moves = n_moves;
+  out->bytes_moved = bytes;
+  return FLOVER_OK;
+}
+
+int32_t flover_get_state(const flover_ctx* c, int32_t* lo_hi_wait, int32_t* state, uint64_t* req_id, int32_t* len,
+                         int32_t* next_token, int32_t* generated) {
+  if (!c) return FLOVER_E_INVAL;
+  if (lo_hi_wait) {
+    lo_hi_wait[0] = c->lo;
+    lo_hi_wait[1] = c->hi;
+    lo_hi_wait[2] = (int)c->reque.size();
+  }
+  for (int i = 0; i < c->cfg.max_concurrency; ++i) {
+    const Slot& s = c->slots[i];
+    if (state) state[i] = s.state;
+    if (req_id) req_id[i] = s.req_id;
+    if (len) len[i] = s.len;
+    if (next_token) next_token[i] = s.next_token;
+    if (generated) generated[i] = s.generated;
+  }
+  return FLOVER_OK;
+}
+
+int32_t flover_get_kv_cache(const flover_ctx* c, void** base, uint64_t* bytes) {
+  if (!c) return FLOVER_E_INVAL;
+  if (base) *base = c->kv;
+  if (bytes) *bytes = c->kv_bytes;
+  return FLOVER_OK;
+}
+
+int32_t flover_last_step_launches(const flover_ctx* c, int32_t* n) {
+  if (!c || !n) return FLOVER_E_INVAL;
+  *n = c->last_launches;
+  return FLOVER_OK;
+}
+
+// --------------------------------------------------------------------- operation-level entry points
+
+int32_t flover_k_find_window(const int32_t* arr, int32_t n, int32_t* mem_offset, int32_t* min_cost, int32_t* non_zero) {
+  if (!arr || n < 0 || !mem_offset || !min_cost || !non_zero) return fail(nullptr, FLOVER_E_INVAL, "bad argument");
+  int mc = 0, nz = 0;
+  *mem_offset = find_window(arr, n, &mc, &nz);
+  *min_cost = mc;
+  *non_zero = nz;
+  return FLOVER_OK;
+}
+
+static size_t attn_ws_layout(int M, int nh, int d, int max_len, size_t* o_items, size_t* o_pml, size_t* o_po) {
+  const int chunks = (max_len + flk::kAttnChunk - 1) / flk::kAttnChunk;
+  const size_t items = (size_t)M * chunks;
+  size_t off = align_up((size_t)4 * M * 4, 256);
+  *o_items = off;
+  off = align_up(off + items * 8, 256);
+  *o_pml = off;
+  off = align_up(off + items * nh * 2 * 4, 256);
+  *o_po = off;
+  off = align_up(off + items * nh * d * 4, 256);
+  return off;
+}
+
+int32_t flover_k_attention_workspace_bytes(int32_t M, int32_t nh, int32_t d, int32_t max_len, uint64_t* out) {
+  if (M < 0 || nh < 1 || (d != 64 && d != 128) || max_len < 1 || !out) return fail(nullptr, FLOVER_E_INVAL, "bad argument");
+  size_t a, b, c2;
+  *out = attn_ws_layout(M, nh, d, max_len, &a, &b, &c2);
+  return FLOVER_OK;
+}
+
+int32_t flover_k_decode_attention(int32_t dtype, const void* q, const void* kcache, const void* vcache,
+                                  const int32_t* slot, const int32_t* len, int32_t M, int32_t C, int32_t nh, int32_t d,
+                                  int32_t S, void* out, void* workspace, uint64_t workspace_bytes, void* stream) {
+  if (dtype < FLOVER_F32 || dtype > FLOVER_BF16 || !q || !kcache || !vcache || !slot || !len || !out || !workspace)
+    return fail(nullptr, FLOVER_E_INVAL, "null or bad argument");
+  if (M < 0 || nh < 4 || nh % 4 || (d != 64 && d != 128) || S < 1 || C < 1) return fail(nullptr, FLOVER_E_INVAL, "bad shape");
+  if (M == 0) return FLOVER_OK;
+  int max_len = 0;
+  for (int i = 0; i < M; ++i) {
+    if (len[i] < 1 || len[i] > S || slot[i] < 0 || slot[i] >= C) return fail(nullptr, FLOVER_E_INVAL, "slot / len out of range");
+    max_len = std::max(max_len, len[i]);
+  }
+  size_t o_items, o_pml, o_po;
+  const size_t need = attn_ws_layout(M, nh, d, max_len, &o_items, &o_pml, &o_po);
+  if (need > workspace_bytes) return fail(nullptr, FLOVER_E_NOMEM, "attention workspace too small");
+  std::vector<int> hs(o_items / 4 + 0);
+  std::vector<int> items;
+  int* h_slot = hs.data();
+  int* h_len = hs.data() + M;
+  int* h_item0 = hs.data() + 2 * M;
+  int* h_nchunk = hs.data() + 3 * M;
+  for (int i = 0; i < M; ++i) {
+    h_slot[i] = slot[i];
+    h_len[i] = len[i];
+    h_item0[i] = (int)items.size() / 2;
+    const int nc = (len[i] + flk::kAttnChunk - 1) / flk::kAttnChunk;
+    h_nchunk[i] = nc;
+    for (int ch = 0; ch < nc; ++ch) {
+      items.push_back(i);
+      items.push_back(ch);
+    }
+  }
+  hipStream_t st = (hipStream_t)stream;
+  char* ws = (char*)workspace;
+  HIPCHK(nullptr, hipMemcpyAsync(ws, hs.data(), (size_t)4 * M * 4, hipMemcpyHostToDevice, st));
+  HIPCHK(nullptr, hipMemcpyAsync(ws + o_items, items.data(), items.size() * 4, hipMemcpyHostToDevice, st));
+  HIPCHK(nullptr, hipStreamSynchronize(st));
+  int* ds = (int*)ws;
+  flk::AttnWork aw{(const int2*)(ws + o_items), ds, ds + M, ds + 2 * M, ds + 3 * M, (float*)(ws + o_pml), (float*)(ws + o_po),
+                   (int)items.size() / 2, flk::kAttnChunk};
+  HIPCHK(nullptr, flk::decode_attention(dtype, d, q, kcache, vcache, aw, M, nh, S, out, st));
+  return FLOVER_OK;
+}
+
+int32_t flover_k_compact_workspace_bytes(int32_t n_moves, uint64_t* out) {
+  if (n_moves < 0 || !out) return fail(nullptr, FLOVER_E_INVAL, "bad argument");
+  *out = align_up((size_t)std::max(n_moves, 1) * sizeof(int4), 256);
+  return FLOVER_OK;
+}
+
+int32_t flover_k_compact(void* cache, int32_t L, int32_t C, int32_t nh, int32_t S, int32_t d, int32_t eb,
+                         const int32_t* src, const int32_t* dst, const int32_t* len, int32_t n_moves, void* workspace,
+                         uint64_t workspace_bytes, void* stream) {
+  if (!cache || L < 1 || C < 1 || nh < 1 || S < 1 || d < 1 || (eb != 2 && eb != 4) || n_moves < 0 || (d * eb) % 16)
+    return fail(nullptr, FLOVER_E_INVAL, "bad argument");
+  if (n_moves == 0) return FLOVER_OK;
+  if (!src || !dst || !len || !workspace) return fail(nullptr, FLOVER_E_INVAL, "null argument");
+  if ((size_t)n_moves * sizeof(int4) > workspace_bytes) return fail(nullptr, FLOVER_E_NOMEM, "compact workspace too small");
+  std::vector<char> is_src(C, 0), is_dst(C, 0);
+  for (int i = 0; i < n_moves; ++i) {
+    if (src[i] < 0 || src[i] >= C || dst[i] < 0 || dst[i] >= C || len[i] < 0 || len[i] > S)
+      return fail(nullptr, FLOVER_E_INVAL, "move out of range");
+    if (is_src[src[i]] || is_dst[dst[i]]) return fail(nullptr, FLOVER_E_INVAL, "slot listed twice");
+    is_src[src[i]] = 1;
+    is_dst[dst[i]] = 1;
+  }
+  for (int i = 0; i < C; ++i)
+    if (is_src[i] && is_dst[i]) return fail(nullptr, FLOVER_E_INVAL, "source and destination sets overlap");
+  std::vector<int4> mv;
+  int blocks = 0;
+  const int nseg = 2 * L * nh;
+  for (int i = 0; i < n_moves; ++i) {
+    if (len[i] == 0) continue;
+    const int seg_bytes = len[i] * d * eb;
+    mv.push_back(make_int4(src[i], dst[i], seg_bytes, blocks));
+    blocks += nseg * ((seg_bytes + flk::kCompactPiece - 1) / flk::kCompactPiece);
+  }
+  if (mv.empty()) return FLOVER_OK;
+  hipStream_t st = (hipStream_t)stream;
+  HIPCHK(nullptr, hipMemcpyAsync(workspace, mv.data(), mv.size() * sizeof(int4), hipMemcpyHostToDevice, st));
+  HIPCHK(nullptr, hipStreamSynchronize(st));
+  HIPCHK(nullptr, flk::compact(cache, 2 * L, C, nh, (size_t)nh * S * d * eb, workspace, (int)mv.size(), blocks,
+                               flk::kCompactPiece, st));
+  return FLOVER_OK;
+}
+
+int32_t flover_k_gemm_tiled_bytes(int32_t dtype, int32_t N, int32_t K, uint64_t* out) {
+  if (dtype < FLOVER_F32 || dtype > FLOVER_BF16 || N < 1 || K < 32 || K % 32 || !out) return fail(nullptr, FLOVER_E_INVAL, "bad argument");
+  *out = flk::gemm_tiled_bytes(dtype, N, K);
+  return FLOVER_OK;
+}
+
+int32_t flover_k_gemm_workspace_bytes(int32_t dtype, int32_t M, int32_t N, int32_t K, uint64_t* out) {
+  if (dtype < FLOVER_F32 || dtype > FLOVER_BF16 || M < 0 || N < 1 || K < 32 || K % 32 || !out) return fail(nullptr, FLOVER_E_INVAL, "bad argument");
+  const flk::GemmPlan p = flk::gemm_plan(dtype, N, K);
+  *out = align_up((size_t)p.S * std::max(M, 1) * N * 4, 256);
+  return FLOVER_OK;
+}
+
+int32_t flover_k_gemm_retile(int32_t dtype, const void* W, int32_t N, int32_t K, void* w_tiled, void* stream) {
+  if (dtype < FLOVER_F32 || dtype > FLOVER_BF16 || !W || !w_tiled || N < 1 || K < 32 || K % 32) return fail(nullptr, FLOVER_E_INVAL, "bad argument");
+  hipStream_t st = (hipStream_t)stream;
+  if (dtype != FLOVER_F32) HIPCHK(nullptr, flk::zero_fill(w_tiled, flk::gemm_tiled_bytes(dtype, N, K), st));
+  HIPCHK(nullptr, flk::retile(dtype, W, N, K, w_tiled, 0, st));
+  return FLOVER_OK;
+}
+
+}  // extern "C"
+
+// y = sum of the split-K slices, in slice order (same order the step's consumers use)
+namespace flk {
+__global__ void slice_sum_kernel(const float* __restrict__ part, int S, size_t stride, float* __restrict__ y, size_t total) {
+  const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+  if (i >= total) return;
+  float v = part[i];
+  for (int s = 1; s < S; ++s) v += part[(size_t)s * stride + i];
+  y[i] = v;
+}
+}  // namespace flk
+
+extern "C" int32_t flover_k_gemm(int32_t dtype, const void* x, const void* w_tiled, int32_t M, int32_t N, int32_t K,
+                                 float* y, void* workspace, uint64_t workspace_bytes, void* stream) {
+  if (dtype < FLOVER_F32 || dtype > FLOVER_BF16 || !x || !w_tiled || !y || !workspace || M < 0 || N < 1 || K < 32 || K % 32)
+    return fail(nullptr, FLOVER_E_INVAL, "bad argument");
+  if (M == 0) return FLOVER_OK;
+  const flk::GemmPlan p = flk::gemm_plan(dtype, N, K);
+  const size_t stride = (size_t)M * N;
+  if ((size_t)p.S * stride * 4 > workspace_bytes) return fail(nullptr, FLOVER_E_NOMEM, "gemm workspace too small");
+  hipStream_t st = (hipStream_t)stream;
+  HIPCHK(nullptr, flk::gemm(dtype, x, w_tiled, M, p, (float*)workspace, stride, N, st));
+  flk::slice_sum_kernel<<<(unsigned)((stride + 255) / 256), 256, 0, st>>>((const float*)workspace, p.S, stride, y, stride);
+  HIPCHK(nullptr, hipGetLastError());
+  return FLOVER_OK;
+}

@@ -1,0 +1,61 @@
+// Host-side launchers of the HIP kernels (internal to the library; the public boundary is include/flover.h).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+namespace flk {
+
+// ---- weight GEMM
+struct GemmPlan {
+  int N, K;
+  int Npad;   // N rounded up to 64 columns (16-bit dtypes)
+  int KB;     // K / 32
+  int S;      // split-K slices, a function of (N, K) only
+  int kbs;    // k-blocks per slice
+};
+GemmPlan gemm_plan(int dtype, int N, int K);
+size_t gemm_tiled_bytes(int dtype, int N, int K);
+// Re-tile W [N][K] into `tiled` starting at output column n_off (multiple of 16) of a possibly larger matrix.
+hipError_t retile(int dtype, const void* W, int N, int K, void* tiled, int n_off, hipStream_t st);
+hipError_t zero_fill(void* p, size_t bytes, hipStream_t st);
+// part[s][m][ldc] (slice stride in floats) = x[M][K] . W^T over slice s of K.
+hipError_t gemm(int dtype, const void* x, const void* w_tiled, int M, const GemmPlan& p, float* part,
+                size_t slice_stride, int ldc, hipStream_t st);
+// rows of x that gemm() may read for M live rows
+inline int gemm_rows_read(int M) { return M <= 16 ? 16 : M <= 32 ? 32 : M <= 64 ? 64 : (M + 127) / 128 * 128; }
+
+// ---- row-wise kernels
+hipError_t embed(int dtype, const void* wte, const void* wpe, const int* tok, const int* pos, float* x, int M, int H,
+                 hipStream_t st);
+hipError_t add_norm(int dtype, bool rms, float* x, const float* part, int S, size_t stride, const void* bias,
+                    const void* g, const void* b, void* h, int M, int H, float eps, hipStream_t st);
+hipError_t qkv_post(int dtype, const float* part, int S, size_t stride, const void* bias, const float* rope_cs,
+                    const int* slot, const int* pos, void* q, void* kcache, void* vcache, int M, int H, int nh, int d,
+                    int Smax, hipStream_t st);
+hipError_t activation(int dtype, bool swiglu, const float* part, int S, size_t stride, const void* bias, void* a, int M,
+                      int F, hipStream_t st);
+hipError_t logits_argmax(const float* part, int S, size_t stride, float* logits, int* tok, int M, int V, hipStream_t st);
+
+// ---- ragged decode attention
+struct AttnWork {          // all device pointers
+  const int2* items;       // [n_items] (row, chunk)
+  const int* row_slot;     // [M]
+  const int* row_len;      // [M] rows of cache attended to (>= 1)
+  const int* row_item0;    // [M] first item of the row
+  const int* row_nchunk;   // [M]
+  float* pml;              // [n_items][nh][2]
+  float* po;               // [n_items][nh][d]
+  int n_items;
+  int chunk;
+};
+constexpr int kAttnChunk = 256;   // positions per wave task; fixed, so chunking depends on a request's own length only
+hipError_t decode_attention(int dtype, int d, const void* q, const void* kc, const void* vc, const AttnWork& w, int M,
+                            int nh, int Smax, void* out, hipStream_t st);
+
+// ---- memory shuffle copy
+constexpr int kCompactPiece = 16384;   // bytes per block
+hipError_t compact(void* cache, int planes, int C, int nh, size_t slot_bytes, const void* moves_dev, int n_moves,
+                   int total_blocks, int piece, hipStream_t st);
+
+}  // namespace flk

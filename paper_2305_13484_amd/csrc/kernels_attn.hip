@@ -1,0 +1,208 @@
+// Ragged masked self-attention of one fused decode iteration: every live row attends over its own request's
+// cached K/V rows [0, len) -- requests arrived at different times, so every row has its own length
+// (temporal fusion, Section V-C; the attention itself sits in Algorithm 2's "...").
+//
+// HBM-bound (about 1 flop per byte, every K/V byte read once), so the kernel is a streamer:
+//   * the cache is [slot][head][pos][d]: one head's rows are contiguous, a wave load instruction fetches
+//     64 lanes x 16 B = 1 KiB of consecutive rows, each row spread over LPR = d*elem/16 adjacent lanes;
+//   * the lane group that holds a row reduces q.k over its LPR lanes with DPP, keeps its own online softmax
+//     state (m, l, o) over the rows it sees (rows r with r % (64/LPR) == group), and the groups are merged
+//     once at the end -- no LDS, no barriers, registers only, occupancy hides latency;
+//   * work is flattened to (row, chunk of CHUNK positions) x head so a launch has thousands of equal-sized
+//     wave tasks however ragged the lengths are; chunking depends on the request's own length only, and a
+//     second tiny kernel merges a row's chunks in chunk order (results never depend on other rows).
+#include "flover_dev.h"
+#include "flover_kernels.h"
+
+namespace flk {
+
+// grid = (n_items, n_head / 4), block = 256: wave w handles head blockIdx.y * 4 + w of item blockIdx.x.
+// items[i] = (row, chunk).  Writes unnormalised partial (m, l, o[D]) per (item, head).
+template <int DT, int D>
+__global__ __launch_bounds__(256) void attn_partial_kernel(const void* __restrict__ q, const void* __restrict__ kc,
+                                                           const void* __restrict__ vc, const int2* __restrict__ items,
+                                                           const int* __restrict__ row_slot,
+                                                           const int* __restrict__ row_len, int nh, int Smax, int chunk,
+                                                           float scale, float* __restrict__ pml, float* __restrict__ po) {
+  constexpr int EB = (DT == DT_F32) ? 4 : 2;
+  constexpr int EPL = 16 / EB;          // elements per lane
+  constexpr int LPR = D / EPL;          // lanes per row
+  constexpr int RPW = 64 / LPR;         // rows per wave load
+  constexpr int U = 4;                  // loads in flight per operand
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int item = blockIdx.x;
+  const int hd = blockIdx.y * 4 + wave;
+  const int row = items[item].x, ch = items[item].y;
+  const int slot = row_slot[row], len = row_len[row];
+  const int j0 = ch * chunk, j1 = min(len, j0 + chunk);
+  const int grp = lane / LPR, li = lane % LPR;
+
+  float qf[EPL];
+  {
+    const u32x4_t qr = *(const u32x4_t*)((const char*)q + ((size_t)(row * nh + hd) * D + li * EPL) * EB);
+    unpack16<DT>(qr, qf);
+#pragma unroll
+    for (int e = 0; e < EPL; ++e) qf[e] *= scale;
+  }
+  const size_t head_off = ((size_t)slot * nh + hd) * Smax * D * EB + (size_t)li * 16;
+  const char* kb = (const char*)kc + head_off;
+  const char* vb = (const char*)vc + head_off;
+
+  float m = -INFINITY, l = 0.f, o[EPL];
+#pragma unroll
+  for (int e = 0; e < EPL; ++e) o[e] = 0.f;
+
+  for (int jb = j0; jb < j1; jb += RPW * U) {
+    u32x4_t kr[U], vr[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const int r = min(jb + u * RPW + grp, j1 - 1);      // clamp: stays inside the request's valid rows
+      kr[u] = __builtin_nontemporal_load((const u32x4_t*)(kb + (size_t)r * D * EB));
+      vr[u] = __builtin_nontemporal_load((const u32x4_t*)(vb + (size_t)r * D * EB));
+    }
+    float s[U];
+    float tmax = -INFINITY;
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      float kf[EPL];
+      unpack16<DT>(kr[u], kf);
+      float d0 = 0.f;
+#pragma unroll
+      for (int e = 0; e < EPL; ++e) d0 = fmaf(qf[e], kf[e], d0);
+      d0 = group_sum<LPR>(d0);
+      s[u] = (jb + u * RPW + grp < j1) ? d0 : -INFINITY;
+      tmax = fmaxf(tmax, s[u]);
+    }
+    const float mn = fmaxf(m, tmax);
+    const float ms = (mn == -INFINITY) ? 0.f : mn;       // a group that has seen no valid row yet
+    const float alpha = __expf(m - ms);                  // m = -inf -> 0
+    l *= alpha;
+#pragma unroll
+    for (int e = 0; e < EPL; ++e) o[e] *= alpha;
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const float p = __expf(s[u] - ms);
+      l += p;
+      float vf[EPL];
+      unpack16<DT>(vr[u], vf);
+#pragma unroll
+      for (int e = 0; e < EPL; ++e) o[e] = fmaf(p, vf[e], o[e]);
+    }
+    m = mn;
+  }
+  // merge the RPW lane groups (lanes with equal li): butterfly over the group index bits
+  if constexpr (RPW > 1) {
+    float mt = m;
+#pragma unroll
+    for (int dlt = LPR; dlt < 64; dlt <<= 1) mt = fmaxf(mt, __shfl_xor(mt, dlt, 64));
+    const float w = (m == -INFINITY) ? 0.f : __expf(m - mt);
+    l *= w;
+#pragma unroll
+    for (int e = 0; e < EPL; ++e) o[e] *= w;
+#pragma unroll
+    for (int dlt = LPR; dlt < 64; dlt <<= 1) {
+      l += __shfl_xor(l, dlt, 64);
+#pragma unroll
+      for (int e = 0; e < EPL; ++e) o[e] += __shfl_xor(o[e], dlt, 64);
+    }
+    m = mt;
+  }
+  if (grp == 0) {
+    const size_t pi = (size_t)item * nh + hd;
+    float* op = po + pi * D + li * EPL;
+#pragma unroll
+    for (int e = 0; e < EPL; ++e) op[e] = o[e];
+    if (li == 0) {
+      pml[pi * 2] = m;
+      pml[pi * 2 + 1] = l;
+    }
+  }
+}
+
+// grid = (M, n_head), block = D: merges a row's chunks in chunk order, normalises, rounds to dtype.
+template <int DT, int D>
+__global__ void attn_merge_kernel(const float* __restrict__ pml, const float* __restrict__ po,
+                                  const int* __restrict__ row_item0, const int* __restrict__ row_nchunk, int nh,
+                                  void* __restrict__ out) {
+  const int row = blockIdx.x, hd = blockIdx.y, i = threadIdx.x;
+  const int it0 = row_item0[row], nc = row_nchunk[row];
+  float mt = -INFINITY;
+  for (int c = 0; c < nc; ++c) mt = fmaxf(mt, pml[((size_t)(it0 + c) * nh + hd) * 2]);
+  float l = 0.f, o = 0.f;
+  for (int c = 0; c < nc; ++c) {
+    const size_t pi = (size_t)(it0 + c) * nh + hd;
+    const float w = __expf(pml[pi * 2] - mt);
+    l += w * pml[pi * 2 + 1];
+    o += w * po[pi * D + i];
+  }
+  st<DT>(out, ((size_t)row * nh + hd) * D + i, o / l);
+}
+
+// ---------------------------------------------------------------- host side
+
+template <int DT, int D>
+static void launch_attn(const void* q, const void* kc, const void* vc, const AttnWork& w, int M, int nh, int Smax,
+                        void* out, hipStream_t st) {
+  const float scale = 1.0f / sqrtf((float)D);
+  attn_partial_kernel<DT, D><<<dim3(w.n_items, nh / 4), 256, 0, st>>>(q, kc, vc, w.items, w.row_slot, w.row_len, nh, Smax,
+                                                                    w.chunk, scale, w.pml, w.po);
+  attn_merge_kernel<DT, D><<<dim3(M, nh), D, 0, st>>>(w.pml, w.po, w.row_item0, w.row_nchunk, nh, out);
+}
+
+hipError_t decode_attention(int dtype, int d, const void* q, const void* kc, const void* vc, const AttnWork& w, int M,
+                            int nh, int Smax, void* out, hipStream_t st) {
+  if (M <= 0 || w.n_items <= 0) return hipSuccess;
+  if (d == 128) {
+    if (dtype == DT_F32) launch_attn<DT_F32, 128>(q, kc, vc, w, M, nh, Smax, out, st);
+    else if (dtype == DT_F16) launch_attn<DT_F16, 128>(q, kc, vc, w, M, nh, Smax, out, st);
+    else launch_attn<DT_BF16, 128>(q, kc, vc, w, M, nh, Smax, out, st);
+  } else {
+    if (dtype == DT_F32) launch_attn<DT_F32, 64>(q, kc, vc, w, M, nh, Smax, out, st);
+    else if (dtype == DT_F16) launch_attn<DT_F16, 64>(q, kc, vc, w, M, nh, Smax, out, st);
+    else launch_attn<DT_BF16, 64>(q, kc, vc, w, M, nh, Smax, out, st);
+  }
+  return hipGetLastError();
+}
+
+// ---------------------------------------------------------------- memory shuffle copy (Section V-D)
+// One launch moves every listed slot: block b -> (move, segment = (layer, K|V, head), piece of PIECE bytes).
+// moves[i] = (src slot, dst slot, bytes per segment = len * d * elem, first block index).
+// Sources lie outside the chosen window and destinations are holes inside it, so the two sets are disjoint and
+// the copies can run in any order.
+__global__ __launch_bounds__(256) void compact_kernel(char* __restrict__ cache, const int4* __restrict__ moves, int n_moves,
+                                                      int nseg_per_slot, int C, size_t slot_bytes, int piece) {
+  // binary search: last move whose first block <= blockIdx.x
+  int lo = 0, hi = n_moves - 1;
+  const int b = blockIdx.x;
+  while (lo < hi) {
+    const int mid = (lo + hi + 1) >> 1;
+    if (moves[mid].w <= b) lo = mid; else hi = mid - 1;
+  }
+  const int4 mv = moves[lo];
+  const int bytes = mv.z;
+  const int ppseg = (bytes + piece - 1) / piece;
+  const int rel = b - mv.w;
+  const int seg = rel / ppseg, pc = rel - seg * ppseg;
+  // segment `seg` = (layer*2 + kv) * nh + head; cache is [(layer*2+kv)][C][nh][S][d]
+  const int nh = nseg_per_slot;             // heads per (layer,kv) plane, passed by the host
+  const int plane = seg / nh, head = seg - plane * nh;
+  const size_t base = ((size_t)plane * C) * slot_bytes;
+  const size_t head_bytes = slot_bytes / nh;
+  const char* src = cache + base + (size_t)mv.x * slot_bytes + (size_t)head * head_bytes + (size_t)pc * piece;
+  char* dst = cache + base + (size_t)mv.y * slot_bytes + (size_t)head * head_bytes + (size_t)pc * piece;
+  const int n = min(piece, bytes - pc * piece);       // multiple of 16
+  for (int off = threadIdx.x * 16; off < n; off += 256 * 16) {
+    const u32x4_t v = __builtin_nontemporal_load((const u32x4_t*)(src + off));
+    __builtin_nontemporal_store(v, (u32x4_t*)(dst + off));
+  }
+}
+
+hipError_t compact(void* cache, int planes, int C, int nh, size_t slot_bytes, const void* moves_dev, int n_moves,
+                   int total_blocks, int piece, hipStream_t st) {
+  if (n_moves <= 0 || total_blocks <= 0) return hipSuccess;
+  (void)planes;
+  compact_kernel<<<total_blocks, 256, 0, st>>>((char*)cache, (const int4*)moves_dev, n_moves, nh, C, slot_bytes, piece);
+  return hipGetLastError();
+}
+
+}  // namespace flk

@@ -1,0 +1,123 @@
+"""Shared drivers for the parity tests: run the HIP path and the CPU oracle in lockstep on one request stream."""
+import numpy as np
+import torch
+
+import flover_synth as synth
+from oracle import oracle as orc
+
+TOL = {synth.DT_F32: 1e-5, synth.DT_F16: 2e-2, synth.DT_BF16: 2e-2}   # max |gpu - ref| / max |ref| per logits row
+
+
+def to_device(weights):
+    return {k: v.cuda() for k, v in weights.items()}
+
+
+class Lockstep:
+    """Feeds the same stream to both sides, compares every step, re-synchronises after a near tie."""
+
+    def __init__(self, cfg, weights, shuffle_off=False):
+        import paper_2305_13484_amd as fl
+        self.cfg = cfg
+        self.gpu = fl.Flover(cfg, to_device(weights), shuffle_off=shuffle_off)
+        self.cpu = orc.OracleServer(cfg, weights, shuffle_off=shuffle_off)
+        self.tol = TOL[cfg.dtype]
+        self.max_err = 0.0
+        self.ties = 0
+        self.tokens = {}
+        self.gpu_logits = {}
+        self.steps = 0
+        self.moves = 0
+        self.compared_rows = 0
+
+    def add(self, req):
+        a = self.gpu.add_request(req.req_id, req.prompt, req.gen_len)
+        b = self.cpu.add_request(req.req_id, req.prompt, req.gen_len)
+        assert a == b, "slot assignment differs"
+
+    def step(self, keep_logits=False):
+        g = self.gpu.step(want_logits=True)
+        c = self.cpu.step(True)
+        assert g.n_live == c.n_live
+        assert np.array_equal(g.req_id, c.req_id) and np.array_equal(g.slot, c.slot)
+        if g.n_live:
+            gl = g.logits.cpu().double().numpy()
+            scale = np.abs(c.logits).max(axis=1)
+            err = np.abs(gl - c.logits).max(axis=1) / scale
+            self.max_err = max(self.max_err, float(err.max()))
+            assert err.max() <= self.tol, "logits error %g > %g at step %d" % (err.max(), self.tol, self.steps)
+            self.compared_rows += g.n_live
+            for j in range(g.n_live):
+                rid = int(g.req_id[j])
+                if keep_logits:
+                    self.gpu_logits.setdefault(rid, []).append(g.logits[j].cpu().clone())
+                if g.token[j] != c.token[j]:
+                    srt = np.sort(c.logits[j])
+                    margin = srt[-1] - srt[-2]
+                    assert margin <= 2 * self.tol * scale[j], "token differs beyond a near tie"
+                    self.ties += 1
+                    if not c.finished[j]:
+                        self.gpu.set_next_token(rid, int(c.token[j]))      # teacher forcing
+                self.tokens.setdefault(rid, []).append(int(c.token[j]))
+            assert np.array_equal(g.finished, c.finished)
+        self.steps += 1
+        return g, c
+
+    def reorder(self):
+        g = self.gpu.reorder_evict()
+        c = self.cpu.reorder_evict()
+        assert np.array_equal(g.evicted, c.evicted)
+        assert (g.mem_offset, g.new_lo, g.new_size, g.min_cost) == (c.mem_offset, c.new_lo, c.new_size, c.min_cost)
+        assert g.moves == c.moves
+        assert g.bytes_moved == c.bytes_moved
+        self.moves += len(g.moves)
+        gs, cs = self.gpu.state(), self.cpu.state()
+        for k in ("lo", "hi", "waiting"):
+            assert gs[k] == cs[k]
+        for k in ("state", "len", "generated"):
+            assert np.array_equal(gs[k], cs[k]), k
+        live = gs["state"] != 0
+        assert np.array_equal(gs["req_id"][live], cs["req_id"][live])
+        return g, c
+
+    def run(self, reqs, keep_logits=False, max_steps=100000):
+        pending = sorted(reqs, key=lambda r: (r.arrival_step, r.req_id))
+        i, done, s = 0, 0, 0
+        live_hist = []
+        while done < len(reqs) and s < max_steps:
+            while i < len(pending) and pending[i].arrival_step <= s:
+                self.add(pending[i])
+                i += 1
+            g, _ = self.step(keep_logits)
+            live_hist.append(g.n_live)
+            done += int(g.finished.sum())
+            self.reorder()
+            s += 1
+        return live_hist
+
+    def close(self):
+        self.gpu.close()
+        self.cpu.close()
+
+
+def gpu_run_stream(cfg, weights_dev, reqs, shuffle_off=False, want_logits=True):
+    """The HIP path alone over a stream; returns per-request token lists and logits (device tensors)."""
+    import paper_2305_13484_amd as fl
+    srv = fl.Flover(cfg, weights_dev, shuffle_off=shuffle_off)
+    pending = sorted(reqs, key=lambda r: (r.arrival_step, r.req_id))
+    toks, logits = {}, {}
+    i, done, s = 0, 0, 0
+    while done < len(reqs):
+        while i < len(pending) and pending[i].arrival_step <= s:
+            srv.add_request(pending[i].req_id, pending[i].prompt, pending[i].gen_len)
+            i += 1
+        out = srv.step(want_logits)
+        for j in range(out.n_live):
+            rid = int(out.req_id[j])
+            toks.setdefault(rid, []).append(int(out.token[j]))
+            if want_logits:
+                logits.setdefault(rid, []).append(out.logits[j].clone())
+        done += int(out.finished.sum())
+        srv.reorder_evict()
+        s += 1
+    srv.close()
+    return toks, logits

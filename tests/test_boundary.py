@@ -1,0 +1,54 @@
+"""The C-ABI library loads and exports every symbol include/flover.h declares (no compute without a GPU)."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+import paper_2305_13484_amd as fl
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def declared_symbols():
+    text = open(os.path.join(ROOT, "include", "flover.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(flover_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    lib = fl.load_library()
+    names = declared_symbols()
+    assert len(names) >= 20
+    for n in names:
+        assert hasattr(lib, n), n
+    assert sorted(fl.EXPORTED_SYMBOLS) == names
+
+
+def test_no_extern_c_torch_types_in_header():
+    text = open(os.path.join(ROOT, "include", "flover.h")).read()
+    assert "torch" not in text and "at::" not in text and "std::" not in text
+
+
+def test_host_only_entry_point_and_argument_errors():
+    lib = fl.load_library()
+    assert fl.k_find_window([0, 1, 1, 0, 1, 1]) == (1, 1, 4)
+    assert fl.k_find_window([]) == (0, 0, 0)
+    n = ctypes.c_uint64()
+    assert lib.flover_k_gemm_tiled_bytes(2, 100, 64, ctypes.byref(n)) == 0 and n.value == 128 * 64 * 2
+    assert lib.flover_k_gemm_tiled_bytes(2, 100, 48, ctypes.byref(n)) == -1          # K not a multiple of 32
+    assert b"bad argument" in lib.flover_last_error(None)
+    assert lib.flover_k_attention_workspace_bytes(4, 8, 96, 100, ctypes.byref(n)) == -1   # head_dim 96 unsupported
+    from paper_2305_13484_amd.binding import _Config
+    cfg = _Config(1, 2, 2, 512, 4, 128, 1376, 2000, 160, 16, -1, 0, 1e-6, 10000.0, None, None, 0)
+    assert lib.flover_query_arena_bytes(ctypes.byref(cfg), ctypes.byref(n)) == 0 and n.value > 0
+    cfg.hidden = 500
+    assert lib.flover_query_arena_bytes(ctypes.byref(cfg), ctypes.byref(n)) == -1
+
+
+def test_host_window_search_matches_oracle():
+    from oracle import oracle as orc
+    import flover_synth as synth
+    for arr in synth.occupancy_arrays(11, 400, 80):
+        assert fl.k_find_window(arr) == orc.find_window(arr)

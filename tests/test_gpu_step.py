@@ -1,0 +1,190 @@
+"""Parity of the fused decode stream (flover_add_request / flover_step / flover_reorder_evict through the C ABI)
+against the CPU oracle, step by step, on seeded synthetic request streams."""
+import dataclasses
+
+import numpy as np
+import pytest
+import torch
+
+import flover_synth as synth
+from oracle import oracle as orc
+from helpers import Lockstep, gpu_run_stream, to_device, TOL
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module", autouse=True)
+def _need_gpu():
+    assert torch.cuda.is_available(), "these tests need the MI355X"
+    import paper_2305_13484_amd as m
+    m.load_library()
+
+
+def test_config1_tiny_gpt_fp32_full_stream():
+    """Config 1: 8 requests, arrival U{0..20}, prompts 8-32, generation 16-64, every step compared."""
+    cfg = synth.tiny_gpt()
+    w = synth.make_weights(cfg, 1)
+    reqs = synth.stream_c1(1, cfg.V)
+    ls = Lockstep(cfg, w)
+    live = ls.run(reqs)
+    print("c1: steps", ls.steps, "max live", max(live), "max rel err", ls.max_err, "ties", ls.ties, "moves", ls.moves)
+    assert ls.ties == 0                      # fp32: greedy ids bit-exact
+    assert ls.max_err <= 1e-5
+    assert max(live) >= 4
+    for r in reqs:
+        assert len(ls.tokens[r.req_id]) == r.gen_len
+    ls.close()
+
+
+@pytest.mark.parametrize("make", [lambda: synth.tiny_llama(synth.DT_F32), lambda: synth.small_gpt16(synth.DT_F16),
+                                  lambda: synth.small_llama16(synth.DT_BF16), lambda: synth.tiny_llama(synth.DT_BF16)])
+def test_small_models_all_dtypes(make):
+    cfg = make()
+    print(cfg.name, flush=True)
+    w = synth.make_weights(cfg, 3)
+    reqs = synth.stream_small(4, cfg.V, n=10, arrive_hi=8, p_lo=1, p_hi=40, g_lo=2, g_hi=24)
+    ls = Lockstep(cfg, w)
+    live = ls.run(reqs)
+    print(cfg.name, "steps", ls.steps, "max live", max(live), "max rel err", ls.max_err, "ties", ls.ties, "moves", ls.moves)
+    assert ls.max_err <= TOL[cfg.dtype]
+    assert ls.ties <= max(1, ls.compared_rows // 50)
+    assert ls.moves > 0                      # the stream really exercised the shuffle
+    ls.close()
+
+
+def test_capacity_wait_eos_and_forced_finish():
+    cfg = dataclasses.replace(synth.tiny_gpt(), C=3)
+    w = synth.make_weights(cfg, 5)
+    # pick an EOS id the model really emits early for one request
+    t0, _ = orc.solo_decode(cfg, w, [7, 8, 9], 10, want_logits=False)
+    cfg = dataclasses.replace(cfg, eos_id=int(t0[3]))
+    reqs = synth.stream_small(6, cfg.V, n=7, arrive_hi=1, p_lo=2, p_hi=6, g_lo=3, g_hi=9)
+    reqs.append(synth.Request(100, 0, np.asarray([7, 8, 9], np.int32), 10))
+    ls = Lockstep(cfg, w)
+    pending = sorted(reqs, key=lambda r: (r.arrival_step, r.req_id))
+    i = done = s = 0
+    forced = False
+    while done < len(reqs):
+        while i < len(pending) and pending[i].arrival_step <= s:
+            ls.add(pending[i])
+            i += 1
+        g, c = ls.step()
+        assert g.n_live <= 3
+        done += int(g.finished.sum())
+        if not forced and g.n_live == 3 and not g.finished[1]:
+            ls.gpu.mark_finished(int(g.req_id[1]))          # forced finish at a chosen index (benchmark hook)
+            ls.cpu.mark_finished(int(c.req_id[1]))
+            forced = True
+            done += 1
+        ls.reorder()
+        s += 1
+    assert forced and len(ls.tokens[100]) <= 10
+    ls.close()
+
+
+def test_fused_equals_alone_on_the_gpu_bitwise():
+    """The HIP path's own invariant: a request's logits do not depend on which other requests share the step."""
+    cfg = synth.small_llama16(synth.DT_BF16)
+    w = to_device(synth.make_weights(cfg, 8))
+    reqs = synth.stream_small(8, cfg.V, n=7, arrive_hi=5, p_lo=1, p_hi=30, g_lo=3, g_hi=14)
+    toks, logits = gpu_run_stream(cfg, w, reqs)
+    for r in reqs:
+        solo = [synth.Request(r.req_id, 0, r.prompt, r.gen_len)]
+        t1, l1 = gpu_run_stream(cfg, w, solo)
+        assert t1[r.req_id] == toks[r.req_id]
+        assert torch.equal(torch.stack(l1[r.req_id]), torch.stack(logits[r.req_id]))
+    # and shuffle on == off
+    toks_off, logits_off = gpu_run_stream(cfg, w, reqs, shuffle_off=True)
+    for r in reqs:
+        assert toks_off[r.req_id] == toks[r.req_id]
+        assert torch.equal(torch.stack(logits_off[r.req_id]), torch.stack(logits[r.req_id]))
+
+
+def test_shuffle_off_variant_matches_oracle():
+    cfg = synth.tiny_gpt()
+    w = synth.make_weights(cfg, 2)
+    reqs = synth.stream_small(12, cfg.V, n=9, arrive_hi=6, p_lo=2, p_hi=10, g_lo=2, g_hi=12)
+    ls = Lockstep(cfg, w, shuffle_off=True)
+    ls.run(reqs)
+    assert ls.moves == 0 and ls.ties == 0
+    ls.close()
+
+
+def test_reorder_moves_kv_as_a_pure_permutation_and_launch_count_is_constant():
+    import paper_2305_13484_amd as fl
+    cfg = synth.small_llama16(synth.DT_BF16)
+    w = to_device(synth.make_weights(cfg, 9))
+    srv = fl.Flover(cfg, w)
+    rng = np.random.default_rng(5)
+    for rid in range(12):
+        srv.add_request(rid, rng.integers(0, cfg.V, size=int(rng.integers(1, 50))), 40)
+    launches = set()
+    for _ in range(3):
+        out = srv.step()
+        launches.add(srv.last_step_launches())
+        srv.reorder_evict()
+    for rid in (0, 3, 4, 9, 11):
+        srv.mark_finished(rid)
+    st = srv.state()
+    kv = srv.kv_cache()
+    before = {}
+    for s in range(cfg.C):
+        if st["state"][s] == 2:
+            before[int(st["req_id"][s])] = kv[:, :, s, :, :int(st["len"][s])].clone()
+    rr = srv.reorder_evict()
+    assert sorted(rr.evicted.tolist()) == [0, 3, 4, 9, 11]
+    assert len(rr.moves) == rr.min_cost > 0
+    st2 = srv.state()
+    assert st2["hi"] - st2["lo"] == 7
+    for s in range(cfg.C):
+        if st2["state"][s] == 2:
+            rid = int(st2["req_id"][s])
+            assert torch.equal(kv[:, :, s, :, :int(st2["len"][s])], before[rid])
+            before.pop(rid)
+    assert not before
+    # Table I: launches per iteration do not depend on the number of live requests
+    out = srv.step()
+    assert out.n_live == 7
+    launches.add(srv.last_step_launches())
+    assert len(launches) == 1
+    srv.close()
+
+
+def test_llama7b_shape_reduced_depth():
+    """The 7B layer shape (hidden 4096, 32 heads, FFN 11008, vocab 32000, bf16) at 2 layers: the kernels run in the
+    launch configuration of the benchmark; a few requests decoded against the oracle."""
+    cfg = synth.llama_7b(L=2, C=8, S=96)
+    print(cfg.name, flush=True)
+    w = synth.make_weights(cfg, 12)
+    reqs = synth.stream_small(3, cfg.V, n=5, arrive_hi=2, p_lo=2, p_hi=12, g_lo=2, g_hi=5)
+    ls = Lockstep(cfg, w)
+    ls.run(reqs)
+    print("7b-shape: steps", ls.steps, "max rel err", ls.max_err, "ties", ls.ties)
+    assert ls.max_err <= 2e-2
+    ls.close()
+
+
+def test_errors_are_reported_not_thrown_across_the_abi():
+    import paper_2305_13484_amd as fl
+    cfg = synth.tiny_gpt()
+    w = to_device(synth.make_weights(cfg, 1))
+    srv = fl.Flover(cfg, w)
+    with pytest.raises(fl.FloverError):
+        srv.add_request(1, [], 4)
+    with pytest.raises(fl.FloverError):
+        srv.add_request(1, [1, 2], cfg.S)            # prompt + generation exceeds the slot
+    with pytest.raises(fl.FloverError):
+        srv.add_request(1, [cfg.V], 4)               # token out of range
+    srv.add_request(1, [1, 2], 4)
+    with pytest.raises(fl.FloverError):
+        srv.add_request(1, [3], 4)                   # duplicate id
+    out = srv.step()
+    assert out.n_live == 1
+    srv.close()
+    bad = {k: v for k, v in w.items() if k != "wo"}
+    with pytest.raises(fl.FloverError):
+        fl.Flover(cfg, bad)
+    empty = fl.Flover(cfg, w)
+    assert empty.step().n_live == 0                  # nothing live is not an error
+    assert empty.reorder_evict().moves == []
+    empty.close()
