@@ -693,10 +693,10 @@ int32_t flover_k_attention_workspace_bytes(int32_t M, int32_t nh, int32_t d, int
 int32_t flover_k_decode_attention(int32_t dtype, const void* q, const void* kcache, const void* vcache,
                                   const int32_t* slot, const int32_t* len, int32_t M, int32_t C, int32_t nh, int32_t d,
                                   int32_t S, void* out, void* workspace, uint64_t workspace_bytes, void* stream) {
-  if (dtype < FLOVER_F32 || dtype > FLOVER_BF16 || !q || !kcache || !vcache || !slot || !len || !out || !workspace)
-    return fail(nullptr, FLOVER_E_INVAL, "null or bad argument");
+  if (dtype < FLOVER_F32 || dtype > FLOVER_BF16) return fail(nullptr, FLOVER_E_INVAL, "bad dtype");
   if (M < 0 || nh < 4 || nh % 4 || (d != 64 && d != 128) || S < 1 || C < 1) return fail(nullptr, FLOVER_E_INVAL, "bad shape");
   if (M == 0) return FLOVER_OK;
+  if (!q || !kcache || !vcache || !slot || !len || !out || !workspace) return fail(nullptr, FLOVER_E_INVAL, "null argument");
   int max_len = 0;
   for (int i = 0; i < M; ++i) {
     if (len[i] < 1 || len[i] > S || slot[i] < 0 || slot[i] >= C) return fail(nullptr, FLOVER_E_INVAL, "slot / len out of range");
