@@ -160,6 +160,16 @@ int32_t flover_get_kv_cache(const flover_ctx* ctx, void** base, uint64_t* bytes)
  * requests are live). */
 int32_t flover_last_step_launches(const flover_ctx* ctx, int32_t* n);
 
+/* Kernel timing with HIP events on the context's stream (measurement aid, not in the paper).
+ * level 0 = off, 1 = the attention streaming kernel of every layer, 2 = also every weight GEMM; the shuffle copy is
+ * timed at levels 1 and 2.  Setting the level clears the totals.  flover_get_profile returns, for one kind, the summed
+ * duration (ms), the number of launches and the summed algorithmic bytes of those launches: for attention the K and V
+ * rows [0,len) of every row; for a GEMM the weight matrix; for the shuffle copy bytes read + written. */
+enum { FLOVER_PROF_ATTENTION = 0, FLOVER_PROF_GEMM_QKV = 1, FLOVER_PROF_GEMM_OUT = 2, FLOVER_PROF_GEMM_FF1 = 3,
+       FLOVER_PROF_GEMM_FF2 = 4, FLOVER_PROF_GEMM_LM = 5, FLOVER_PROF_COMPACT = 6, FLOVER_PROF_KINDS = 7 };
+int32_t flover_set_profile(flover_ctx* ctx, int32_t level);
+int32_t flover_get_profile(const flover_ctx* ctx, int32_t kind, double* ms, int64_t* launches, int64_t* bytes);
+
 /* ------------------------------------------------------------------ operation-level entry points
  * The same kernels the step uses, callable on caller-owned buffers (micro-benchmarks, unit parity).
  * All enqueue on `stream` and return without waiting unless stated. */
@@ -195,7 +205,8 @@ int32_t flover_k_compact(void* cache, int32_t L, int32_t C, int32_t n_head, int3
  * dtypes).  W is first re-tiled into `w_tiled` (flover_k_gemm_tiled_bytes bytes, [device]) by flover_k_gemm_retile;
  * flover_k_gemm then streams the tiled copy.  x [device][Mpad][K]: rows up to M rounded up to a multiple of 128 must be
  * readable (their contents do not matter);
- * workspace holds the split-K partial sums.  K % 32 == 0. */
+ * workspace holds the split-K partial sums.  K % 32 == 0.  y == NULL leaves the result as partial sums in the
+ * workspace (timing the streaming kernel alone). */
 int32_t flover_k_gemm_tiled_bytes(int32_t dtype, int32_t N, int32_t K, uint64_t* out);
 int32_t flover_k_gemm_workspace_bytes(int32_t dtype, int32_t M, int32_t N, int32_t K, uint64_t* out);
 int32_t flover_k_gemm_retile(int32_t dtype, const void* W, int32_t N, int32_t K, void* w_tiled, void* stream);

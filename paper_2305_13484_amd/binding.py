@@ -18,7 +18,7 @@ _LIB_PATH = os.path.join(_HERE, "libflover.so")
 EXPORTED_SYMBOLS = [
     "flover_query_arena_bytes", "flover_init", "flover_destroy", "flover_last_error", "flover_add_request",
     "flover_step", "flover_reorder_evict", "flover_mark_finished", "flover_set_next_token", "flover_get_state",
-    "flover_get_kv_cache", "flover_last_step_launches", "flover_k_find_window", "flover_k_attention_workspace_bytes",
+    "flover_get_kv_cache", "flover_last_step_launches", "flover_set_profile", "flover_get_profile", "flover_k_find_window", "flover_k_attention_workspace_bytes",
     "flover_k_decode_attention", "flover_k_compact_workspace_bytes", "flover_k_compact", "flover_k_gemm_tiled_bytes",
     "flover_k_gemm_workspace_bytes", "flover_k_gemm_retile", "flover_k_gemm",
 ]
@@ -84,6 +84,9 @@ def load_library():
     L.flover_get_state.argtypes = [C.c_void_p] + [C.c_void_p] * 6
     L.flover_get_kv_cache.argtypes = [C.c_void_p, C.POINTER(C.c_void_p), C.POINTER(C.c_uint64)]
     L.flover_last_step_launches.argtypes = [C.c_void_p, C.POINTER(C.c_int32)]
+    L.flover_set_profile.argtypes = [C.c_void_p, C.c_int32]
+    L.flover_get_profile.argtypes = [C.c_void_p, C.c_int32, C.POINTER(C.c_double), C.POINTER(C.c_int64),
+                                     C.POINTER(C.c_int64)]
     L.flover_k_find_window.argtypes = [C.c_void_p, C.c_int32] + [C.POINTER(C.c_int32)] * 3
     L.flover_k_attention_workspace_bytes.argtypes = [C.c_int32] * 4 + [C.POINTER(C.c_uint64)]
     L.flover_k_decode_attention.argtypes = [C.c_int32] + [C.c_void_p] * 5 + [C.c_int32] * 5 + \
@@ -212,6 +215,19 @@ class Flover:
         n = C.c_int32(0)
         _check(load_library().flover_last_step_launches(self._ctx, C.byref(n)), self._ctx)
         return n.value
+
+    PROF_KINDS = ["attention", "gemm_qkv", "gemm_out", "gemm_ff1", "gemm_ff2", "gemm_lm", "compact"]
+
+    def set_profile(self, level: int):
+        _check(load_library().flover_set_profile(self._ctx, level), self._ctx)
+
+    def get_profile(self):
+        out = {}
+        for k, name in enumerate(self.PROF_KINDS):
+            ms, n, b = C.c_double(), C.c_int64(), C.c_int64()
+            _check(load_library().flover_get_profile(self._ctx, k, C.byref(ms), C.byref(n), C.byref(b)), self._ctx)
+            out[name] = {"ms": ms.value, "launches": n.value, "bytes": b.value}
+        return out
 
     def state(self):
         Cn = self.cfg.C

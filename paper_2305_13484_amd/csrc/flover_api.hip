@@ -76,7 +76,6 @@ struct flover_ctx {
   float* x;
   void *h, *q, *att, *act;
   float* part;
-  float* logits;
   int* tok_out;
   int* d_stage;   // tok | pos | slot | len | item0 | nchunk | items(2x)
   float *pml, *po;
@@ -92,6 +91,15 @@ struct flover_ctx {
   int lo = 0, hi = 0;          // window [lo,hi): buffer offset and size in slots
   int last_launches = 0;
   int launches = 0;
+  // optional timing of the kernels with HIP events on the library's stream
+  int profile = 0;                         // 0 off, 1 attention only, 2 every GEMM too
+  bool in_step = false;                    // only the fused iteration is timed, not pre-processing
+  std::vector<hipEvent_t> ev;              // pairs, reused every pass
+  std::vector<int> ev_kind;                // kind of each recorded pair in this pass
+  std::vector<int64_t> ev_bytes;           // algorithmic bytes of each recorded pair
+  double prof_ms[FLOVER_PROF_KINDS] = {0};
+  int64_t prof_launches[FLOVER_PROF_KINDS] = {0};
+  int64_t prof_bytes[FLOVER_PROF_KINDS] = {0};
 };
 
 namespace {
@@ -170,9 +178,8 @@ size_t layout(flover_ctx* c, char* base) {
   c->att = b.take((size_t)R * H * e);
   c->act = b.take((size_t)R * F * e);
   size_t pw = 0;
-  for (const flk::GemmPlan* p : {&c->p_qkv, &c->p_o, &c->p_1, &c->p_2, &c->p_lm}) pw = std::max(pw, (size_t)p->S * p->N);
+  for (const flk::GemmPlan* p : {&c->p_qkv, &c->p_o, &c->p_1, &c->p_2, &c->p_lm}) pw = std::max(pw, (size_t)p->S * p->ldc);
   c->part = (float*)b.take(pw * R * 4);
-  c->logits = (float*)b.take((size_t)R * V * 4);
   c->tok_out = (int*)b.take((size_t)R * 4);
   c->stage_ints = (size_t)6 * R + (size_t)2 * c->max_items;
   c->d_stage = (int*)b.take(c->stage_ints * 4);
@@ -194,6 +201,41 @@ int place(flover_ctx* c) {
   return -1;
 }
 
+// Event pair for a profiled launch; returns the pair index or -1 when profiling of `kind` is off.
+int prof_begin(flover_ctx* c, int kind, int64_t bytes) {
+  if (c->profile == 0 || (c->profile == 1 && kind != FLOVER_PROF_ATTENTION && kind != FLOVER_PROF_COMPACT)) return -1;
+  if (!c->in_step && kind != FLOVER_PROF_COMPACT) return -1;
+  const size_t i = c->ev_kind.size();
+  while (c->ev.size() < 2 * (i + 1)) {
+    hipEvent_t e;
+    if (hipEventCreate(&e) != hipSuccess) return -1;
+    c->ev.push_back(e);
+  }
+  c->ev_kind.push_back(kind);
+  c->ev_bytes.push_back(bytes);
+  return (int)i;
+}
+void prof_collect(flover_ctx* c) {   // after the stream has been synchronised
+  for (size_t i = 0; i < c->ev_kind.size(); ++i) {
+    float ms = 0.f;
+    if (hipEventElapsedTime(&ms, c->ev[2 * i], c->ev[2 * i + 1]) == hipSuccess) {
+      c->prof_ms[c->ev_kind[i]] += ms;
+      c->prof_launches[c->ev_kind[i]] += 1;
+      c->prof_bytes[c->ev_kind[i]] += c->ev_bytes[i];
+    }
+  }
+  c->ev_kind.clear();
+  c->ev_bytes.clear();
+}
+hipError_t timed_gemm(flover_ctx* c, int kind, const void* x, const void* w, int n, const flk::GemmPlan& p, size_t ss) {
+  const int64_t bytes = (int64_t)flk::gemm_tiled_bytes(c->cfg.dtype, p.N, p.K);
+  const int pi = prof_begin(c, kind, bytes);
+  if (pi >= 0) (void)hipEventRecord(c->ev[2 * pi], c->st);
+  hipError_t e = flk::gemm(c->cfg.dtype, x, w, n, p, c->part, ss, c->st);
+  if (pi >= 0) (void)hipEventRecord(c->ev[2 * pi + 1], c->st);
+  return e;
+}
+
 // One pass of the decoder over n rows: a single launch per operation covers all of them.
 // With want_tokens the final norm, output projection and argmax run and tok_out (device) holds the choices.
 int run_rows(flover_ctx* c, const Row* rows, int n, bool want_tokens, float* logits_out) {
@@ -207,7 +249,9 @@ int run_rows(flover_ctx* c, const Row* rows, int n, bool want_tokens, float* log
   int *tok = hs, *pos = hs + R, *slot = hs + 2 * R, *len = hs + 3 * R, *item0 = hs + 4 * R, *nchunk = hs + 5 * R;
   int* items = hs + 6 * R;
   int n_items = 0;
+  int64_t attn_bytes = 0;   // K and V rows [0,len) of every row, all heads: what one attention launch has to read
   for (int i = 0; i < n; ++i) {
+    attn_bytes += (int64_t)(rows[i].pos + 1) * 2 * H * esize(f.dtype);
     tok[i] = rows[i].tok;
     pos[i] = rows[i].pos;
     slot[i] = rows[i].slot;
@@ -228,36 +272,43 @@ int run_rows(flover_ctx* c, const Row* rows, int n, bool want_tokens, float* log
   flk::AttnWork aw{(const int2*)(ds + 6 * R), d_slot, d_len, d_item0, d_nchunk, c->pml, c->po, n_items, flk::kAttnChunk};
 
   int launches = 0;
-  const size_t ss_qkv = (size_t)n * 3 * H, ss_h = (size_t)n * H, ss_1 = (size_t)n * c->p_1.N, ss_v = (size_t)n * V;
+  const size_t ss_qkv = (size_t)n * c->p_qkv.ldc, ss_h = (size_t)n * c->p_o.ldc, ss_1 = (size_t)n * c->p_1.ldc,
+               ss_v = (size_t)n * c->p_lm.ldc;
   HIPCHK(c, flk::embed(f.dtype, c->wte, c->wpe, d_tok, d_pos, c->x, n, H, st));
   ++launches;
   for (int l = 0; l < L; ++l) {
     const LayerW& w = c->lw[l];
     const bool first = l == 0;
-    HIPCHK(c, flk::add_norm(f.dtype, !gpt, c->x, first ? nullptr : c->part, c->p_2.S, ss_h, first ? nullptr : c->lw[l - 1].b2,
+    HIPCHK(c, flk::add_norm(f.dtype, !gpt, c->x, first ? nullptr : c->part, c->p_2.S, ss_h, c->p_2.ldc,
+                            first ? nullptr : c->lw[l - 1].b2,
                             w.ln1_g, w.ln1_b, c->h, n, H, f.norm_eps, st));
-    HIPCHK(c, flk::gemm(f.dtype, c->h, w.wqkv, n, c->p_qkv, c->part, ss_qkv, 3 * H, st));
+    HIPCHK(c, timed_gemm(c, FLOVER_PROF_GEMM_QKV, c->h, w.wqkv, n, c->p_qkv, ss_qkv));
     char* kl = c->kv + (size_t)(2 * l) * c->plane_bytes;
     char* vl = kl + c->plane_bytes;
-    HIPCHK(c, flk::qkv_post(f.dtype, c->part, c->p_qkv.S, ss_qkv, w.bqkv, c->rope_cs, d_slot, d_pos, c->q, kl, vl, n, H, nh,
+    HIPCHK(c, flk::qkv_post(f.dtype, c->part, c->p_qkv.S, ss_qkv, c->p_qkv.ldc, w.bqkv, c->rope_cs, d_slot, d_pos, c->q, kl, vl, n, H, nh,
                             d, f.max_seq, st));
-    HIPCHK(c, flk::decode_attention(f.dtype, d, c->q, kl, vl, aw, n, nh, f.max_seq, c->att, st));
-    HIPCHK(c, flk::gemm(f.dtype, c->att, w.wo, n, c->p_o, c->part, ss_h, H, st));
-    HIPCHK(c, flk::add_norm(f.dtype, !gpt, c->x, c->part, c->p_o.S, ss_h, w.bo, w.ln2_g, w.ln2_b, c->h, n, H, f.norm_eps, st));
-    HIPCHK(c, flk::gemm(f.dtype, c->h, w.w1, n, c->p_1, c->part, ss_1, c->p_1.N, st));
-    HIPCHK(c, flk::activation(f.dtype, !gpt, c->part, c->p_1.S, ss_1, w.b1, c->act, n, F, st));
-    HIPCHK(c, flk::gemm(f.dtype, c->act, w.w2, n, c->p_2, c->part, ss_h, H, st));
+    {
+      const int pi = prof_begin(c, FLOVER_PROF_ATTENTION, attn_bytes);
+      HIPCHK(c, flk::decode_attention(f.dtype, d, c->q, kl, vl, aw, n, nh, f.max_seq, c->att, st,
+                                      pi >= 0 ? c->ev[2 * pi] : nullptr, pi >= 0 ? c->ev[2 * pi + 1] : nullptr));
+    }
+    HIPCHK(c, timed_gemm(c, FLOVER_PROF_GEMM_OUT, c->att, w.wo, n, c->p_o, ss_h));
+    HIPCHK(c, flk::add_norm(f.dtype, !gpt, c->x, c->part, c->p_o.S, ss_h, c->p_o.ldc, w.bo, w.ln2_g, w.ln2_b, c->h, n, H, f.norm_eps, st));
+    HIPCHK(c, timed_gemm(c, FLOVER_PROF_GEMM_FF1, c->h, w.w1, n, c->p_1, ss_1));
+    HIPCHK(c, flk::activation(f.dtype, !gpt, c->part, c->p_1.S, ss_1, c->p_1.ldc, w.b1, c->act, n, F, st));
+    HIPCHK(c, timed_gemm(c, FLOVER_PROF_GEMM_FF2, c->act, w.w2, n, c->p_2, ss_h));
     launches += 10;
   }
   if (want_tokens) {
-    HIPCHK(c, flk::add_norm(f.dtype, !gpt, c->x, c->part, c->p_2.S, ss_h, c->lw[L - 1].b2, c->lnf_g, c->lnf_b, c->h, n, H,
+    HIPCHK(c, flk::add_norm(f.dtype, !gpt, c->x, c->part, c->p_2.S, ss_h, c->p_2.ldc, c->lw[L - 1].b2, c->lnf_g, c->lnf_b, c->h, n, H,
                             f.norm_eps, st));
-    HIPCHK(c, flk::gemm(f.dtype, c->h, c->wlm, n, c->p_lm, c->part, ss_v, V, st));
-    HIPCHK(c, flk::logits_argmax(c->part, c->p_lm.S, ss_v, logits_out, c->tok_out, n, V, st));
+    HIPCHK(c, timed_gemm(c, FLOVER_PROF_GEMM_LM, c->h, c->wlm, n, c->p_lm, ss_v));
+    HIPCHK(c, flk::logits_argmax(c->part, c->p_lm.S, ss_v, c->p_lm.ldc, logits_out, c->tok_out, n, V, st));
     HIPCHK(c, hipMemcpyAsync(c->h_tok, c->tok_out, (size_t)n * 4, hipMemcpyDeviceToHost, st));
     launches += 3;
   }
   HIPCHK(c, hipStreamSynchronize(st));   // staging buffers are reused by the next call
+  prof_collect(c);
   c->launches += launches;
   return FLOVER_OK;
 }
@@ -460,6 +511,7 @@ int32_t flover_destroy(flover_ctx* ctx) {
   (void)hipHostFree(ctx->h_stage);
   (void)hipHostFree(ctx->h_tok);
   (void)hipHostFree(ctx->h_moves);
+  for (hipEvent_t e : ctx->ev) (void)hipEventDestroy(e);
   delete ctx;
   return FLOVER_OK;
 }
@@ -514,7 +566,9 @@ int32_t flover_step(flover_ctx* c, flover_step_out* out) {
   out->n_live = n;
   c->last_launches = 0;
   if (n == 0) return FLOVER_OK;
+  c->in_step = true;
   int rc = run_rows(c, rows.data(), (int)rows.size(), true, out->logits);
+  c->in_step = false;
   if (rc != FLOVER_OK) return rc;
   c->last_launches = c->launches;
   for (int j = 0; j < n; ++j) {
@@ -604,9 +658,13 @@ int32_t flover_reorder_evict(flover_ctx* c, flover_reorder_out* out) {
       }
       if (n_dev > 0) {
         HIPCHK(c, hipMemcpyAsync(c->d_moves, c->h_moves, (size_t)n_dev * sizeof(int4), hipMemcpyHostToDevice, c->st));
+        const int pi = prof_begin(c, FLOVER_PROF_COMPACT, bytes);
+        if (pi >= 0) (void)hipEventRecord(c->ev[2 * pi], c->st);
         HIPCHK(c, flk::compact(c->kv, 2 * f.n_layer, C, f.n_head, c->slot_bytes, c->d_moves, n_dev, blocks,
                                flk::kCompactPiece, c->st));
+        if (pi >= 0) (void)hipEventRecord(c->ev[2 * pi + 1], c->st);
         HIPCHK(c, hipStreamSynchronize(c->st));   // following iterations wait until memory is in order (Section V-D)
+        prof_collect(c);
       }
       c->lo = old_lo + off;
       c->hi = c->lo + n1;
@@ -650,6 +708,25 @@ int32_t flover_get_kv_cache(const flover_ctx* c, void** base, uint64_t* bytes) {
   if (!c) return FLOVER_E_INVAL;
   if (base) *base = c->kv;
   if (bytes) *bytes = c->kv_bytes;
+  return FLOVER_OK;
+}
+
+int32_t flover_set_profile(flover_ctx* c, int32_t level) {
+  if (!c || level < 0 || level > 2) return fail(c, FLOVER_E_INVAL, "profile level must be 0, 1 or 2");
+  c->profile = level;
+  for (int k = 0; k < FLOVER_PROF_KINDS; ++k) {
+    c->prof_ms[k] = 0;
+    c->prof_launches[k] = 0;
+    c->prof_bytes[k] = 0;
+  }
+  return FLOVER_OK;
+}
+
+int32_t flover_get_profile(const flover_ctx* c, int32_t kind, double* ms, int64_t* launches, int64_t* bytes) {
+  if (!c || kind < 0 || kind >= FLOVER_PROF_KINDS) return FLOVER_E_INVAL;
+  if (ms) *ms = c->prof_ms[kind];
+  if (launches) *launches = c->prof_launches[kind];
+  if (bytes) *bytes = c->prof_bytes[kind];
   return FLOVER_OK;
 }
 
@@ -785,7 +862,7 @@ int32_t flover_k_gemm_tiled_bytes(int32_t dtype, int32_t N, int32_t K, uint64_t*
 int32_t flover_k_gemm_workspace_bytes(int32_t dtype, int32_t M, int32_t N, int32_t K, uint64_t* out) {
   if (dtype < FLOVER_F32 || dtype > FLOVER_BF16 || M < 0 || N < 1 || K < 32 || K % 32 || !out) return fail(nullptr, FLOVER_E_INVAL, "bad argument");
   const flk::GemmPlan p = flk::gemm_plan(dtype, N, K);
-  *out = align_up((size_t)p.S * std::max(M, 1) * N * 4, 256);
+  *out = align_up((size_t)p.S * std::max(M, 1) * p.ldc * 4, 256);
   return FLOVER_OK;
 }
 
@@ -801,26 +878,33 @@ int32_t flover_k_gemm_retile(int32_t dtype, const void* W, int32_t N, int32_t K,
 
 // y = sum of the split-K slices, in slice order (same order the step's consumers use)
 namespace flk {
-__global__ void slice_sum_kernel(const float* __restrict__ part, int S, size_t stride, float* __restrict__ y, size_t total) {
+__global__ void slice_sum_kernel(const float* __restrict__ part, int S, size_t stride, int ldc, float* __restrict__ y, int M,
+                                 int N) {
   const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
-  if (i >= total) return;
-  float v = part[i];
-  for (int s = 1; s < S; ++s) v += part[(size_t)s * stride + i];
+  if (i >= (size_t)M * N) return;
+  const size_t m = i / N, n = i - m * N;
+  const size_t idx = m * ldc + n;
+  float v = part[idx];
+  for (int s = 1; s < S; ++s) v += part[(size_t)s * stride + idx];
   y[i] = v;
 }
 }  // namespace flk
 
 extern "C" int32_t flover_k_gemm(int32_t dtype, const void* x, const void* w_tiled, int32_t M, int32_t N, int32_t K,
                                  float* y, void* workspace, uint64_t workspace_bytes, void* stream) {
-  if (dtype < FLOVER_F32 || dtype > FLOVER_BF16 || !x || !w_tiled || !y || !workspace || M < 0 || N < 1 || K < 32 || K % 32)
+  if (dtype < FLOVER_F32 || dtype > FLOVER_BF16 || M < 0 || N < 1 || K < 32 || K % 32)
     return fail(nullptr, FLOVER_E_INVAL, "bad argument");
   if (M == 0) return FLOVER_OK;
+  if (!x || !w_tiled || !workspace) return fail(nullptr, FLOVER_E_INVAL, "null argument");
   const flk::GemmPlan p = flk::gemm_plan(dtype, N, K);
-  const size_t stride = (size_t)M * N;
+  const size_t stride = (size_t)M * p.ldc;
   if ((size_t)p.S * stride * 4 > workspace_bytes) return fail(nullptr, FLOVER_E_NOMEM, "gemm workspace too small");
   hipStream_t st = (hipStream_t)stream;
-  HIPCHK(nullptr, flk::gemm(dtype, x, w_tiled, M, p, (float*)workspace, stride, N, st));
-  flk::slice_sum_kernel<<<(unsigned)((stride + 255) / 256), 256, 0, st>>>((const float*)workspace, p.S, stride, y, stride);
-  HIPCHK(nullptr, hipGetLastError());
+  HIPCHK(nullptr, flk::gemm(dtype, x, w_tiled, M, p, (float*)workspace, stride, st));
+  if (y) {
+    const size_t total = (size_t)M * N;
+    flk::slice_sum_kernel<<<(unsigned)((total + 255) / 256), 256, 0, st>>>((const float*)workspace, p.S, stride, p.ldc, y, M, N);
+    HIPCHK(nullptr, hipGetLastError());
+  }
   return FLOVER_OK;
 }

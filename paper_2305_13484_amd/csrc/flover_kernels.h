@@ -10,32 +10,37 @@ namespace flk {
 struct GemmPlan {
   int N, K;
   int Npad;   // N rounded up to 64 columns (16-bit dtypes)
+  int NT;     // n-tiles (of 16 columns) per wave
   int KB;     // K / 32
   int S;      // split-K slices, a function of (N, K) only
   int kbs;    // k-blocks per slice
+  int ldc;    // row length of the partial-sum slices (N rounded up to 4)
 };
+inline int part_ld(int N) { return (N + 3) / 4 * 4; }
 GemmPlan gemm_plan(int dtype, int N, int K);
 size_t gemm_tiled_bytes(int dtype, int N, int K);
 // Re-tile W [N][K] into `tiled` starting at output column n_off (multiple of 16) of a possibly larger matrix.
 hipError_t retile(int dtype, const void* W, int N, int K, void* tiled, int n_off, hipStream_t st);
 hipError_t zero_fill(void* p, size_t bytes, hipStream_t st);
-// part[s][m][ldc] (slice stride in floats) = x[M][K] . W^T over slice s of K.
+// part[s][m][p.ldc] (slice stride in floats) = x[M][K] . W^T over slice s of K.
 hipError_t gemm(int dtype, const void* x, const void* w_tiled, int M, const GemmPlan& p, float* part,
-                size_t slice_stride, int ldc, hipStream_t st);
+                size_t slice_stride, hipStream_t st);
 // rows of x that gemm() may read for M live rows
 inline int gemm_rows_read(int M) { return M <= 16 ? 16 : M <= 32 ? 32 : M <= 64 ? 64 : (M + 127) / 128 * 128; }
 
 // ---- row-wise kernels
 hipError_t embed(int dtype, const void* wte, const void* wpe, const int* tok, const int* pos, float* x, int M, int H,
                  hipStream_t st);
-hipError_t add_norm(int dtype, bool rms, float* x, const float* part, int S, size_t stride, const void* bias,
+// `part` is the preceding GEMM's split-K output: S slices, `stride` floats apart, rows of `ldp` floats (ldp % 4 == 0).
+hipError_t add_norm(int dtype, bool rms, float* x, const float* part, int S, size_t stride, int ldp, const void* bias,
                     const void* g, const void* b, void* h, int M, int H, float eps, hipStream_t st);
-hipError_t qkv_post(int dtype, const float* part, int S, size_t stride, const void* bias, const float* rope_cs,
+hipError_t qkv_post(int dtype, const float* part, int S, size_t stride, int ldp, const void* bias, const float* rope_cs,
                     const int* slot, const int* pos, void* q, void* kcache, void* vcache, int M, int H, int nh, int d,
                     int Smax, hipStream_t st);
-hipError_t activation(int dtype, bool swiglu, const float* part, int S, size_t stride, const void* bias, void* a, int M,
-                      int F, hipStream_t st);
-hipError_t logits_argmax(const float* part, int S, size_t stride, float* logits, int* tok, int M, int V, hipStream_t st);
+hipError_t activation(int dtype, bool swiglu, const float* part, int S, size_t stride, int ldp, const void* bias, void* a,
+                      int M, int F, hipStream_t st);
+hipError_t logits_argmax(const float* part, int S, size_t stride, int ldp, float* logits, int* tok, int M, int V,
+                         hipStream_t st);
 
 // ---- ragged decode attention
 struct AttnWork {          // all device pointers
@@ -50,8 +55,10 @@ struct AttnWork {          // all device pointers
   int chunk;
 };
 constexpr int kAttnChunk = 256;   // positions per wave task; fixed, so chunking depends on a request's own length only
+// ev0 / ev1 (optional) are recorded right before / after the streaming kernel (the merge kernel follows ev1).
 hipError_t decode_attention(int dtype, int d, const void* q, const void* kc, const void* vc, const AttnWork& w, int M,
-                            int nh, int Smax, void* out, hipStream_t st);
+                            int nh, int Smax, void* out, hipStream_t st, hipEvent_t ev0 = nullptr,
+                            hipEvent_t ev1 = nullptr);
 
 // ---- memory shuffle copy
 constexpr int kCompactPiece = 16384;   // bytes per block

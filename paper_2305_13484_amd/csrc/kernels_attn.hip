@@ -142,24 +142,26 @@ __global__ void attn_merge_kernel(const float* __restrict__ pml, const float* __
 
 template <int DT, int D>
 static void launch_attn(const void* q, const void* kc, const void* vc, const AttnWork& w, int M, int nh, int Smax,
-                        void* out, hipStream_t st) {
+                        void* out, hipStream_t st, hipEvent_t ev0, hipEvent_t ev1) {
   const float scale = 1.0f / sqrtf((float)D);
+  if (ev0) (void)hipEventRecord(ev0, st);
   attn_partial_kernel<DT, D><<<dim3(w.n_items, nh / 4), 256, 0, st>>>(q, kc, vc, w.items, w.row_slot, w.row_len, nh, Smax,
                                                                     w.chunk, scale, w.pml, w.po);
+  if (ev1) (void)hipEventRecord(ev1, st);
   attn_merge_kernel<DT, D><<<dim3(M, nh), D, 0, st>>>(w.pml, w.po, w.row_item0, w.row_nchunk, nh, out);
 }
 
 hipError_t decode_attention(int dtype, int d, const void* q, const void* kc, const void* vc, const AttnWork& w, int M,
-                            int nh, int Smax, void* out, hipStream_t st) {
+                            int nh, int Smax, void* out, hipStream_t st, hipEvent_t ev0, hipEvent_t ev1) {
   if (M <= 0 || w.n_items <= 0) return hipSuccess;
   if (d == 128) {
-    if (dtype == DT_F32) launch_attn<DT_F32, 128>(q, kc, vc, w, M, nh, Smax, out, st);
-    else if (dtype == DT_F16) launch_attn<DT_F16, 128>(q, kc, vc, w, M, nh, Smax, out, st);
-    else launch_attn<DT_BF16, 128>(q, kc, vc, w, M, nh, Smax, out, st);
+    if (dtype == DT_F32) launch_attn<DT_F32, 128>(q, kc, vc, w, M, nh, Smax, out, st, ev0, ev1);
+    else if (dtype == DT_F16) launch_attn<DT_F16, 128>(q, kc, vc, w, M, nh, Smax, out, st, ev0, ev1);
+    else launch_attn<DT_BF16, 128>(q, kc, vc, w, M, nh, Smax, out, st, ev0, ev1);
   } else {
-    if (dtype == DT_F32) launch_attn<DT_F32, 64>(q, kc, vc, w, M, nh, Smax, out, st);
-    else if (dtype == DT_F16) launch_attn<DT_F16, 64>(q, kc, vc, w, M, nh, Smax, out, st);
-    else launch_attn<DT_BF16, 64>(q, kc, vc, w, M, nh, Smax, out, st);
+    if (dtype == DT_F32) launch_attn<DT_F32, 64>(q, kc, vc, w, M, nh, Smax, out, st, ev0, ev1);
+    else if (dtype == DT_F16) launch_attn<DT_F16, 64>(q, kc, vc, w, M, nh, Smax, out, st, ev0, ev1);
+    else launch_attn<DT_BF16, 64>(q, kc, vc, w, M, nh, Smax, out, st, ev0, ev1);
   }
   return hipGetLastError();
 }

@@ -9,11 +9,46 @@
 
 namespace flk {
 
-// sum of S partial slices at element idx, slice order
-__device__ __forceinline__ float psum(const float* __restrict__ part, int S, size_t stride, size_t idx) {
-  float v = part[idx];
-  for (int s = 1; s < S; ++s) v += part[(size_t)s * stride + idx];
+// Sum of S split-K slices at 4 consecutive elements, added in slice order.  Loads of 4 slices are issued together so a
+// thread keeps several 16-byte requests in flight; the additions stay sequential (s = 0, 1, 2, ...).
+__device__ __forceinline__ f32x4_t ld4(const float* p) { return *(const f32x4_t*)p; }
+__device__ __forceinline__ f32x4_t psum4(const float* __restrict__ part, int S, size_t stride, size_t idx) {
+  const float* p = part + idx;
+  f32x4_t v = ld4(p);
+  int s = 1;
+  for (; s + 3 < S; s += 4) {
+    const f32x4_t a = ld4(p + (size_t)s * stride), b = ld4(p + (size_t)(s + 1) * stride),
+                  c = ld4(p + (size_t)(s + 2) * stride), d = ld4(p + (size_t)(s + 3) * stride);
+    v += a; v += b; v += c; v += d;
+  }
+  for (; s < S; ++s) v += ld4(p + (size_t)s * stride);
   return v;
+}
+template <int DT> __device__ __forceinline__ f32x4_t ldv4(const void* p, size_t i) {   // 4 consecutive dtype elements
+  if constexpr (DT == DT_F32) return *(const f32x4_t*)((const float*)p + i);
+  else {
+    const uint2 r = *(const uint2*)((const uint16_t*)p + i);
+    if constexpr (DT == DT_BF16)
+      return f32x4_t{__uint_as_float(r.x << 16), __uint_as_float(r.x & 0xffff0000u), __uint_as_float(r.y << 16),
+                     __uint_as_float(r.y & 0xffff0000u)};
+    else
+      return f32x4_t{f16_to_f32((uint16_t)(r.x & 0xffffu)), f16_to_f32((uint16_t)(r.x >> 16)),
+                     f16_to_f32((uint16_t)(r.y & 0xffffu)), f16_to_f32((uint16_t)(r.y >> 16))};
+  }
+}
+template <int DT> __device__ __forceinline__ void stv4(void* p, size_t i, f32x4_t v) {
+  if constexpr (DT == DT_F32) *(f32x4_t*)((float*)p + i) = v;
+  else {
+    uint2 r;
+    if constexpr (DT == DT_BF16) {
+      r.x = (uint32_t)f32_to_bf16(v[0]) | ((uint32_t)f32_to_bf16(v[1]) << 16);
+      r.y = (uint32_t)f32_to_bf16(v[2]) | ((uint32_t)f32_to_bf16(v[3]) << 16);
+    } else {
+      r.x = (uint32_t)f32_to_f16(v[0]) | ((uint32_t)f32_to_f16(v[1]) << 16);
+      r.y = (uint32_t)f32_to_f16(v[2]) | ((uint32_t)f32_to_f16(v[3]) << 16);
+    }
+    *(uint2*)((uint16_t*)p + i) = r;
+  }
 }
 
 // ---------------------------------------------------------------- embedding
@@ -25,41 +60,41 @@ __global__ __launch_bounds__(256) void embed_kernel(const void* __restrict__ wte
   const int m = blockIdx.x;
   const size_t t = (size_t)tok[m] * H;
   const size_t p = wpe ? (size_t)pos[m] * H : 0;
-  for (int i = threadIdx.x; i < H; i += 256) {
-    float v = ld<DT>(wte, t + i);
-    if (wpe) v += ld<DT>(wpe, p + i);
-    x[(size_t)m * H + i] = v;
+  for (int i = threadIdx.x * 4; i < H; i += 1024) {
+    f32x4_t v = ldv4<DT>(wte, t + i);
+    if (wpe) v += ldv4<DT>(wpe, p + i);
+    *(f32x4_t*)(x + (size_t)m * H + i) = v;
   }
 }
 
 // ---------------------------------------------------------------- residual add + norm
 // x[m] += sum_s part[s][m] + bias   (skipped when part == nullptr), then
 // h[m] = LayerNorm(x[m]) * g + b   (RMS == 0)   or   x[m] / rms(x[m]) * g   (RMS == 1), rounded to dtype.
-// grid = M, block = 256; H <= 256 * 32.
+// grid = M, block = 256, 4 consecutive elements per thread and pass; H <= 8192, H % 4 == 0.  part rows have length ldp.
 template <int DT, int RMS>
 __global__ __launch_bounds__(256) void add_norm_kernel(float* __restrict__ x, const float* __restrict__ part, int S,
-                                                       size_t stride, const void* __restrict__ bias,
+                                                       size_t stride, int ldp, const void* __restrict__ bias,
                                                        const void* __restrict__ g, const void* __restrict__ b,
                                                        void* __restrict__ h, int H, float eps) {
   __shared__ float red[4];
   const int m = blockIdx.x;
-  constexpr int PER = 32;
-  float v[PER];
+  constexpr int PER = 8;
+  f32x4_t v[PER];
   float sum = 0.f;
 #pragma unroll
   for (int c = 0; c < PER; ++c) {
-    const int i = threadIdx.x + c * 256;
-    v[c] = 0.f;
+    const int i = (threadIdx.x + c * 256) * 4;
+    v[c] = f32x4_t{0.f, 0.f, 0.f, 0.f};
     if (i < H) {
-      float t = x[(size_t)m * H + i];
+      f32x4_t t = *(const f32x4_t*)(x + (size_t)m * H + i);
       if (part) {
-        float a = psum(part, S, stride, (size_t)m * H + i);
-        if (bias) a += ld<DT>(bias, i);
+        f32x4_t a = psum4(part, S, stride, (size_t)m * ldp + i);
+        if (bias) a += ldv4<DT>(bias, i);
         t += a;
-        x[(size_t)m * H + i] = t;
+        *(f32x4_t*)(x + (size_t)m * H + i) = t;
       }
       v[c] = t;
-      sum += RMS ? t * t : t;
+      sum += RMS ? (t[0] * t[0] + t[1] * t[1]) + (t[2] * t[2] + t[3] * t[3]) : (t[0] + t[1]) + (t[2] + t[3]);
     }
   }
   sum = block_sum<4>(sum, red);
@@ -71,96 +106,110 @@ __global__ __launch_bounds__(256) void add_norm_kernel(float* __restrict__ x, co
     float sq = 0.f;
 #pragma unroll
     for (int c = 0; c < PER; ++c)
-      if (threadIdx.x + c * 256 < H) sq += (v[c] - mean) * (v[c] - mean);
+      if ((threadIdx.x + c * 256) * 4 < H) {
+        const f32x4_t dlt = v[c] - mean;
+        sq += (dlt[0] * dlt[0] + dlt[1] * dlt[1]) + (dlt[2] * dlt[2] + dlt[3] * dlt[3]);
+      }
     sq = block_sum<4>(sq, red);
     inv = 1.0f / sqrtf(sq / (float)H + eps);
   }
 #pragma unroll
   for (int c = 0; c < PER; ++c) {
-    const int i = threadIdx.x + c * 256;
+    const int i = (threadIdx.x + c * 256) * 4;
     if (i < H) {
-      float o = (v[c] - mean) * inv * ld<DT>(g, i);
-      if (!RMS) o += ld<DT>(b, i);
-      st<DT>(h, (size_t)m * H + i, o);
+      f32x4_t o = (v[c] - mean) * inv * ldv4<DT>(g, i);
+      if (!RMS) o += ldv4<DT>(b, i);
+      stv4<DT>(h, (size_t)m * H + i, o);
     }
   }
 }
 
 // ---------------------------------------------------------------- QKV epilogue: bias, rotary, KV append
-// part: [S][M][3H] (q | k | v).  For row m (slot, pos) and head hd: q -> qout[m][hd][:] (dtype),
-// k, v -> cache[slot][hd][pos][:] (dtype).  Rotary (LLaMA): pairs (i, i + d/2), cos/sin from a table [max_seq][d/2].
-// grid = (M, n_head), block = d/2.
+// part: [S][M][ldp] rows (q | k | v).  For row m (slot, pos) and head hd: q -> qout[m][hd][:] (dtype),
+// k, v -> cache[slot][hd][pos][:] (dtype).  Rotary (LLaMA): pairs (i, i + d/2), cos/sin from a table [max_seq][d/2][2].
+// grid = M, block = n_head * d / 8: thread (hd, j) owns elements 4j..4j+3 and their partners 4j + d/2 .. of q, k and v.
 template <int DT>
-__global__ void qkv_post_kernel(const float* __restrict__ part, int S, size_t stride, const void* __restrict__ bias,
-                                const float* __restrict__ rope_cs, const int* __restrict__ slot,
-                                const int* __restrict__ pos, void* __restrict__ qout, void* __restrict__ kcache,
-                                void* __restrict__ vcache, int H, int nh, int d, int Smax) {
-  const int m = blockIdx.x, hd = blockIdx.y, i = threadIdx.x, half = d >> 1;
-  const size_t row = (size_t)m * 3 * H;
+__global__ void qkv_post_kernel(const float* __restrict__ part, int S, size_t stride, int ldp,
+                                const void* __restrict__ bias, const float* __restrict__ rope_cs,
+                                const int* __restrict__ slot, const int* __restrict__ pos, void* __restrict__ qout,
+                                void* __restrict__ kcache, void* __restrict__ vcache, int H, int nh, int d, int Smax) {
+  const int m = blockIdx.x, half = d >> 1, tph = d >> 3;
+  const int hd = threadIdx.x / tph, i = (threadIdx.x - hd * tph) * 4;
+  const size_t row = (size_t)m * ldp;
   const int c0 = hd * d + i, c1 = c0 + half;
-  float q0 = psum(part, S, stride, row + c0), q1 = psum(part, S, stride, row + c1);
-  float k0 = psum(part, S, stride, row + H + c0), k1 = psum(part, S, stride, row + H + c1);
-  float v0 = psum(part, S, stride, row + 2 * H + c0), v1 = psum(part, S, stride, row + 2 * H + c1);
+  f32x4_t q0 = psum4(part, S, stride, row + c0), q1 = psum4(part, S, stride, row + c1);
+  f32x4_t k0 = psum4(part, S, stride, row + H + c0), k1 = psum4(part, S, stride, row + H + c1);
+  f32x4_t v0 = psum4(part, S, stride, row + 2 * H + c0), v1 = psum4(part, S, stride, row + 2 * H + c1);
   if (bias) {
-    q0 += ld<DT>(bias, c0); q1 += ld<DT>(bias, c1);
-    k0 += ld<DT>(bias, H + c0); k1 += ld<DT>(bias, H + c1);
-    v0 += ld<DT>(bias, 2 * H + c0); v1 += ld<DT>(bias, 2 * H + c1);
+    q0 += ldv4<DT>(bias, c0); q1 += ldv4<DT>(bias, c1);
+    k0 += ldv4<DT>(bias, H + c0); k1 += ldv4<DT>(bias, H + c1);
+    v0 += ldv4<DT>(bias, 2 * H + c0); v1 += ldv4<DT>(bias, 2 * H + c1);
   }
   const int p = pos[m];
   if (rope_cs) {
-    const float cs = rope_cs[((size_t)p * half + i) * 2], sn = rope_cs[((size_t)p * half + i) * 2 + 1];
-    const float a = q0 * cs - q1 * sn, b = q1 * cs + q0 * sn;
-    q0 = a; q1 = b;
-    const float c = k0 * cs - k1 * sn, e = k1 * cs + k0 * sn;
+    const float* t = rope_cs + ((size_t)p * half + i) * 2;
+    const f32x4_t t0 = ld4(t), t1 = ld4(t + 4);          // (cos, sin) of 4 consecutive pairs
+    const f32x4_t cs = {t0[0], t0[2], t1[0], t1[2]}, sn = {t0[1], t0[3], t1[1], t1[3]};
+    const f32x4_t a = q0 * cs - q1 * sn, bq = q1 * cs + q0 * sn;
+    q0 = a; q1 = bq;
+    const f32x4_t c = k0 * cs - k1 * sn, e = k1 * cs + k0 * sn;
     k0 = c; k1 = e;
   }
-  st<DT>(qout, (size_t)m * H + c0, q0);
-  st<DT>(qout, (size_t)m * H + c1, q1);
+  stv4<DT>(qout, (size_t)m * H + c0, q0);
+  stv4<DT>(qout, (size_t)m * H + c1, q1);
   const size_t kv = (((size_t)slot[m] * nh + hd) * Smax + p) * d;
-  st<DT>(kcache, kv + i, k0);
-  st<DT>(kcache, kv + i + half, k1);
-  st<DT>(vcache, kv + i, v0);
-  st<DT>(vcache, kv + i + half, v1);
+  stv4<DT>(kcache, kv + i, k0);
+  stv4<DT>(kcache, kv + i + half, k1);
+  stv4<DT>(vcache, kv + i, v0);
+  stv4<DT>(vcache, kv + i + half, v1);
 }
 
 // ---------------------------------------------------------------- MLP activation
-// GPT:   a[m][j] = gelu_tanh(sum_s part[s][m][j] + b1[j])                      part row length F
-// LLaMA: a[m][j] = silu(gate) * up, gate = part[..][m][j], up = part[..][m][F + j]   part row length 2F
+// GPT:   a[m][j] = gelu_tanh(sum_s part[s][m][j] + b1[j])                            part row length ldp >= F
+// LLaMA: a[m][j] = silu(gate) * up, gate = part[..][m][j], up = part[..][m][F + j]   part row length ldp >= 2F
+// 4 consecutive j per thread; F % 4 == 0.
 template <int DT, int SWIGLU>
-__global__ __launch_bounds__(256) void act_kernel(const float* __restrict__ part, int S, size_t stride,
-                                                  const void* __restrict__ bias, void* __restrict__ a, int F, long total) {
+__global__ __launch_bounds__(256) void act_kernel(const float* __restrict__ part, int S, size_t stride, int ldp,
+                                                  const void* __restrict__ bias, void* __restrict__ a, int F, long total4) {
   const long idx = (long)blockIdx.x * 256 + threadIdx.x;
-  if (idx >= total) return;
-  const long m = idx / F;
-  const int j = (int)(idx - m * F);
-  float o;
+  if (idx >= total4) return;
+  const int F4 = F >> 2;
+  const long m = idx / F4;
+  const int j = (int)(idx - m * F4) * 4;
+  f32x4_t o;
   if (SWIGLU) {
-    const float g = psum(part, S, stride, (size_t)m * 2 * F + j);
-    const float u = psum(part, S, stride, (size_t)m * 2 * F + F + j);
-    o = g / (1.0f + expf(-g)) * u;
+    const f32x4_t g = psum4(part, S, stride, (size_t)m * ldp + j);
+    const f32x4_t u = psum4(part, S, stride, (size_t)m * ldp + F + j);
+#pragma unroll
+    for (int e = 0; e < 4; ++e) o[e] = g[e] / (1.0f + expf(-g[e])) * u[e];
   } else {
-    const float t = psum(part, S, stride, (size_t)m * F + j) + ld<DT>(bias, j);
-    o = 0.5f * t * (1.0f + tanhf(0.7978845608028654f * (t + 0.044715f * t * t * t)));
+    const f32x4_t t = psum4(part, S, stride, (size_t)m * ldp + j) + ldv4<DT>(bias, j);
+#pragma unroll
+    for (int e = 0; e < 4; ++e)
+      o[e] = 0.5f * t[e] * (1.0f + tanhf(0.7978845608028654f * (t[e] + 0.044715f * t[e] * t[e] * t[e])));
   }
-  st<DT>(a, idx, o);
+  stv4<DT>(a, (size_t)m * F + j, o);
 }
 
 // ---------------------------------------------------------------- logits + greedy token
-// logits[m][j] = sum_s part[s][m][j] (fp32, optionally stored); tok[m] = argmax_j, lowest j on ties.
-// grid = M, block = 256.
-__global__ __launch_bounds__(256) void argmax_kernel(const float* __restrict__ part, int S, size_t stride,
-                                                     float* __restrict__ logits, int* __restrict__ tok, int V) {
-  __shared__ float bv[4];
-  __shared__ int bi[4];
+// logits[m][j] = sum_s part[s][m][j] (fp32, optionally stored, row length V); tok[m] = argmax_j, lowest j on ties.
+// grid = M, block = 1024; part rows have length ldp (multiple of 4, >= V).
+__global__ __launch_bounds__(1024) void argmax_kernel(const float* __restrict__ part, int S, size_t stride, int ldp,
+                                                      float* __restrict__ logits, int* __restrict__ tok, int V) {
+  __shared__ float bv[16];
+  __shared__ int bi[16];
   const int m = blockIdx.x;
   float best = -INFINITY;
   int arg = 0x7fffffff;
-  for (int j = threadIdx.x; j < V; j += 256) {
-    const float v = psum(part, S, stride, (size_t)m * V + j);
-    if (logits) logits[(size_t)m * V + j] = v;
-    if (v > best || (v == best && j < arg)) { best = v; arg = j; }
+  for (int j = threadIdx.x * 4; j < V; j += 4096) {
+    const f32x4_t v = psum4(part, S, stride, (size_t)m * ldp + j);
+#pragma unroll
+    for (int e = 0; e < 4; ++e)
+      if (j + e < V) {
+        if (logits) logits[(size_t)m * V + j + e] = v[e];
+        if (v[e] > best) { best = v[e]; arg = j + e; }      // ascending j: the first maximum stays
+      }
   }
-  if (arg == 0x7fffffff) { best = -INFINITY; }
 #pragma unroll
   for (int dlt = 1; dlt < 64; dlt <<= 1) {
     const float ov = __shfl_xor(best, dlt, 64);
@@ -170,9 +219,9 @@ __global__ __launch_bounds__(256) void argmax_kernel(const float* __restrict__ p
   if ((threadIdx.x & 63) == 0) { bv[threadIdx.x >> 6] = best; bi[threadIdx.x >> 6] = arg; }
   __syncthreads();
   if (threadIdx.x == 0) {
-    for (int w = 1; w < 4; ++w)
+    for (int w = 1; w < 16; ++w)
       if (bv[w] > best || (bv[w] == best && bi[w] < arg)) { best = bv[w]; arg = bi[w]; }
-    tok[m] = arg;
+    tok[m] = (arg == 0x7fffffff) ? 0 : arg;       // a row of NaNs has no maximum
   }
 }
 
@@ -192,42 +241,43 @@ hipError_t embed(int dtype, const void* wte, const void* wpe, const int* tok, co
   return hipGetLastError();
 }
 
-hipError_t add_norm(int dtype, bool rms, float* x, const float* part, int S, size_t stride, const void* bias,
+hipError_t add_norm(int dtype, bool rms, float* x, const float* part, int S, size_t stride, int ldp, const void* bias,
                     const void* g, const void* b, void* h, int M, int H, float eps, hipStream_t st) {
   if (M <= 0) return hipSuccess;
   if (rms) {
-    FLK_DT_SWITCH(dtype, (add_norm_kernel<DT, 1><<<M, 256, 0, st>>>(x, part, S, stride, bias, g, b, h, H, eps)));
+    FLK_DT_SWITCH(dtype, (add_norm_kernel<DT, 1><<<M, 256, 0, st>>>(x, part, S, stride, ldp, bias, g, b, h, H, eps)));
   } else {
-    FLK_DT_SWITCH(dtype, (add_norm_kernel<DT, 0><<<M, 256, 0, st>>>(x, part, S, stride, bias, g, b, h, H, eps)));
+    FLK_DT_SWITCH(dtype, (add_norm_kernel<DT, 0><<<M, 256, 0, st>>>(x, part, S, stride, ldp, bias, g, b, h, H, eps)));
   }
   return hipGetLastError();
 }
 
-hipError_t qkv_post(int dtype, const float* part, int S, size_t stride, const void* bias, const float* rope_cs,
+hipError_t qkv_post(int dtype, const float* part, int S, size_t stride, int ldp, const void* bias, const float* rope_cs,
                     const int* slot, const int* pos, void* q, void* kcache, void* vcache, int M, int H, int nh, int d,
                     int Smax, hipStream_t st) {
   if (M <= 0) return hipSuccess;
-  FLK_DT_SWITCH(dtype, (qkv_post_kernel<DT><<<dim3(M, nh), d / 2, 0, st>>>(part, S, stride, bias, rope_cs, slot, pos, q,
+  FLK_DT_SWITCH(dtype, (qkv_post_kernel<DT><<<M, nh * d / 8, 0, st>>>(part, S, stride, ldp, bias, rope_cs, slot, pos, q,
                                                                            kcache, vcache, H, nh, d, Smax)));
   return hipGetLastError();
 }
 
-hipError_t activation(int dtype, bool swiglu, const float* part, int S, size_t stride, const void* bias, void* a, int M,
-                      int F, hipStream_t st) {
+hipError_t activation(int dtype, bool swiglu, const float* part, int S, size_t stride, int ldp, const void* bias, void* a,
+                      int M, int F, hipStream_t st) {
   if (M <= 0) return hipSuccess;
-  const long total = (long)M * F;
+  const long total = (long)M * (F / 4);
   const unsigned grid = (unsigned)((total + 255) / 256);
   if (swiglu) {
-    FLK_DT_SWITCH(dtype, (act_kernel<DT, 1><<<grid, 256, 0, st>>>(part, S, stride, bias, a, F, total)));
+    FLK_DT_SWITCH(dtype, (act_kernel<DT, 1><<<grid, 256, 0, st>>>(part, S, stride, ldp, bias, a, F, total)));
   } else {
-    FLK_DT_SWITCH(dtype, (act_kernel<DT, 0><<<grid, 256, 0, st>>>(part, S, stride, bias, a, F, total)));
+    FLK_DT_SWITCH(dtype, (act_kernel<DT, 0><<<grid, 256, 0, st>>>(part, S, stride, ldp, bias, a, F, total)));
   }
   return hipGetLastError();
 }
 
-hipError_t logits_argmax(const float* part, int S, size_t stride, float* logits, int* tok, int M, int V, hipStream_t st) {
+hipError_t logits_argmax(const float* part, int S, size_t stride, int ldp, float* logits, int* tok, int M, int V,
+                         hipStream_t st) {
   if (M <= 0) return hipSuccess;
-  argmax_kernel<<<M, 256, 0, st>>>(part, S, stride, logits, tok, V);
+  argmax_kernel<<<M, 1024, 0, st>>>(part, S, stride, ldp, logits, tok, V);
   return hipGetLastError();
 }
 

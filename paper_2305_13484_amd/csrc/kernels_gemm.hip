@@ -5,13 +5,17 @@
 // at full bandwidth:
 //   * W is re-tiled once at init into MFMA operand order: tile (n-tile of 16 columns, k-block of 32) is 1 KiB,
 //     lane l holds W[n0 + l%16][k0 + 8*(l/16) .. +8], so every wave load is one contiguous, fully used 1 KiB.
-//   * a wave owns 64 output columns (4 n-tiles) x one K slice x up to 128 rows; no LDS, no barriers: the rows'
-//     operand comes straight from L2/L1 (the 4 waves of a block share the K slice, so they hit the same lines).
+//   * a wave owns 32 or 64 output columns (2 or 4 n-tiles) x one K slice x all rows of its row block; up to 32 rows
+//     the rows' operand comes straight from L2/L1 (no LDS, no barriers); above that it is staged through LDS once
+//     per block and shared by the block's 4 waves.
 //   * split-K: slice count and boundaries depend on (N, K) only -- never on M -- and partial sums are written per
 //     slice and added by the consumer in slice order, so a row's result does not depend on which other rows
 //     are live (the paper's premise that fused requests undergo identical operations).
 //   * MFMA v_mfma_f32_16x16x32_{bf16,f16}: A = 16 rows of x, B = 16 columns of W, 32-deep.
 // fp32 models (tiny configurations only) use a plain FMA kernel on the untiled matrix.
+#include <algorithm>
+#include <cstdlib>
+
 #include "flover_dev.h"
 #include "flover_kernels.h"
 
@@ -43,11 +47,12 @@ template <int DT> __device__ __forceinline__ f32x4_t mfma16(const u32x4_t& a, co
     return __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(f16x8_t, a), __builtin_bit_cast(f16x8_t, b), c, 0, 0, 0);
 }
 
-// grid = (ceil(ngroups/4), S, ceil(M/(16*MT))), block = 256 (4 independent waves)
-template <int DT, int MT, int PF>
-__global__ __launch_bounds__(256) void gemm16_kernel(const uint16_t* __restrict__ x, const u32x4_t* __restrict__ wt,
-                                                     float* __restrict__ part, int M, int N, int K, int ngroups, int KB,
-                                                     int kbs, size_t slice_stride, int ldc) {
+// ---- small M (<= 32 rows): 4 independent waves per block, no LDS, no barriers.
+// grid = (ceil(ngroups/4), S, 1), block = 256; a wave owns NT n-tiles (16*NT columns) x one K slice x 16*MT rows.
+template <int DT, int MT, int NT, int PF>
+__global__ __launch_bounds__(256) void gemm16_direct_kernel(const uint16_t* __restrict__ x, const u32x4_t* __restrict__ wt,
+                                                            float* __restrict__ part, int M, int N, int K, int ngroups,
+                                                            int KB, int kbs, size_t slice_stride, int ldc) {
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int g = blockIdx.x * 4 + wave;
   if (g >= ngroups) return;
@@ -56,22 +61,22 @@ __global__ __launch_bounds__(256) void gemm16_kernel(const uint16_t* __restrict_
   const int kb0 = s * kbs;
   const int kb1 = min(KB, kb0 + kbs);
 
-  f32x4_t acc[MT][4];
+  f32x4_t acc[MT][NT];
 #pragma unroll
   for (int i = 0; i < MT; ++i)
 #pragma unroll
-    for (int t = 0; t < 4; ++t) acc[i][t] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+    for (int t = 0; t < NT; ++t) acc[i][t] = f32x4_t{0.f, 0.f, 0.f, 0.f};
 
-  const u32x4_t* wp = wt + ((size_t)(g * 4) * KB) * 64 + lane;                     // + t*KB*64 + kb*64
+  const u32x4_t* wp = wt + ((size_t)(g * NT) * KB) * 64 + lane;                  // + t*KB*64 + kb*64
   const uint16_t* xp = x + (size_t)(m0 + (lane & 15)) * K + (lane >> 4) * 8;     // + i*16*K + kb*32
   const size_t wtile = (size_t)KB * 64;
 
-  u32x4_t bq[PF][4], aq[PF][MT];
+  u32x4_t bq[PF][NT], aq[PF][MT];
 #pragma unroll
   for (int j = 0; j < PF; ++j) {
     const int kk = min(kb0 + j, kb1 - 1);
 #pragma unroll
-    for (int t = 0; t < 4; ++t) bq[j][t] = __builtin_nontemporal_load(wp + t * wtile + (size_t)kk * 64);
+    for (int t = 0; t < NT; ++t) bq[j][t] = __builtin_nontemporal_load(wp + t * wtile + (size_t)kk * 64);
 #pragma unroll
     for (int i = 0; i < MT; ++i) aq[j][i] = *(const u32x4_t*)(xp + (size_t)i * 16 * K + kk * 32);
   }
@@ -82,11 +87,11 @@ __global__ __launch_bounds__(256) void gemm16_kernel(const uint16_t* __restrict_
 #pragma unroll
         for (int i = 0; i < MT; ++i)
 #pragma unroll
-          for (int t = 0; t < 4; ++t) acc[i][t] = mfma16<DT>(aq[j][i], bq[j][t], acc[i][t]);
+          for (int t = 0; t < NT; ++t) acc[i][t] = mfma16<DT>(aq[j][i], bq[j][t], acc[i][t]);
       }
       const int kk = min(kb + j + PF, kb1 - 1);      // tail re-reads the last block (in bounds, unused)
 #pragma unroll
-      for (int t = 0; t < 4; ++t) bq[j][t] = __builtin_nontemporal_load(wp + t * wtile + (size_t)kk * 64);
+      for (int t = 0; t < NT; ++t) bq[j][t] = __builtin_nontemporal_load(wp + t * wtile + (size_t)kk * 64);
 #pragma unroll
       for (int i = 0; i < MT; ++i) aq[j][i] = *(const u32x4_t*)(xp + (size_t)i * 16 * K + kk * 32);
     }
@@ -95,8 +100,98 @@ __global__ __launch_bounds__(256) void gemm16_kernel(const uint16_t* __restrict_
 #pragma unroll
   for (int i = 0; i < MT; ++i)
 #pragma unroll
-    for (int t = 0; t < 4; ++t) {
-      const int n = (g * 4 + t) * 16 + (lane & 15);
+    for (int t = 0; t < NT; ++t) {
+      const int n = (g * NT + t) * 16 + (lane & 15);
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        const int m = m0 + i * 16 + (lane >> 4) * 4 + r;
+        if (m < M && n < N) out[(size_t)m * ldc + n] = acc[i][t][r];
+      }
+    }
+}
+
+// ---- larger M (33..128 rows per block): the rows' operand is staged through LDS once per block and shared by the
+// 4 waves (each wave owns its own NT n-tiles and streams their W tiles from HBM into registers, one chunk ahead).
+// LDS holds the x tile in MFMA fragment order ([k-block][m-tile][lane] x 16 B), so every ds_read_b128 of a fragment
+// is 1 KiB contiguous and bank-conflict free.  Double-buffered, one barrier per chunk of KC k-blocks.
+// The per-(m, n) arithmetic (MFMA sequence over k) is identical to the direct kernel's.
+template <int DT, int MT, int NT, int KC>
+__global__ __launch_bounds__(256) void gemm16_lds_kernel(const uint16_t* __restrict__ x, const u32x4_t* __restrict__ wt,
+                                                         float* __restrict__ part, int M, int N, int K, int ngroups,
+                                                         int KB, int kbs, size_t slice_stride, int ldc) {
+  __shared__ u32x4_t lds[2][KC * MT * 64];
+  constexpr int FPW = KC * MT / 4;               // fragments each wave stages per chunk
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int g = blockIdx.x * 4 + wave;
+  const int gl = min(g, ngroups - 1);            // surplus waves repeat the last group (they still serve the barriers)
+  const int s = blockIdx.y;
+  const int m0 = blockIdx.z * (16 * MT);
+  const int kb0 = s * kbs;
+  const int kb1 = min(KB, kb0 + kbs);
+  const int nchunks = (kb1 - kb0 + KC - 1) / KC;
+
+  f32x4_t acc[MT][NT];
+#pragma unroll
+  for (int i = 0; i < MT; ++i)
+#pragma unroll
+    for (int t = 0; t < NT; ++t) acc[i][t] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+
+  const u32x4_t* wp = wt + ((size_t)(gl * NT) * KB) * 64 + lane;
+  const uint16_t* xp = x + (size_t)(m0 + (lane & 15)) * K + (lane >> 4) * 8;
+  const size_t wtile = (size_t)KB * 64;
+
+  u32x4_t bq[KC][NT], areg[FPW];
+#pragma unroll
+  for (int j = 0; j < KC; ++j) {
+    const int kk = min(kb0 + j, kb1 - 1);
+#pragma unroll
+    for (int t = 0; t < NT; ++t) bq[j][t] = __builtin_nontemporal_load(wp + t * wtile + (size_t)kk * 64);
+  }
+  auto load_a = [&](int chunk) {
+#pragma unroll
+    for (int j = 0; j < FPW; ++j) {
+      const int f = wave + 4 * j, kc = f / MT, i = f - kc * MT;
+      const int kk = min(kb0 + chunk * KC + kc, kb1 - 1);
+      areg[j] = *(const u32x4_t*)(xp + (size_t)i * 16 * K + kk * 32);
+    }
+  };
+  auto store_a = [&](int buf) {
+#pragma unroll
+    for (int j = 0; j < FPW; ++j) lds[buf][(wave + 4 * j) * 64 + lane] = areg[j];
+  };
+  load_a(0);
+  store_a(0);
+  __syncthreads();
+  for (int c = 0; c < nchunks; ++c) {
+    const bool more = c + 1 < nchunks;
+    if (more) load_a(c + 1);
+    const u32x4_t* la = lds[c & 1];
+#pragma unroll
+    for (int kc = 0; kc < KC; ++kc) {
+      const int kb = kb0 + c * KC + kc;
+      if (kb < kb1) {
+        u32x4_t af[MT];
+#pragma unroll
+        for (int i = 0; i < MT; ++i) af[i] = la[(kc * MT + i) * 64 + lane];
+#pragma unroll
+        for (int i = 0; i < MT; ++i)
+#pragma unroll
+          for (int t = 0; t < NT; ++t) acc[i][t] = mfma16<DT>(af[i], bq[kc][t], acc[i][t]);
+      }
+      const int kk = min(kb + KC, kb1 - 1);
+#pragma unroll
+      for (int t = 0; t < NT; ++t) bq[kc][t] = __builtin_nontemporal_load(wp + t * wtile + (size_t)kk * 64);
+    }
+    if (more) store_a((c + 1) & 1);
+    __syncthreads();
+  }
+  if (g >= ngroups) return;
+  float* out = part + (size_t)s * slice_stride;
+#pragma unroll
+  for (int i = 0; i < MT; ++i)
+#pragma unroll
+    for (int t = 0; t < NT; ++t) {
+      const int n = (g * NT + t) * 16 + (lane & 15);
 #pragma unroll
       for (int r = 0; r < 4; ++r) {
         const int m = m0 + i * 16 + (lane >> 4) * 4 + r;
@@ -135,12 +230,19 @@ __global__ __launch_bounds__(256) void gemm32_kernel(const float* __restrict__ x
 
 // ---------------------------------------------------------------- host side
 
+static int tune_env(const char* name, int dflt) {
+  const char* v = getenv(name);
+  return v ? atoi(v) : dflt;
+}
+
 GemmPlan gemm_plan(int dtype, int N, int K) {
   GemmPlan p{};
   p.N = N;
   p.K = K;
+  p.ldc = part_ld(N);
   if (dtype == DT_F32) {
     p.Npad = N;
+    p.NT = 0;
     p.KB = 0;
     p.S = 1;
     p.kbs = 0;
@@ -148,13 +250,15 @@ GemmPlan gemm_plan(int dtype, int N, int K) {
   }
   p.Npad = (N + 63) / 64 * 64;
   p.KB = K / 32;
-  const int ngroups = p.Npad / 64;
-  // enough waves to fill 256 CUs a few times over, each with at least 8 k-blocks to stream; a function of (N,K) only
-  int S = (2048 + ngroups - 1) / ngroups;
-  int maxS = p.KB / 8;
+  // Everything below is a function of (N, K) only, never of the number of live rows.
+  // wide matrices: a wave owns 64 columns; narrow ones 32, so that enough waves exist without deep K splits
+  p.NT = tune_env("FLOVER_TUNE_NT", N >= 8192 ? 4 : 2);
+  const int ngroups = p.Npad / (16 * p.NT);
+  const int target = tune_env("FLOVER_TUNE_WAVES", 1536);
+  int S = (target + ngroups - 1) / ngroups;
+  int maxS = std::min(tune_env("FLOVER_TUNE_MAXS", 8), p.KB / 8);
   if (maxS < 1) maxS = 1;
   if (S > maxS) S = maxS;
-  if (S > 16) S = 16;
   if (S < 1) S = 1;
   p.kbs = (p.KB + S - 1) / S;
   p.S = (p.KB + p.kbs - 1) / p.kbs;
@@ -180,34 +284,41 @@ hipError_t retile(int dtype, const void* W, int N, int K, void* tiled, int n_off
 
 hipError_t zero_fill(void* p, size_t bytes, hipStream_t st) { return hipMemsetAsync(p, 0, bytes, st); }
 
-template <int DT, int MT, int PF>
-static void launch16(const void* x, const void* wt, float* part, int M, const GemmPlan& p, size_t slice_stride, int ldc,
-                     hipStream_t st) {
-  const int ngroups = p.Npad / 64;
+template <int DT, int MT, int NT, int PF>
+static void launch_direct(const void* x, const void* wt, float* part, int M, const GemmPlan& p, size_t ss, hipStream_t st) {
+  const int ngroups = p.Npad / (16 * NT);
   dim3 grid((ngroups + 3) / 4, p.S, (M + 16 * MT - 1) / (16 * MT));
-  gemm16_kernel<DT, MT, PF><<<grid, 256, 0, st>>>((const uint16_t*)x, (const u32x4_t*)wt, part, M, p.N, p.K, ngroups, p.KB,
-                                                  p.kbs, slice_stride, ldc);
+  gemm16_direct_kernel<DT, MT, NT, PF><<<grid, 256, 0, st>>>((const uint16_t*)x, (const u32x4_t*)wt, part, M, p.N, p.K,
+                                                             ngroups, p.KB, p.kbs, ss, p.ldc);
+}
+template <int DT, int MT, int NT>
+static void launch_lds(const void* x, const void* wt, float* part, int M, const GemmPlan& p, size_t ss, hipStream_t st) {
+  const int ngroups = p.Npad / (16 * NT);
+  dim3 grid((ngroups + 3) / 4, p.S, (M + 16 * MT - 1) / (16 * MT));
+  gemm16_lds_kernel<DT, MT, NT, 4><<<grid, 256, 0, st>>>((const uint16_t*)x, (const u32x4_t*)wt, part, M, p.N, p.K, ngroups,
+                                                         p.KB, p.kbs, ss, p.ldc);
 }
 
-template <int DT>
-static void dispatch16(const void* x, const void* wt, float* part, int M, const GemmPlan& p, size_t ss, int ldc,
-                       hipStream_t st) {
-  if (M <= 16) launch16<DT, 1, 8>(x, wt, part, M, p, ss, ldc, st);
-  else if (M <= 32) launch16<DT, 2, 6>(x, wt, part, M, p, ss, ldc, st);
-  else if (M <= 64) launch16<DT, 4, 4>(x, wt, part, M, p, ss, ldc, st);
-  else launch16<DT, 8, 2>(x, wt, part, M, p, ss, ldc, st);
+template <int DT, int NT>
+static void dispatch16(const void* x, const void* wt, float* part, int M, const GemmPlan& p, size_t ss, hipStream_t st) {
+  if (M <= 16) launch_direct<DT, 1, NT, 8>(x, wt, part, M, p, ss, st);
+  else if (M <= 32) launch_direct<DT, 2, NT, 6>(x, wt, part, M, p, ss, st);
+  else if (M <= 64) launch_lds<DT, 4, NT>(x, wt, part, M, p, ss, st);
+  else launch_lds<DT, 8, NT>(x, wt, part, M, p, ss, st);
 }
 
 hipError_t gemm(int dtype, const void* x, const void* wt, int M, const GemmPlan& p, float* part, size_t slice_stride,
-                int ldc, hipStream_t st) {
+                hipStream_t st) {
   if (M <= 0) return hipSuccess;
   if (dtype == DT_F32) {
     dim3 grid((p.N + 3) / 4, (M + 7) / 8);
-    gemm32_kernel<<<grid, 256, 0, st>>>((const float*)x, (const float*)wt, part, M, p.N, p.K, ldc);
+    gemm32_kernel<<<grid, 256, 0, st>>>((const float*)x, (const float*)wt, part, M, p.N, p.K, p.ldc);
   } else if (dtype == DT_BF16) {
-    dispatch16<DT_BF16>(x, wt, part, M, p, slice_stride, ldc, st);
+    if (p.NT == 4) dispatch16<DT_BF16, 4>(x, wt, part, M, p, slice_stride, st);
+    else dispatch16<DT_BF16, 2>(x, wt, part, M, p, slice_stride, st);
   } else {
-    dispatch16<DT_F16>(x, wt, part, M, p, slice_stride, ldc, st);
+    if (p.NT == 4) dispatch16<DT_F16, 4>(x, wt, part, M, p, slice_stride, st);
+    else dispatch16<DT_F16, 2>(x, wt, part, M, p, slice_stride, st);
   }
   return hipGetLastError();
 }
