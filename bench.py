@@ -33,6 +33,11 @@ def parse():
     ap.add_argument("--profile-level", type=int, default=1)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--seed", type=int, default=4)
+    ap.add_argument("--cached-context", action="store_true",
+                    help="profiler runs: requests join with their context cache taken as present (no pre-processing "
+                         "kernels), so every launch in the trace is a fused-iteration launch")
+    ap.add_argument("--copy-probe", type=int, default=0, metavar="MiB",
+                    help="only run the plain copy kernel on MiB mebibytes, 10 times (reference for profiler byte counters)")
     return ap.parse_args()
 
 
@@ -46,7 +51,7 @@ def step_bytes(cfg, lens):
     return cfg.weight_bytes_per_step() + sum(l + 1 for l in lens) * kvb + M * kvb + M * cfg.H * e + M * cfg.V * 4
 
 
-def run_stream(srv, cfg, reqs, max_steps, warm=False):
+def run_stream(srv, cfg, reqs, max_steps, cached=False):
     """Drives the stream; returns totals.  Steps are bracketed by host clocks; flover_step and flover_reorder_evict
     both return only after their GPU work has completed."""
     import torch
@@ -63,7 +68,10 @@ def run_stream(srv, cfg, reqs, max_steps, warm=False):
         t0 = time.perf_counter()
         while i < len(pending) and pending[i].arrival_step <= s:
             r = pending[i]
-            srv.add_request(r.req_id, r.prompt, r.gen_len)
+            if cached:
+                srv.add_request_cached(r.req_id, len(r.prompt) - 1, int(r.prompt[-1]), r.gen_len)
+            else:
+                srv.add_request(r.req_id, r.prompt, r.gen_len)
             lens[r.req_id] = len(r.prompt) - 1
             i += 1
         torch.cuda.synchronize()
@@ -125,6 +133,16 @@ def main():
     assert torch.cuda.is_available(), "bench.py needs the GPU"
     torch.cuda.set_device(0)
 
+    if a.copy_probe:
+        n = a.copy_probe << 20
+        src = torch.zeros(n, dtype=torch.uint8, device="cuda")
+        dst = torch.empty_like(src)
+        for _ in range(10):
+            fl.k_copy_probe(dst, src)
+        torch.cuda.synchronize()
+        print(json.dumps({"copy_probe_bytes": n, "launches": 10}))
+        return
+
     if a.workload == "c4":
         cfg = synth.llama_7b(L=a.layers or 32)
         reqs = synth.stream_c4(a.seed, cfg.V, n=a.requests or 128)
@@ -156,10 +174,10 @@ def main():
     if a.warmup > 0:
         rng = np.random.default_rng(1)
         warm = [synth.Request(10 ** 6 + i, 0, rng.integers(0, cfg.V, size=200).astype(np.int32), a.warmup) for i in range(8)]
-        run_stream(srv, cfg, warm, 0)
+        run_stream(srv, cfg, warm, 0, cached=a.cached_context)
 
     srv.set_profile(a.profile_level)
-    res = run_stream(srv, cfg, reqs, a.steps)
+    res = run_stream(srv, cfg, reqs, a.steps, cached=a.cached_context)
     prof = srv.get_profile()
     srv.close()
 
@@ -176,6 +194,14 @@ def main():
     per = res["per_step"]
     tot_bytes = sum(b for _, _, b in per)
     step_gbs = tot_bytes / total / 1e9 if total > 0 else 0.0
+    buckets = {}
+    for lo, hi in ((1, 16), (17, 32), (33, 64), (65, 10 ** 9)):
+        sel = [(n, t, b) for n, t, b in per if lo <= n <= hi]
+        if sel:
+            tt = sum(t for _, t, _ in sel)
+            buckets["live_%d_%s" % (lo, hi if hi < 10 ** 9 else "up")] = {
+                "steps": len(sel), "ms_per_step": round(1e3 * tt / len(sel), 3),
+                "hbm_GBs": round(sum(b for _, _, b in sel) / tt / 1e9, 1)}
     gemms = {}
     for k in ("gemm_qkv", "gemm_out", "gemm_ff1", "gemm_ff2", "gemm_lm", "compact"):
         p = prof[k]
@@ -188,9 +214,9 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": synth.DTYPE_NAME[cfg.dtype],
         "data": "synthetic",
         "config": {"workload": wl, "layers": cfg.L, "requests": len(reqs), "whole_stream": res["all_done"],
-                   "seed": a.seed},
+                   "seed": a.seed, "cached_context": a.cached_context},
         "tokens": res["tokens"], "mean_live": round(res["tokens"] / K, 2),
-        "step_hbm_GBs": round(step_gbs, 1), "step_hbm_frac": round(step_gbs / HBM_PEAK_GBS, 4),
+        "step_hbm_GBs": round(step_gbs, 1), "step_hbm_frac": round(step_gbs / HBM_PEAK_GBS, 4), "by_live_rows": buckets,
         "preprocess_s": round(res["t_pre"], 3), "tokens_per_s_incl_preprocess": round(res["tokens"] / (total + res["t_pre"]), 2),
         "shuffle_moves": res["moves"], "shuffle_bytes": res["bytes_moved"],
         "roofline": roof, "other_kernels": gemms, "cpu_baseline": cpu, "weights_gen_s": round(t_w, 2),

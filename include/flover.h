@@ -141,6 +141,15 @@ typedef struct flover_reorder_out {
  * With shuffle_off only the empty ends of the window are dropped.  Safe to call after every step. */
 int32_t flover_reorder_evict(flover_ctx* ctx, flover_reorder_out* out);
 
+/* Measurement hook (not in the paper): like flover_add_request, but the slot's context cache (KV rows
+ * [0, context_len)) is taken to be whatever the slot already holds -- no pre-processing kernels run.  The request
+ * feeds next_token at position context_len in the next flover_step.  Meant for profiler runs in which every launch
+ * must be a fused-iteration launch; results are meaningless numerically unless the caller filled the cache.
+ * Errors: INVAL (context_len < 0, context_len + 1 + max_new_tokens > max_seq, bad token, duplicate id),
+ * FULL (no adjacent slot free or requests already waiting; this call never queues). */
+int32_t flover_add_request_cached(flover_ctx* ctx, uint64_t req_id, int32_t context_len, int32_t next_token,
+                                  int32_t max_new_tokens, int32_t* out_slot);
+
 /* Test / benchmark hooks (not in the paper): end a request as if it had produced EOS; overwrite the token a
  * live request feeds in the next iteration (teacher forcing, to re-synchronise a comparison after a near tie). */
 int32_t flover_mark_finished(flover_ctx* ctx, uint64_t req_id);
@@ -212,6 +221,10 @@ int32_t flover_k_gemm_workspace_bytes(int32_t dtype, int32_t M, int32_t N, int32
 int32_t flover_k_gemm_retile(int32_t dtype, const void* W, int32_t N, int32_t K, void* w_tiled, void* stream);
 int32_t flover_k_gemm(int32_t dtype, const void* x, const void* w_tiled, int32_t M, int32_t N, int32_t K, float* y,
                       void* workspace, uint64_t workspace_bytes, void* stream);
+
+/* Plain device-to-device copy kernel of a known size (bytes % 16 == 0): the reference against which profiler byte
+ * counters (FETCH_SIZE / WRITE_SIZE) are scaled.  Measurement aid only. */
+int32_t flover_k_copy_probe(void* dst, const void* src, uint64_t bytes, void* stream);
 
 #ifdef __cplusplus
 }

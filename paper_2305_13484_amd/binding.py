@@ -20,7 +20,8 @@ EXPORTED_SYMBOLS = [
     "flover_step", "flover_reorder_evict", "flover_mark_finished", "flover_set_next_token", "flover_get_state",
     "flover_get_kv_cache", "flover_last_step_launches", "flover_set_profile", "flover_get_profile", "flover_k_find_window", "flover_k_attention_workspace_bytes",
     "flover_k_decode_attention", "flover_k_compact_workspace_bytes", "flover_k_compact", "flover_k_gemm_tiled_bytes",
-    "flover_k_gemm_workspace_bytes", "flover_k_gemm_retile", "flover_k_gemm",
+    "flover_k_gemm_workspace_bytes", "flover_k_gemm_retile", "flover_k_gemm", "flover_add_request_cached",
+    "flover_k_copy_probe",
 ]
 
 WEIGHT_FIELDS = ["wte", "wpe", "ln1_g", "ln1_b", "wqkv", "bqkv", "wo", "bo", "ln2_g", "ln2_b", "w1", "b1", "wu", "w2",
@@ -77,6 +78,9 @@ def load_library():
     L.flover_init.argtypes = [C.POINTER(_Config), C.POINTER(_Weights), C.POINTER(C.c_void_p)]
     L.flover_destroy.argtypes = [C.c_void_p]
     L.flover_add_request.argtypes = [C.c_void_p, C.c_uint64, C.c_void_p, C.c_int32, C.c_int32, C.POINTER(C.c_int32)]
+    L.flover_add_request_cached.argtypes = [C.c_void_p, C.c_uint64, C.c_int32, C.c_int32, C.c_int32,
+                                            C.POINTER(C.c_int32)]
+    L.flover_k_copy_probe.argtypes = [C.c_void_p, C.c_void_p, C.c_uint64, C.c_void_p]
     L.flover_step.argtypes = [C.c_void_p, C.POINTER(_StepOut)]
     L.flover_reorder_evict.argtypes = [C.c_void_p, C.POINTER(_ReorderOut)]
     L.flover_mark_finished.argtypes = [C.c_void_p, C.c_uint64]
@@ -184,6 +188,12 @@ class Flover:
         slot = C.c_int32(-2)
         _check(load_library().flover_add_request(self._ctx, req_id, p.ctypes.data, len(p), max_new_tokens,
                                                  C.byref(slot)), self._ctx)
+        return slot.value
+
+    def add_request_cached(self, req_id: int, context_len: int, next_token: int, max_new_tokens: int) -> int:
+        slot = C.c_int32(-2)
+        _check(load_library().flover_add_request_cached(self._ctx, req_id, context_len, next_token, max_new_tokens,
+                                                        C.byref(slot)), self._ctx)
         return slot.value
 
     def step(self, want_logits: bool = False) -> StepOut:
@@ -328,3 +338,9 @@ def k_gemm(x: torch.Tensor, W, out: Optional[torch.Tensor] = None, workspace: Op
                                         workspace.data_ptr(), workspace.numel(), _stream_ptr()))
     torch.cuda.current_stream().synchronize()
     return out
+
+
+def k_copy_probe(dst: torch.Tensor, src: torch.Tensor):
+    assert dst.is_contiguous() and src.is_contiguous() and dst.numel() * dst.element_size() == src.numel() * src.element_size()
+    _check(load_library().flover_k_copy_probe(dst.data_ptr(), src.data_ptr(), src.numel() * src.element_size(),
+                                              _stream_ptr()))

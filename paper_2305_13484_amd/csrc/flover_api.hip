@@ -170,7 +170,7 @@ size_t layout(flover_ctx* c, char* base) {
   c->kv = (char*)b.take(c->kv_bytes);
   const int R = (std::max(C, 128) + 127) / 128 * 128;
   c->rows_cap = R;
-  const int chunks = (S + flk::kAttnChunk - 1) / flk::kAttnChunk;
+  const int chunks = (S + flk::attn_chunk() - 1) / flk::attn_chunk();
   c->max_items = R * chunks;
   c->x = (float*)b.take((size_t)R * H * 4);
   c->h = b.take((size_t)R * H * e);
@@ -257,7 +257,7 @@ int run_rows(flover_ctx* c, const Row* rows, int n, bool want_tokens, float* log
     slot[i] = rows[i].slot;
     len[i] = rows[i].pos + 1;
     item0[i] = n_items;
-    const int nc = (len[i] + flk::kAttnChunk - 1) / flk::kAttnChunk;
+    const int nc = (len[i] + flk::attn_chunk() - 1) / flk::attn_chunk();
     nchunk[i] = nc;
     for (int ch = 0; ch < nc; ++ch) {
       items[2 * n_items] = i;
@@ -269,7 +269,7 @@ int run_rows(flover_ctx* c, const Row* rows, int n, bool want_tokens, float* log
   int* ds = c->d_stage;
   const int *d_tok = ds, *d_pos = ds + R, *d_slot = ds + 2 * R, *d_len = ds + 3 * R, *d_item0 = ds + 4 * R,
             *d_nchunk = ds + 5 * R;
-  flk::AttnWork aw{(const int2*)(ds + 6 * R), d_slot, d_len, d_item0, d_nchunk, c->pml, c->po, n_items, flk::kAttnChunk};
+  flk::AttnWork aw{(const int2*)(ds + 6 * R), d_slot, d_len, d_item0, d_nchunk, c->pml, c->po, n_items, flk::attn_chunk()};
 
   int launches = 0;
   const size_t ss_qkv = (size_t)n * c->p_qkv.ldc, ss_h = (size_t)n * c->p_o.ldc, ss_1 = (size_t)n * c->p_1.ldc,
@@ -458,11 +458,11 @@ int32_t flover_init(const flover_config* cfg, const flover_weights* w, flover_ct
       HIPTRY(flk::zero_fill(lw.w1, flk::gemm_tiled_bytes(f.dtype, gpt ? F : 2 * F, H), st));
       HIPTRY(flk::zero_fill(lw.w2, flk::gemm_tiled_bytes(f.dtype, H, F), st));
     }
-    HIPTRY(flk::retile(f.dtype, (const char*)w->wqkv + (size_t)l * 3 * H * H * e, 3 * H, H, lw.wqkv, 0, st));
-    HIPTRY(flk::retile(f.dtype, (const char*)w->wo + (size_t)l * H * H * e, H, H, lw.wo, 0, st));
-    HIPTRY(flk::retile(f.dtype, (const char*)w->w1 + (size_t)l * F * H * e, F, H, lw.w1, 0, st));
-    if (!gpt) HIPTRY(flk::retile(f.dtype, (const char*)w->wu + (size_t)l * F * H * e, F, H, lw.w1, F, st));
-    HIPTRY(flk::retile(f.dtype, (const char*)w->w2 + (size_t)l * H * F * e, H, F, lw.w2, 0, st));
+    HIPTRY(flk::retile(f.dtype, (const char*)w->wqkv + (size_t)l * 3 * H * H * e, 3 * H, H, lw.wqkv, 0, c->p_qkv.NT, st));
+    HIPTRY(flk::retile(f.dtype, (const char*)w->wo + (size_t)l * H * H * e, H, H, lw.wo, 0, c->p_o.NT, st));
+    HIPTRY(flk::retile(f.dtype, (const char*)w->w1 + (size_t)l * F * H * e, F, H, lw.w1, 0, c->p_1.NT, st));
+    if (!gpt) HIPTRY(flk::retile(f.dtype, (const char*)w->wu + (size_t)l * F * H * e, F, H, lw.w1, F, c->p_1.NT, st));
+    HIPTRY(flk::retile(f.dtype, (const char*)w->w2 + (size_t)l * H * F * e, H, F, lw.w2, 0, c->p_2.NT, st));
     if (gpt) {
       TRY(copy_in(c, lw.ln1_b, w->ln1_b ? (const char*)w->ln1_b + o1 : nullptr, (size_t)H * e, "ln1_b"));
       TRY(copy_in(c, lw.ln2_b, w->ln2_b ? (const char*)w->ln2_b + o1 : nullptr, (size_t)H * e, "ln2_b"));
@@ -484,7 +484,7 @@ int32_t flover_init(const flover_config* cfg, const flover_weights* w, flover_ct
     return bail(FLOVER_E_INVAL);
   }
   if (f.dtype != FLOVER_F32) HIPTRY(flk::zero_fill(c->wlm, flk::gemm_tiled_bytes(f.dtype, V, H), st));
-  HIPTRY(flk::retile(f.dtype, lm, V, H, c->wlm, 0, st));
+  HIPTRY(flk::retile(f.dtype, lm, V, H, c->wlm, 0, c->p_lm.NT, st));
   if (!gpt) {
     // cos/sin of pos * theta^(-2i/d), evaluated in double and rounded once to fp32
     const int half = f.head_dim / 2;
@@ -533,6 +533,28 @@ int32_t flover_add_request(flover_ctx* c, uint64_t req_id, const int32_t* prompt
   } else {
     c->reque.push_back(std::move(r));
   }
+  if (out_slot) *out_slot = slot;
+  return FLOVER_OK;
+}
+
+int32_t flover_add_request_cached(flover_ctx* c, uint64_t req_id, int32_t context_len, int32_t next_token,
+                                  int32_t max_new, int32_t* out_slot) {
+  if (!c) return FLOVER_E_INVAL;
+  const flover_config& f = c->cfg;
+  if (context_len < 0 || max_new < 1 || context_len + 1 + max_new > f.max_seq)
+    return fail(c, FLOVER_E_INVAL, "context_len / max_new_tokens out of range");
+  if (next_token < 0 || next_token >= f.vocab) return fail(c, FLOVER_E_INVAL, "token out of range");
+  if (known(c, req_id)) return fail(c, FLOVER_E_INVAL, "req_id already waiting or live");
+  if (!c->reque.empty()) return fail(c, FLOVER_E_FULL, "requests are waiting for a slot");
+  const int slot = place(c);
+  if (slot < 0) return fail(c, FLOVER_E_FULL, "no adjacent slot free");
+  Slot& s = c->slots[slot];
+  s.state = FLOVER_SLOT_READY;
+  s.req_id = req_id;
+  s.generated = 0;
+  s.max_new = max_new;
+  s.len = context_len;
+  s.next_token = next_token;
   if (out_slot) *out_slot = slot;
   return FLOVER_OK;
 }
@@ -748,7 +770,7 @@ int32_t flover_k_find_window(const int32_t* arr, int32_t n, int32_t* mem_offset,
 }
 
 static size_t attn_ws_layout(int M, int nh, int d, int max_len, size_t* o_items, size_t* o_pml, size_t* o_po) {
-  const int chunks = (max_len + flk::kAttnChunk - 1) / flk::kAttnChunk;
+  const int chunks = (max_len + flk::attn_chunk() - 1) / flk::attn_chunk();
   const size_t items = (size_t)M * chunks;
   size_t off = align_up((size_t)4 * M * 4, 256);
   *o_items = off;
@@ -792,7 +814,7 @@ int32_t flover_k_decode_attention(int32_t dtype, const void* q, const void* kcac
     h_slot[i] = slot[i];
     h_len[i] = len[i];
     h_item0[i] = (int)items.size() / 2;
-    const int nc = (len[i] + flk::kAttnChunk - 1) / flk::kAttnChunk;
+    const int nc = (len[i] + flk::attn_chunk() - 1) / flk::attn_chunk();
     h_nchunk[i] = nc;
     for (int ch = 0; ch < nc; ++ch) {
       items.push_back(i);
@@ -806,7 +828,7 @@ int32_t flover_k_decode_attention(int32_t dtype, const void* q, const void* kcac
   HIPCHK(nullptr, hipStreamSynchronize(st));
   int* ds = (int*)ws;
   flk::AttnWork aw{(const int2*)(ws + o_items), ds, ds + M, ds + 2 * M, ds + 3 * M, (float*)(ws + o_pml), (float*)(ws + o_po),
-                   (int)items.size() / 2, flk::kAttnChunk};
+                   (int)items.size() / 2, flk::attn_chunk()};
   HIPCHK(nullptr, flk::decode_attention(dtype, d, q, kcache, vcache, aw, M, nh, S, out, st));
   return FLOVER_OK;
 }
@@ -870,11 +892,27 @@ int32_t flover_k_gemm_retile(int32_t dtype, const void* W, int32_t N, int32_t K,
   if (dtype < FLOVER_F32 || dtype > FLOVER_BF16 || !W || !w_tiled || N < 1 || K < 32 || K % 32) return fail(nullptr, FLOVER_E_INVAL, "bad argument");
   hipStream_t st = (hipStream_t)stream;
   if (dtype != FLOVER_F32) HIPCHK(nullptr, flk::zero_fill(w_tiled, flk::gemm_tiled_bytes(dtype, N, K), st));
-  HIPCHK(nullptr, flk::retile(dtype, W, N, K, w_tiled, 0, st));
+  HIPCHK(nullptr, flk::retile(dtype, W, N, K, w_tiled, 0, flk::gemm_plan(dtype, N, K).NT, st));
   return FLOVER_OK;
 }
 
 }  // extern "C"
+
+namespace flk {
+__global__ __launch_bounds__(256) void copy_probe_kernel(const uint4* __restrict__ a, uint4* __restrict__ b, size_t n) {
+  size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+  const size_t stride = (size_t)gridDim.x * 256;
+  for (; i < n; i += stride) b[i] = a[i];
+}
+}  // namespace flk
+
+extern "C" int32_t flover_k_copy_probe(void* dst, const void* src, uint64_t bytes, void* stream) {
+  if (!dst || !src || bytes % 16) return fail(nullptr, FLOVER_E_INVAL, "bad argument");
+  if (bytes == 0) return FLOVER_OK;
+  flk::copy_probe_kernel<<<8192, 256, 0, (hipStream_t)stream>>>((const uint4*)src, (uint4*)dst, bytes / 16);
+  HIPCHK(nullptr, hipGetLastError());
+  return FLOVER_OK;
+}
 
 // y = sum of the split-K slices, in slice order (same order the step's consumers use)
 namespace flk {

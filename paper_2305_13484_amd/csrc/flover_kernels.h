@@ -19,8 +19,9 @@ struct GemmPlan {
 inline int part_ld(int N) { return (N + 3) / 4 * 4; }
 GemmPlan gemm_plan(int dtype, int N, int K);
 size_t gemm_tiled_bytes(int dtype, int N, int K);
-// Re-tile W [N][K] into `tiled` starting at output column n_off (multiple of 16) of a possibly larger matrix.
-hipError_t retile(int dtype, const void* W, int N, int K, void* tiled, int n_off, hipStream_t st);
+// Re-tile W [N][K] into `tiled` starting at output column n_off (multiple of 16) of a possibly larger matrix whose
+// plan uses NT n-tiles per column group.
+hipError_t retile(int dtype, const void* W, int N, int K, void* tiled, int n_off, int NT, hipStream_t st);
 hipError_t zero_fill(void* p, size_t bytes, hipStream_t st);
 // part[s][m][p.ldc] (slice stride in floats) = x[M][K] . W^T over slice s of K.
 hipError_t gemm(int dtype, const void* x, const void* w_tiled, int M, const GemmPlan& p, float* part,
@@ -54,7 +55,7 @@ struct AttnWork {          // all device pointers
   int n_items;
   int chunk;
 };
-constexpr int kAttnChunk = 256;   // positions per wave task; fixed, so chunking depends on a request's own length only
+int attn_chunk();   // positions per wave task; fixed for the process, so chunking depends on a request's own length only
 // ev0 / ev1 (optional) are recorded right before / after the streaming kernel (the merge kernel follows ev1).
 hipError_t decode_attention(int dtype, int d, const void* q, const void* kc, const void* vc, const AttnWork& w, int M,
                             int nh, int Smax, void* out, hipStream_t st, hipEvent_t ev0 = nullptr,

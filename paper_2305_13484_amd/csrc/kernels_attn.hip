@@ -11,6 +11,8 @@
 //   * work is flattened to (row, chunk of CHUNK positions) x head so a launch has thousands of equal-sized
 //     wave tasks however ragged the lengths are; chunking depends on the request's own length only, and a
 //     second tiny kernel merges a row's chunks in chunk order (results never depend on other rows).
+#include <cstdlib>
+
 #include "flover_dev.h"
 #include "flover_kernels.h"
 
@@ -18,7 +20,7 @@ namespace flk {
 
 // grid = (n_items, n_head / 4), block = 256: wave w handles head blockIdx.y * 4 + w of item blockIdx.x.
 // items[i] = (row, chunk).  Writes unnormalised partial (m, l, o[D]) per (item, head).
-template <int DT, int D>
+template <int DT, int D, int U>
 __global__ __launch_bounds__(256) void attn_partial_kernel(const void* __restrict__ q, const void* __restrict__ kc,
                                                            const void* __restrict__ vc, const int2* __restrict__ items,
                                                            const int* __restrict__ row_slot,
@@ -28,7 +30,6 @@ __global__ __launch_bounds__(256) void attn_partial_kernel(const void* __restric
   constexpr int EPL = 16 / EB;          // elements per lane
   constexpr int LPR = D / EPL;          // lanes per row
   constexpr int RPW = 64 / LPR;         // rows per wave load
-  constexpr int U = 4;                  // loads in flight per operand
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int item = blockIdx.x;
   const int hd = blockIdx.y * 4 + wave;
@@ -140,13 +141,26 @@ __global__ void attn_merge_kernel(const float* __restrict__ pml, const float* __
 
 // ---------------------------------------------------------------- host side
 
+int attn_chunk() {
+  static const int c = getenv("FLOVER_TUNE_CHUNK") ? atoi(getenv("FLOVER_TUNE_CHUNK")) : 256;
+  return c;
+}
+
 template <int DT, int D>
 static void launch_attn(const void* q, const void* kc, const void* vc, const AttnWork& w, int M, int nh, int Smax,
                         void* out, hipStream_t st, hipEvent_t ev0, hipEvent_t ev1) {
   const float scale = 1.0f / sqrtf((float)D);
   if (ev0) (void)hipEventRecord(ev0, st);
-  attn_partial_kernel<DT, D><<<dim3(w.n_items, nh / 4), 256, 0, st>>>(q, kc, vc, w.items, w.row_slot, w.row_len, nh, Smax,
-                                                                    w.chunk, scale, w.pml, w.po);
+  static const int tune_u = getenv("FLOVER_TUNE_U") ? atoi(getenv("FLOVER_TUNE_U")) : 4;
+  if (tune_u == 8)
+    attn_partial_kernel<DT, D, 8><<<dim3(w.n_items, nh / 4), 256, 0, st>>>(q, kc, vc, w.items, w.row_slot, w.row_len, nh,
+                                                                         Smax, w.chunk, scale, w.pml, w.po);
+  else if (tune_u == 2)
+    attn_partial_kernel<DT, D, 2><<<dim3(w.n_items, nh / 4), 256, 0, st>>>(q, kc, vc, w.items, w.row_slot, w.row_len, nh,
+                                                                         Smax, w.chunk, scale, w.pml, w.po);
+  else
+    attn_partial_kernel<DT, D, 4><<<dim3(w.n_items, nh / 4), 256, 0, st>>>(q, kc, vc, w.items, w.row_slot, w.row_len, nh,
+                                                                         Smax, w.chunk, scale, w.pml, w.po);
   if (ev1) (void)hipEventRecord(ev1, st);
   attn_merge_kernel<DT, D><<<dim3(M, nh), D, 0, st>>>(w.pml, w.po, w.row_item0, w.row_nchunk, nh, out);
 }

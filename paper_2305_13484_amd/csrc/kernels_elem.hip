@@ -70,25 +70,35 @@ __global__ __launch_bounds__(256) void embed_kernel(const void* __restrict__ wte
 // ---------------------------------------------------------------- residual add + norm
 // x[m] += sum_s part[s][m] + bias   (skipped when part == nullptr), then
 // h[m] = LayerNorm(x[m]) * g + b   (RMS == 0)   or   x[m] / rms(x[m]) * g   (RMS == 1), rounded to dtype.
-// grid = M, block = 256, 4 consecutive elements per thread and pass; H <= 8192, H % 4 == 0.  part rows have length ldp.
+// grid = M, block = 1024, 4 consecutive elements per thread and pass (2 passes cover H <= 8192); H % 4 == 0.
+// part rows have length ldp.  All slice loads of a pass are issued before the first addition (S <= 8 at a time).
 template <int DT, int RMS>
-__global__ __launch_bounds__(256) void add_norm_kernel(float* __restrict__ x, const float* __restrict__ part, int S,
-                                                       size_t stride, int ldp, const void* __restrict__ bias,
-                                                       const void* __restrict__ g, const void* __restrict__ b,
-                                                       void* __restrict__ h, int H, float eps) {
-  __shared__ float red[4];
+__global__ __launch_bounds__(1024) void add_norm_kernel(float* __restrict__ x, const float* __restrict__ part, int S,
+                                                        size_t stride, int ldp, const void* __restrict__ bias,
+                                                        const void* __restrict__ g, const void* __restrict__ b,
+                                                        void* __restrict__ h, int H, float eps) {
+  __shared__ float red[16];
   const int m = blockIdx.x;
-  constexpr int PER = 8;
+  constexpr int PER = 2;
   f32x4_t v[PER];
   float sum = 0.f;
 #pragma unroll
   for (int c = 0; c < PER; ++c) {
-    const int i = (threadIdx.x + c * 256) * 4;
+    const int i = (threadIdx.x + c * 1024) * 4;
     v[c] = f32x4_t{0.f, 0.f, 0.f, 0.f};
     if (i < H) {
       f32x4_t t = *(const f32x4_t*)(x + (size_t)m * H + i);
       if (part) {
-        f32x4_t a = psum4(part, S, stride, (size_t)m * ldp + i);
+        const float* p = part + (size_t)m * ldp + i;
+        f32x4_t a = ld4(p);
+        for (int s0 = 1; s0 < S; s0 += 8) {
+          f32x4_t pv[8];
+#pragma unroll
+          for (int j = 0; j < 8; ++j) pv[j] = ld4(p + (size_t)min(s0 + j, S - 1) * stride);
+#pragma unroll
+          for (int j = 0; j < 8; ++j)
+            if (s0 + j < S) a += pv[j];
+        }
         if (bias) a += ldv4<DT>(bias, i);
         t += a;
         *(f32x4_t*)(x + (size_t)m * H + i) = t;
@@ -97,7 +107,7 @@ __global__ __launch_bounds__(256) void add_norm_kernel(float* __restrict__ x, co
       sum += RMS ? (t[0] * t[0] + t[1] * t[1]) + (t[2] * t[2] + t[3] * t[3]) : (t[0] + t[1]) + (t[2] + t[3]);
     }
   }
-  sum = block_sum<4>(sum, red);
+  sum = block_sum<16>(sum, red);
   float mean = 0.f, inv;
   if (RMS) {
     inv = 1.0f / sqrtf(sum / (float)H + eps);
@@ -106,16 +116,16 @@ __global__ __launch_bounds__(256) void add_norm_kernel(float* __restrict__ x, co
     float sq = 0.f;
 #pragma unroll
     for (int c = 0; c < PER; ++c)
-      if ((threadIdx.x + c * 256) * 4 < H) {
+      if ((threadIdx.x + c * 1024) * 4 < H) {
         const f32x4_t dlt = v[c] - mean;
         sq += (dlt[0] * dlt[0] + dlt[1] * dlt[1]) + (dlt[2] * dlt[2] + dlt[3] * dlt[3]);
       }
-    sq = block_sum<4>(sq, red);
+    sq = block_sum<16>(sq, red);
     inv = 1.0f / sqrtf(sq / (float)H + eps);
   }
 #pragma unroll
   for (int c = 0; c < PER; ++c) {
-    const int i = (threadIdx.x + c * 256) * 4;
+    const int i = (threadIdx.x + c * 1024) * 4;
     if (i < H) {
       f32x4_t o = (v[c] - mean) * inv * ldv4<DT>(g, i);
       if (!RMS) o += ldv4<DT>(b, i);
@@ -127,41 +137,49 @@ __global__ __launch_bounds__(256) void add_norm_kernel(float* __restrict__ x, co
 // ---------------------------------------------------------------- QKV epilogue: bias, rotary, KV append
 // part: [S][M][ldp] rows (q | k | v).  For row m (slot, pos) and head hd: q -> qout[m][hd][:] (dtype),
 // k, v -> cache[slot][hd][pos][:] (dtype).  Rotary (LLaMA): pairs (i, i + d/2), cos/sin from a table [max_seq][d/2][2].
-// grid = M, block = n_head * d / 8: thread (hd, j) owns elements 4j..4j+3 and their partners 4j + d/2 .. of q, k and v.
+// grid = (M, 3): blockIdx.y picks q, k or v; block = n_head * d / 8: thread (hd, j) owns elements 4j..4j+3 and their
+// partners 4j + d/2 .. of its vector.
 template <int DT>
 __global__ void qkv_post_kernel(const float* __restrict__ part, int S, size_t stride, int ldp,
                                 const void* __restrict__ bias, const float* __restrict__ rope_cs,
                                 const int* __restrict__ slot, const int* __restrict__ pos, void* __restrict__ qout,
                                 void* __restrict__ kcache, void* __restrict__ vcache, int H, int nh, int d, int Smax) {
-  const int m = blockIdx.x, half = d >> 1, tph = d >> 3;
+  const int m = blockIdx.x, which = blockIdx.y, half = d >> 1, tph = d >> 3;
   const int hd = threadIdx.x / tph, i = (threadIdx.x - hd * tph) * 4;
-  const size_t row = (size_t)m * ldp;
-  const int c0 = hd * d + i, c1 = c0 + half;
-  f32x4_t q0 = psum4(part, S, stride, row + c0), q1 = psum4(part, S, stride, row + c1);
-  f32x4_t k0 = psum4(part, S, stride, row + H + c0), k1 = psum4(part, S, stride, row + H + c1);
-  f32x4_t v0 = psum4(part, S, stride, row + 2 * H + c0), v1 = psum4(part, S, stride, row + 2 * H + c1);
-  if (bias) {
-    q0 += ldv4<DT>(bias, c0); q1 += ldv4<DT>(bias, c1);
-    k0 += ldv4<DT>(bias, H + c0); k1 += ldv4<DT>(bias, H + c1);
-    v0 += ldv4<DT>(bias, 2 * H + c0); v1 += ldv4<DT>(bias, 2 * H + c1);
+  const int c0 = which * H + hd * d + i, c1 = c0 + half;
+  const float* p0 = part + (size_t)m * ldp + c0;
+  const float* p1 = part + (size_t)m * ldp + c1;
+  f32x4_t a0 = ld4(p0), a1 = ld4(p1);
+  for (int s0 = 1; s0 < S; s0 += 8) {
+    f32x4_t u0[8], u1[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      const size_t o = (size_t)min(s0 + j, S - 1) * stride;
+      u0[j] = ld4(p0 + o);
+      u1[j] = ld4(p1 + o);
+    }
+#pragma unroll
+    for (int j = 0; j < 8; ++j)
+      if (s0 + j < S) { a0 += u0[j]; a1 += u1[j]; }
   }
+  if (bias) { a0 += ldv4<DT>(bias, c0); a1 += ldv4<DT>(bias, c1); }
   const int p = pos[m];
-  if (rope_cs) {
+  if (rope_cs && which < 2) {
     const float* t = rope_cs + ((size_t)p * half + i) * 2;
     const f32x4_t t0 = ld4(t), t1 = ld4(t + 4);          // (cos, sin) of 4 consecutive pairs
     const f32x4_t cs = {t0[0], t0[2], t1[0], t1[2]}, sn = {t0[1], t0[3], t1[1], t1[3]};
-    const f32x4_t a = q0 * cs - q1 * sn, bq = q1 * cs + q0 * sn;
-    q0 = a; q1 = bq;
-    const f32x4_t c = k0 * cs - k1 * sn, e = k1 * cs + k0 * sn;
-    k0 = c; k1 = e;
+    const f32x4_t r0 = a0 * cs - a1 * sn, r1 = a1 * cs + a0 * sn;
+    a0 = r0; a1 = r1;
   }
-  stv4<DT>(qout, (size_t)m * H + c0, q0);
-  stv4<DT>(qout, (size_t)m * H + c1, q1);
-  const size_t kv = (((size_t)slot[m] * nh + hd) * Smax + p) * d;
-  stv4<DT>(kcache, kv + i, k0);
-  stv4<DT>(kcache, kv + i + half, k1);
-  stv4<DT>(vcache, kv + i, v0);
-  stv4<DT>(vcache, kv + i + half, v1);
+  if (which == 0) {
+    stv4<DT>(qout, (size_t)m * H + hd * d + i, a0);
+    stv4<DT>(qout, (size_t)m * H + hd * d + i + half, a1);
+  } else {
+    void* cache = which == 1 ? kcache : vcache;
+    const size_t kv = (((size_t)slot[m] * nh + hd) * Smax + p) * d;
+    stv4<DT>(cache, kv + i, a0);
+    stv4<DT>(cache, kv + i + half, a1);
+  }
 }
 
 // ---------------------------------------------------------------- MLP activation
@@ -245,9 +263,9 @@ hipError_t add_norm(int dtype, bool rms, float* x, const float* part, int S, siz
                     const void* g, const void* b, void* h, int M, int H, float eps, hipStream_t st) {
   if (M <= 0) return hipSuccess;
   if (rms) {
-    FLK_DT_SWITCH(dtype, (add_norm_kernel<DT, 1><<<M, 256, 0, st>>>(x, part, S, stride, ldp, bias, g, b, h, H, eps)));
+    FLK_DT_SWITCH(dtype, (add_norm_kernel<DT, 1><<<M, 1024, 0, st>>>(x, part, S, stride, ldp, bias, g, b, h, H, eps)));
   } else {
-    FLK_DT_SWITCH(dtype, (add_norm_kernel<DT, 0><<<M, 256, 0, st>>>(x, part, S, stride, ldp, bias, g, b, h, H, eps)));
+    FLK_DT_SWITCH(dtype, (add_norm_kernel<DT, 0><<<M, 1024, 0, st>>>(x, part, S, stride, ldp, bias, g, b, h, H, eps)));
   }
   return hipGetLastError();
 }
@@ -256,7 +274,7 @@ hipError_t qkv_post(int dtype, const float* part, int S, size_t stride, int ldp,
                     const int* slot, const int* pos, void* q, void* kcache, void* vcache, int M, int H, int nh, int d,
                     int Smax, hipStream_t st) {
   if (M <= 0) return hipSuccess;
-  FLK_DT_SWITCH(dtype, (qkv_post_kernel<DT><<<M, nh * d / 8, 0, st>>>(part, S, stride, ldp, bias, rope_cs, slot, pos, q,
+  FLK_DT_SWITCH(dtype, (qkv_post_kernel<DT><<<dim3(M, 3), nh * d / 8, 0, st>>>(part, S, stride, ldp, bias, rope_cs, slot, pos, q,
                                                                            kcache, vcache, H, nh, d, Smax)));
   return hipGetLastError();
 }

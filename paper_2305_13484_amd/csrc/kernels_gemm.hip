@@ -4,7 +4,9 @@
 // The work is HBM-bound for M up to a few hundred (M flop per weight byte), so the design goal is to stream W
 // at full bandwidth:
 //   * W is re-tiled once at init into MFMA operand order: tile (n-tile of 16 columns, k-block of 32) is 1 KiB,
-//     lane l holds W[n0 + l%16][k0 + 8*(l/16) .. +8], so every wave load is one contiguous, fully used 1 KiB.
+//     lane l holds W[n0 + l%16][k0 + 8*(l/16) .. +8], so every wave load is one contiguous, fully used 1 KiB;
+//     tiles are ordered [column group of NT n-tiles][k-block][n-tile in group], so the K slice a wave streams is
+//     one contiguous run of memory (NT KiB per k-block).
 //   * a wave owns 32 or 64 output columns (2 or 4 n-tiles) x one K slice x all rows of its row block; up to 32 rows
 //     the rows' operand comes straight from L2/L1 (no LDS, no barriers); above that it is staged through LDS once
 //     per block and shared by the block's 4 waves.
@@ -24,7 +26,7 @@ namespace flk {
 // ---------------------------------------------------------------- re-tiling (init time)
 
 __global__ void retile16_kernel(const uint16_t* __restrict__ W, u32x4_t* __restrict__ wt, int N, int K, int KB,
-                                int ntile0, long total) {
+                                int ntile0, int NT, long total) {
   long i = (long)blockIdx.x * blockDim.x + threadIdx.x;
   if (i >= total) return;
   int lane = (int)(i & 63);
@@ -35,7 +37,8 @@ __global__ void retile16_kernel(const uint16_t* __restrict__ W, u32x4_t* __restr
   int k = kb * 32 + (lane >> 4) * 8;
   u32x4_t v = {0u, 0u, 0u, 0u};
   if (n < N) v = *(const u32x4_t*)(W + (size_t)n * K + k);
-  wt[((size_t)(ntile0 + ntile) * KB + kb) * 64 + lane] = v;
+  const int tile = ntile0 + ntile, g = tile / NT, tt = tile - g * NT;
+  wt[(((size_t)g * KB + kb) * NT + tt) * 64 + lane] = v;
 }
 
 // ---------------------------------------------------------------- 16-bit MFMA kernel
@@ -47,12 +50,14 @@ template <int DT> __device__ __forceinline__ f32x4_t mfma16(const u32x4_t& a, co
     return __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(f16x8_t, a), __builtin_bit_cast(f16x8_t, b), c, 0, 0, 0);
 }
 
-// ---- small M (<= 32 rows): 4 independent waves per block, no LDS, no barriers.
-// grid = (ceil(ngroups/4), S, 1), block = 256; a wave owns NT n-tiles (16*NT columns) x one K slice x 16*MT rows.
-template <int DT, int MT, int NT, int PF>
+// ---- direct variant: 4 independent waves per block, no LDS, no barriers; the rows' operand comes straight from L2/L1.
+// grid = (ceil(ngroups/4), S, row blocks), block = 256; a wave owns NT n-tiles (16*NT columns) x one K slice x 16*MT rows.
+// W is prefetched PFW k-blocks ahead, x PFA k-blocks ahead (PFW % PFA == 0).
+template <int DT, int MT, int NT, int PFW, int PFA>
 __global__ __launch_bounds__(256) void gemm16_direct_kernel(const uint16_t* __restrict__ x, const u32x4_t* __restrict__ wt,
                                                             float* __restrict__ part, int M, int N, int K, int ngroups,
                                                             int KB, int kbs, size_t slice_stride, int ldc) {
+  static_assert(PFW % PFA == 0, "ring shapes");
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int g = blockIdx.x * 4 + wave;
   if (g >= ngroups) return;
@@ -67,33 +72,37 @@ __global__ __launch_bounds__(256) void gemm16_direct_kernel(const uint16_t* __re
 #pragma unroll
     for (int t = 0; t < NT; ++t) acc[i][t] = f32x4_t{0.f, 0.f, 0.f, 0.f};
 
-  const u32x4_t* wp = wt + ((size_t)(g * NT) * KB) * 64 + lane;                  // + t*KB*64 + kb*64
+  const u32x4_t* wp = wt + ((size_t)g * KB) * NT * 64 + lane;                    // + (kb*NT + t)*64
   const uint16_t* xp = x + (size_t)(m0 + (lane & 15)) * K + (lane >> 4) * 8;     // + i*16*K + kb*32
-  const size_t wtile = (size_t)KB * 64;
 
-  u32x4_t bq[PF][NT], aq[PF][MT];
+  u32x4_t bq[PFW][NT], aq[PFA][MT];
 #pragma unroll
-  for (int j = 0; j < PF; ++j) {
+  for (int j = 0; j < PFW; ++j) {
     const int kk = min(kb0 + j, kb1 - 1);
 #pragma unroll
-    for (int t = 0; t < NT; ++t) bq[j][t] = __builtin_nontemporal_load(wp + t * wtile + (size_t)kk * 64);
+    for (int t = 0; t < NT; ++t) bq[j][t] = __builtin_nontemporal_load(wp + ((size_t)kk * NT + t) * 64);
+  }
+#pragma unroll
+  for (int j = 0; j < PFA; ++j) {
+    const int kk = min(kb0 + j, kb1 - 1);
 #pragma unroll
     for (int i = 0; i < MT; ++i) aq[j][i] = *(const u32x4_t*)(xp + (size_t)i * 16 * K + kk * 32);
   }
-  for (int kb = kb0; kb < kb1; kb += PF) {
+  for (int kb = kb0; kb < kb1; kb += PFW) {
 #pragma unroll
-    for (int j = 0; j < PF; ++j) {
+    for (int j = 0; j < PFW; ++j) {
       if (kb + j < kb1) {
 #pragma unroll
         for (int i = 0; i < MT; ++i)
 #pragma unroll
-          for (int t = 0; t < NT; ++t) acc[i][t] = mfma16<DT>(aq[j][i], bq[j][t], acc[i][t]);
+          for (int t = 0; t < NT; ++t) acc[i][t] = mfma16<DT>(aq[j % PFA][i], bq[j][t], acc[i][t]);
       }
-      const int kk = min(kb + j + PF, kb1 - 1);      // tail re-reads the last block (in bounds, unused)
+      const int kw = min(kb + j + PFW, kb1 - 1);      // tail re-reads the last block (in bounds, unused)
 #pragma unroll
-      for (int t = 0; t < NT; ++t) bq[j][t] = __builtin_nontemporal_load(wp + t * wtile + (size_t)kk * 64);
+      for (int t = 0; t < NT; ++t) bq[j][t] = __builtin_nontemporal_load(wp + ((size_t)kw * NT + t) * 64);
+      const int ka = min(kb + j + PFA, kb1 - 1);
 #pragma unroll
-      for (int i = 0; i < MT; ++i) aq[j][i] = *(const u32x4_t*)(xp + (size_t)i * 16 * K + kk * 32);
+      for (int i = 0; i < MT; ++i) aq[j % PFA][i] = *(const u32x4_t*)(xp + (size_t)i * 16 * K + ka * 32);
     }
   }
   float* out = part + (size_t)s * slice_stride;
@@ -110,17 +119,19 @@ __global__ __launch_bounds__(256) void gemm16_direct_kernel(const uint16_t* __re
     }
 }
 
-// ---- larger M (33..128 rows per block): the rows' operand is staged through LDS once per block and shared by the
-// 4 waves (each wave owns its own NT n-tiles and streams their W tiles from HBM into registers, one chunk ahead).
+// ---- larger M (17..128 rows per block): the rows' operand is staged through LDS once per block and shared by the
+// 4 waves (each wave owns its own NT n-tiles and streams their W tiles from HBM into registers, PF k-blocks ahead).
 // LDS holds the x tile in MFMA fragment order ([k-block][m-tile][lane] x 16 B), so every ds_read_b128 of a fragment
-// is 1 KiB contiguous and bank-conflict free.  Double-buffered, one barrier per chunk of KC k-blocks.
+// is 1 KiB contiguous and bank-conflict free.  Double-buffered chunks of KC k-blocks, one barrier per chunk.
 // The per-(m, n) arithmetic (MFMA sequence over k) is identical to the direct kernel's.
-template <int DT, int MT, int NT, int KC>
+template <int DT, int MT, int NT, int KC, int PF>
 __global__ __launch_bounds__(256) void gemm16_lds_kernel(const uint16_t* __restrict__ x, const u32x4_t* __restrict__ wt,
                                                          float* __restrict__ part, int M, int N, int K, int ngroups,
                                                          int KB, int kbs, size_t slice_stride, int ldc) {
+  static_assert(PF % KC == 0, "ring shape");
   __shared__ u32x4_t lds[2][KC * MT * 64];
-  constexpr int FPW = KC * MT / 4;               // fragments each wave stages per chunk
+  constexpr int FPW = (KC * MT + 3) / 4;         // fragments each wave stages per chunk (surplus ones are skipped)
+  constexpr int CPR = PF / KC;                   // chunks per turn of the W ring
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int g = blockIdx.x * 4 + wave;
   const int gl = min(g, ngroups - 1);            // surplus waves repeat the last group (they still serve the barriers)
@@ -136,54 +147,60 @@ __global__ __launch_bounds__(256) void gemm16_lds_kernel(const uint16_t* __restr
 #pragma unroll
     for (int t = 0; t < NT; ++t) acc[i][t] = f32x4_t{0.f, 0.f, 0.f, 0.f};
 
-  const u32x4_t* wp = wt + ((size_t)(gl * NT) * KB) * 64 + lane;
+  const u32x4_t* wp = wt + ((size_t)gl * KB) * NT * 64 + lane;
   const uint16_t* xp = x + (size_t)(m0 + (lane & 15)) * K + (lane >> 4) * 8;
-  const size_t wtile = (size_t)KB * 64;
 
-  u32x4_t bq[KC][NT], areg[FPW];
+  u32x4_t bq[PF][NT], areg[FPW];
 #pragma unroll
-  for (int j = 0; j < KC; ++j) {
+  for (int j = 0; j < PF; ++j) {
     const int kk = min(kb0 + j, kb1 - 1);
 #pragma unroll
-    for (int t = 0; t < NT; ++t) bq[j][t] = __builtin_nontemporal_load(wp + t * wtile + (size_t)kk * 64);
+    for (int t = 0; t < NT; ++t) bq[j][t] = __builtin_nontemporal_load(wp + ((size_t)kk * NT + t) * 64);
   }
   auto load_a = [&](int chunk) {
 #pragma unroll
     for (int j = 0; j < FPW; ++j) {
-      const int f = wave + 4 * j, kc = f / MT, i = f - kc * MT;
+      const int f = min(wave + 4 * j, KC * MT - 1), kc = f / MT, i = f - kc * MT;
       const int kk = min(kb0 + chunk * KC + kc, kb1 - 1);
       areg[j] = *(const u32x4_t*)(xp + (size_t)i * 16 * K + kk * 32);
     }
   };
   auto store_a = [&](int buf) {
 #pragma unroll
-    for (int j = 0; j < FPW; ++j) lds[buf][(wave + 4 * j) * 64 + lane] = areg[j];
+    for (int j = 0; j < FPW; ++j)
+      if (wave + 4 * j < KC * MT) lds[buf][(wave + 4 * j) * 64 + lane] = areg[j];
   };
   load_a(0);
   store_a(0);
   __syncthreads();
-  for (int c = 0; c < nchunks; ++c) {
-    const bool more = c + 1 < nchunks;
-    if (more) load_a(c + 1);
-    const u32x4_t* la = lds[c & 1];
+  for (int c0 = 0; c0 < nchunks; c0 += CPR) {
 #pragma unroll
-    for (int kc = 0; kc < KC; ++kc) {
-      const int kb = kb0 + c * KC + kc;
-      if (kb < kb1) {
-        u32x4_t af[MT];
+    for (int cc = 0; cc < CPR; ++cc) {
+      const int c = c0 + cc;
+      if (c < nchunks) {                          // uniform over the block
+        const bool more = c + 1 < nchunks;
+        if (more) load_a(c + 1);
+        const u32x4_t* la = lds[c & 1];
 #pragma unroll
-        for (int i = 0; i < MT; ++i) af[i] = la[(kc * MT + i) * 64 + lane];
+        for (int kc = 0; kc < KC; ++kc) {
+          const int kb = kb0 + c * KC + kc;
+          if (kb < kb1) {
+            u32x4_t af[MT];
 #pragma unroll
-        for (int i = 0; i < MT; ++i)
+            for (int i = 0; i < MT; ++i) af[i] = la[(kc * MT + i) * 64 + lane];
 #pragma unroll
-          for (int t = 0; t < NT; ++t) acc[i][t] = mfma16<DT>(af[i], bq[kc][t], acc[i][t]);
+            for (int i = 0; i < MT; ++i)
+#pragma unroll
+              for (int t = 0; t < NT; ++t) acc[i][t] = mfma16<DT>(af[i], bq[cc * KC + kc][t], acc[i][t]);
+          }
+          const int kk = min(kb + PF, kb1 - 1);
+#pragma unroll
+          for (int t = 0; t < NT; ++t) bq[cc * KC + kc][t] = __builtin_nontemporal_load(wp + ((size_t)kk * NT + t) * 64);
+        }
+        if (more) store_a((c + 1) & 1);
+        __syncthreads();
       }
-      const int kk = min(kb + KC, kb1 - 1);
-#pragma unroll
-      for (int t = 0; t < NT; ++t) bq[kc][t] = __builtin_nontemporal_load(wp + t * wtile + (size_t)kk * 64);
     }
-    if (more) store_a((c + 1) & 1);
-    __syncthreads();
   }
   if (g >= ngroups) return;
   float* out = part + (size_t)s * slice_stride;
@@ -250,13 +267,14 @@ GemmPlan gemm_plan(int dtype, int N, int K) {
   }
   p.Npad = (N + 63) / 64 * 64;
   p.KB = K / 32;
-  // Everything below is a function of (N, K) only, never of the number of live rows.
-  // wide matrices: a wave owns 64 columns; narrow ones 32, so that enough waves exist without deep K splits
-  p.NT = tune_env("FLOVER_TUNE_NT", N >= 8192 ? 4 : 2);
+  // Everything below is a function of (N, K) only, never of the number of live rows.  A wave owns 64 columns; K is
+  // split just enough for about 800 waves (3 per CU, each streaming a contiguous run of W with a deep prefetch ring):
+  // more slices would only add partial-sum traffic.
+  p.NT = tune_env("FLOVER_TUNE_NT", 4);
   const int ngroups = p.Npad / (16 * p.NT);
-  const int target = tune_env("FLOVER_TUNE_WAVES", 1536);
-  int S = (target + ngroups - 1) / ngroups;
-  int maxS = std::min(tune_env("FLOVER_TUNE_MAXS", 8), p.KB / 8);
+  const int target = tune_env("FLOVER_TUNE_WAVES", 800);
+  int S = (target + ngroups / 2) / ngroups;
+  int maxS = std::min(tune_env("FLOVER_TUNE_MAXS", 16), p.KB / 8);
   if (maxS < 1) maxS = 1;
   if (S > maxS) S = maxS;
   if (S < 1) S = 1;
@@ -271,40 +289,46 @@ size_t gemm_tiled_bytes(int dtype, int N, int K) {
   return Npad * K * 2;
 }
 
-hipError_t retile(int dtype, const void* W, int N, int K, void* tiled, int n_off, hipStream_t st) {
+hipError_t retile(int dtype, const void* W, int N, int K, void* tiled, int n_off, int NT, hipStream_t st) {
   if (dtype == DT_F32)
     return hipMemcpyAsync((char*)tiled + (size_t)n_off * K * 4, W, (size_t)N * K * 4, hipMemcpyDeviceToDevice, st);
   const int KB = K / 32;
   const int ntiles = (N + 15) / 16;
   const long total = (long)ntiles * KB * 64;
   retile16_kernel<<<dim3((unsigned)((total + 255) / 256)), 256, 0, st>>>((const uint16_t*)W, (u32x4_t*)tiled, N, K, KB,
-                                                                         n_off / 16, total);
+                                                                         n_off / 16, NT, total);
   return hipGetLastError();
 }
 
 hipError_t zero_fill(void* p, size_t bytes, hipStream_t st) { return hipMemsetAsync(p, 0, bytes, st); }
 
-template <int DT, int MT, int NT, int PF>
+template <int DT, int MT, int NT, int PFW, int PFA>
 static void launch_direct(const void* x, const void* wt, float* part, int M, const GemmPlan& p, size_t ss, hipStream_t st) {
   const int ngroups = p.Npad / (16 * NT);
   dim3 grid((ngroups + 3) / 4, p.S, (M + 16 * MT - 1) / (16 * MT));
-  gemm16_direct_kernel<DT, MT, NT, PF><<<grid, 256, 0, st>>>((const uint16_t*)x, (const u32x4_t*)wt, part, M, p.N, p.K,
+  gemm16_direct_kernel<DT, MT, NT, PFW, PFA><<<grid, 256, 0, st>>>((const uint16_t*)x, (const u32x4_t*)wt, part, M, p.N, p.K,
                                                              ngroups, p.KB, p.kbs, ss, p.ldc);
 }
 template <int DT, int MT, int NT>
 static void launch_lds(const void* x, const void* wt, float* part, int M, const GemmPlan& p, size_t ss, hipStream_t st) {
   const int ngroups = p.Npad / (16 * NT);
   dim3 grid((ngroups + 3) / 4, p.S, (M + 16 * MT - 1) / (16 * MT));
-  gemm16_lds_kernel<DT, MT, NT, 4><<<grid, 256, 0, st>>>((const uint16_t*)x, (const u32x4_t*)wt, part, M, p.N, p.K, ngroups,
+  gemm16_lds_kernel<DT, MT, NT, 2, 4><<<grid, 256, 0, st>>>((const uint16_t*)x, (const u32x4_t*)wt, part, M, p.N, p.K, ngroups,
                                                          p.KB, p.kbs, ss, p.ldc);
 }
 
 template <int DT, int NT>
 static void dispatch16(const void* x, const void* wt, float* part, int M, const GemmPlan& p, size_t ss, hipStream_t st) {
-  if (M <= 16) launch_direct<DT, 1, NT, 8>(x, wt, part, M, p, ss, st);
-  else if (M <= 32) launch_direct<DT, 2, NT, 6>(x, wt, part, M, p, ss, st);
-  else if (M <= 64) launch_lds<DT, 4, NT>(x, wt, part, M, p, ss, st);
-  else launch_lds<DT, 8, NT>(x, wt, part, M, p, ss, st);
+  static const int bigm = tune_env("FLOVER_TUNE_BIGM_DIRECT", 0);
+  if (M <= 16) launch_direct<DT, 1, NT, 8, 8>(x, wt, part, M, p, ss, st);
+  else if (M <= 32) launch_lds<DT, 2, NT>(x, wt, part, M, p, ss, st);
+  else if (M <= 64) {
+    if (bigm) launch_direct<DT, 4, NT, 6, 3>(x, wt, part, M, p, ss, st);
+    else launch_lds<DT, 4, NT>(x, wt, part, M, p, ss, st);
+  } else {
+    if (bigm) launch_direct<DT, 8, NT, 4, 2>(x, wt, part, M, p, ss, st);
+    else launch_lds<DT, 8, NT>(x, wt, part, M, p, ss, st);
+  }
 }
 
 hipError_t gemm(int dtype, const void* x, const void* wt, int M, const GemmPlan& p, float* part, size_t slice_stride,
