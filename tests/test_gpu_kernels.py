@@ -197,3 +197,11 @@ def test_compact_benchmark_shape():
     assert torch.equal(after[untouched], sums[untouched])
     del cache
     torch.cuda.empty_cache()
+
+
+def test_copy_probe_copies():
+    src = torch.arange(1 << 20, dtype=torch.int32, device="cuda")
+    dst = torch.zeros_like(src)
+    fl.k_copy_probe(dst, src)
+    torch.cuda.synchronize()
+    assert torch.equal(dst, src)

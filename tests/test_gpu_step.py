@@ -188,3 +188,48 @@ def test_errors_are_reported_not_thrown_across_the_abi():
     assert empty.step().n_live == 0                  # nothing live is not an error
     assert empty.reorder_evict().moves == []
     empty.close()
+
+
+def test_cached_context_join_equals_real_preprocessing():
+    """flover_add_request_cached (profiler hook): joining on a cache that really holds the context gives bit-identical
+    logits to the normal path; bad arguments are rejected."""
+    import paper_2305_13484_amd as fl
+    cfg = synth.small_llama16(synth.DT_BF16)
+    w = to_device(synth.make_weights(cfg, 21))
+    prompt = np.random.default_rng(1).integers(0, cfg.V, size=23).astype(np.int32)
+    a = fl.Flover(cfg, w)
+    a.add_request(7, prompt, 6)
+    ref = [a.step(want_logits=True).logits[0].clone() for _ in range(6)]
+    a.reorder_evict()
+    # the slot (0) still holds the prompt's cache rows: join again without pre-processing
+    assert a.add_request_cached(8, len(prompt) - 1, int(prompt[-1]), 6) == 0
+    got = [a.step(want_logits=True).logits[0].clone() for _ in range(6)]
+    assert all(torch.equal(x, y) for x, y in zip(ref, got))
+    with pytest.raises(fl.FloverError):
+        a.add_request_cached(9, cfg.S, 1, 4)
+    with pytest.raises(fl.FloverError):
+        a.add_request_cached(9, 4, cfg.V, 4)
+    a.close()
+
+
+def test_kernel_timing_profile_counts_step_launches():
+    import paper_2305_13484_amd as fl
+    cfg = synth.small_llama16(synth.DT_BF16)
+    w = to_device(synth.make_weights(cfg, 22))
+    srv = fl.Flover(cfg, w)
+    srv.set_profile(2)
+    srv.add_request(1, [5, 6, 7, 8], 3)
+    srv.add_request(2, [9], 3)
+    for _ in range(3):
+        srv.step()
+    p = srv.get_profile()
+    e = 2
+    assert p["attention"]["launches"] == 3 * cfg.L            # pre-processing passes are not counted
+    lens = [(3 + i + 1) + (0 + i + 1) for i in range(3)]      # rows of cache attended to per step
+    assert p["attention"]["bytes"] == cfg.L * sum(lens) * 2 * cfg.H * e
+    assert p["gemm_qkv"]["launches"] == 3 * cfg.L and p["gemm_lm"]["launches"] == 3
+    assert p["attention"]["ms"] > 0
+    srv.set_profile(0)
+    srv.step()
+    assert srv.get_profile()["attention"]["launches"] == 0
+    srv.close()
