@@ -95,15 +95,15 @@ def run_stream(srv, cfg, reqs, max_steps, cached=False):
 
 
 def cpu_baseline(cfg_full, weights_dev, reqs, budget_rows=14):
-    """The oracle as it stands, timed on this machine's host cores on a bounded sample of the same workload: the first two
-    requests of the stream with prompts cut to their last 4 tokens, 4 fused steps at full depth and width."""
+    """The oracle as it stands, timed on this machine's host cores on a bounded sample of the same workload: the first three
+    requests of the stream with prompts cut to their last 4 tokens, 5 fused steps at full depth and width."""
     import dataclasses
     import numpy as np
     from oracle import oracle as orc
     cfg = dataclasses.replace(cfg_full, C=2, S=64)
     w = {k: v.cpu() for k, v in weights_dev.items()}
     srv = orc.OracleServer(cfg, w)
-    n_req, n_steps, keep = 2, 4, 4
+    n_req, n_steps, keep = 3, 5, 4
     for r in reqs[:n_req]:
         srv.add_request(r.req_id, np.asarray(r.prompt[-keep:]), n_steps)
     t0 = time.perf_counter()
@@ -117,6 +117,21 @@ def cpu_baseline(cfg_full, weights_dev, reqs, budget_rows=14):
     return {"value": toks / dt, "unit": "tokens/s", "cores": orc.num_threads(), "kind": "oracle",
             "sample": "%d requests of the stream, prompts cut to their last %d tokens, %d fused steps at full depth "
                       "(%d layers) and width; %.1f s" % (n_req, keep, n_steps, cfg.L, dt)}
+
+
+def committed_traffic(kernel: str):
+    """HBM bytes per launch of `kernel` from the committed rocprofv3 --pmc summary of this workload (FETCH_SIZE and
+    WRITE_SIZE runs, scaled by the copy probe); None if the summary is absent."""
+    path = os.path.join(ROOT, "profiles", "c4_llama7b_first200steps_hbm_counters.txt")
+    if not os.path.exists(path):
+        return None
+    import re
+    for line in open(path):
+        m = re.match(r"#\s*%s: traffic_bytes_per_launch=(\d+) algorithmic_bytes_per_launch=(\d+)" % kernel, line)
+        if m:
+            return {"bytes_per_launch": int(m.group(1)), "algorithmic_bytes_per_launch_same_run": int(m.group(2)),
+                    "source": "profiles/c4_llama7b_first200steps_hbm_counters.txt"}
+    return None
 
 
 def main():
@@ -189,7 +204,8 @@ def main():
         ach = att["bytes"] / (att["ms"] * 1e-3) / 1e9
         roof = {"bound": "hbm", "kernel": "attn_partial_kernel (ragged decode attention, one launch per layer)",
                 "achieved": round(ach, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(ach / HBM_PEAK_GBS, 4),
-                "traffic": None, "launches": att["launches"], "avg_launch_us": round(1e3 * att["ms"] / att["launches"], 2),
+                "traffic": (committed_traffic("attn_partial_kernel") or {}).get("bytes_per_launch"),
+                "traffic_detail": committed_traffic("attn_partial_kernel"), "launches": att["launches"], "avg_launch_us": round(1e3 * att["ms"] / att["launches"], 2),
                 "avg_bytes_per_launch": att["bytes"] // att["launches"]}
     per = res["per_step"]
     tot_bytes = sum(b for _, _, b in per)

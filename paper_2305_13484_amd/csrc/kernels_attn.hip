@@ -11,8 +11,6 @@
 //   * work is flattened to (row, chunk of CHUNK positions) x head so a launch has thousands of equal-sized
 //     wave tasks however ragged the lengths are; chunking depends on the request's own length only, and a
 //     second tiny kernel merges a row's chunks in chunk order (results never depend on other rows).
-#include <cstdlib>
-
 #include "flover_dev.h"
 #include "flover_kernels.h"
 
@@ -125,42 +123,49 @@ template <int DT, int D>
 __global__ void attn_merge_kernel(const float* __restrict__ pml, const float* __restrict__ po,
                                   const int* __restrict__ row_item0, const int* __restrict__ row_nchunk, int nh,
                                   void* __restrict__ out) {
+  float red_m = 0.f;
   const int row = blockIdx.x, hd = blockIdx.y, i = threadIdx.x;
   const int it0 = row_item0[row], nc = row_nchunk[row];
-  float mt = -INFINITY;
-  for (int c = 0; c < nc; ++c) mt = fmaxf(mt, pml[((size_t)(it0 + c) * nh + hd) * 2]);
   float l = 0.f, o = 0.f;
-  for (int c = 0; c < nc; ++c) {
-    const size_t pi = (size_t)(it0 + c) * nh + hd;
-    const float w = __expf(pml[pi * 2] - mt);
-    l += w * pml[pi * 2 + 1];
-    o += w * po[pi * D + i];
+  for (int c0 = 0; c0 < nc; c0 += 8) {          // 8 chunks at a time: all loads first, then the arithmetic in chunk order
+    float mc[8], lc[8], oc[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      const size_t pi = (size_t)(it0 + min(c0 + j, nc - 1)) * nh + hd;
+      mc[j] = pml[pi * 2];
+      lc[j] = pml[pi * 2 + 1];
+      oc[j] = po[pi * D + i];
+    }
+    if (c0 == 0) {                                // the global maximum needs the m of every chunk
+      float mt = -INFINITY;
+#pragma unroll
+      for (int j = 0; j < 8; ++j)
+        if (j < nc) mt = fmaxf(mt, mc[j]);
+      for (int c = 8; c < nc; ++c) mt = fmaxf(mt, pml[((size_t)(it0 + c) * nh + hd) * 2]);
+      red_m = mt;
+    }
+#pragma unroll
+    for (int j = 0; j < 8; ++j)
+      if (c0 + j < nc) {
+        const float w = __expf(mc[j] - red_m);
+        l += w * lc[j];
+        o += w * oc[j];
+      }
   }
   st<DT>(out, ((size_t)row * nh + hd) * D + i, o / l);
 }
 
 // ---------------------------------------------------------------- host side
 
-int attn_chunk() {
-  static const int c = getenv("FLOVER_TUNE_CHUNK") ? atoi(getenv("FLOVER_TUNE_CHUNK")) : 256;
-  return c;
-}
+int attn_chunk() { return 256; }
 
 template <int DT, int D>
 static void launch_attn(const void* q, const void* kc, const void* vc, const AttnWork& w, int M, int nh, int Smax,
                         void* out, hipStream_t st, hipEvent_t ev0, hipEvent_t ev1) {
   const float scale = 1.0f / sqrtf((float)D);
   if (ev0) (void)hipEventRecord(ev0, st);
-  static const int tune_u = getenv("FLOVER_TUNE_U") ? atoi(getenv("FLOVER_TUNE_U")) : 4;
-  if (tune_u == 8)
-    attn_partial_kernel<DT, D, 8><<<dim3(w.n_items, nh / 4), 256, 0, st>>>(q, kc, vc, w.items, w.row_slot, w.row_len, nh,
-                                                                         Smax, w.chunk, scale, w.pml, w.po);
-  else if (tune_u == 2)
-    attn_partial_kernel<DT, D, 2><<<dim3(w.n_items, nh / 4), 256, 0, st>>>(q, kc, vc, w.items, w.row_slot, w.row_len, nh,
-                                                                         Smax, w.chunk, scale, w.pml, w.po);
-  else
-    attn_partial_kernel<DT, D, 4><<<dim3(w.n_items, nh / 4), 256, 0, st>>>(q, kc, vc, w.items, w.row_slot, w.row_len, nh,
-                                                                         Smax, w.chunk, scale, w.pml, w.po);
+  attn_partial_kernel<DT, D, 4><<<dim3(w.n_items, nh / 4), 256, 0, st>>>(q, kc, vc, w.items, w.row_slot, w.row_len, nh, Smax,
+                                                                       w.chunk, scale, w.pml, w.po);
   if (ev1) (void)hipEventRecord(ev1, st);
   attn_merge_kernel<DT, D><<<dim3(M, nh), D, 0, st>>>(w.pml, w.po, w.row_item0, w.row_nchunk, nh, out);
 }

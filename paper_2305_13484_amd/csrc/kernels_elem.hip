@@ -80,13 +80,17 @@ __global__ __launch_bounds__(1024) void add_norm_kernel(float* __restrict__ x, c
   __shared__ float red[16];
   const int m = blockIdx.x;
   constexpr int PER = 2;
-  f32x4_t v[PER];
+  f32x4_t v[PER], gv[PER], bv[PER];
   float sum = 0.f;
 #pragma unroll
   for (int c = 0; c < PER; ++c) {
     const int i = (threadIdx.x + c * 1024) * 4;
     v[c] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+    gv[c] = v[c];
+    bv[c] = v[c];
     if (i < H) {
+      gv[c] = ldv4<DT>(g, i);                     // issued early: needed only after the reductions
+      if (!RMS) bv[c] = ldv4<DT>(b, i);
       f32x4_t t = *(const f32x4_t*)(x + (size_t)m * H + i);
       if (part) {
         const float* p = part + (size_t)m * ldp + i;
@@ -127,8 +131,8 @@ __global__ __launch_bounds__(1024) void add_norm_kernel(float* __restrict__ x, c
   for (int c = 0; c < PER; ++c) {
     const int i = (threadIdx.x + c * 1024) * 4;
     if (i < H) {
-      f32x4_t o = (v[c] - mean) * inv * ldv4<DT>(g, i);
-      if (!RMS) o += ldv4<DT>(b, i);
+      f32x4_t o = (v[c] - mean) * inv * gv[c];
+      if (!RMS) o += bv[c];
       stv4<DT>(h, (size_t)m * H + i, o);
     }
   }
@@ -149,6 +153,14 @@ __global__ void qkv_post_kernel(const float* __restrict__ part, int S, size_t st
   const int c0 = which * H + hd * d + i, c1 = c0 + half;
   const float* p0 = part + (size_t)m * ldp + c0;
   const float* p1 = part + (size_t)m * ldp + c1;
+  const int p = pos[m];
+  const bool rot = rope_cs && which < 2;
+  f32x4_t t0 = {1.f, 0.f, 1.f, 0.f}, t1 = t0;          // (cos, sin) of 4 consecutive pairs, fetched early
+  if (rot) {
+    const float* t = rope_cs + ((size_t)p * half + i) * 2;
+    t0 = ld4(t);
+    t1 = ld4(t + 4);
+  }
   f32x4_t a0 = ld4(p0), a1 = ld4(p1);
   for (int s0 = 1; s0 < S; s0 += 8) {
     f32x4_t u0[8], u1[8];
@@ -163,10 +175,7 @@ __global__ void qkv_post_kernel(const float* __restrict__ part, int S, size_t st
       if (s0 + j < S) { a0 += u0[j]; a1 += u1[j]; }
   }
   if (bias) { a0 += ldv4<DT>(bias, c0); a1 += ldv4<DT>(bias, c1); }
-  const int p = pos[m];
-  if (rope_cs && which < 2) {
-    const float* t = rope_cs + ((size_t)p * half + i) * 2;
-    const f32x4_t t0 = ld4(t), t1 = ld4(t + 4);          // (cos, sin) of 4 consecutive pairs
+  if (rot) {
     const f32x4_t cs = {t0[0], t0[2], t1[0], t1[2]}, sn = {t0[1], t0[3], t1[1], t1[3]};
     const f32x4_t r0 = a0 * cs - a1 * sn, r1 = a1 * cs + a0 * sn;
     a0 = r0; a1 = r1;

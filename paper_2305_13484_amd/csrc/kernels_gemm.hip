@@ -16,7 +16,6 @@
 //   * MFMA v_mfma_f32_16x16x32_{bf16,f16}: A = 16 rows of x, B = 16 columns of W, 32-deep.
 // fp32 models (tiny configurations only) use a plain FMA kernel on the untiled matrix.
 #include <algorithm>
-#include <cstdlib>
 
 #include "flover_dev.h"
 #include "flover_kernels.h"
@@ -130,7 +129,7 @@ __global__ __launch_bounds__(256) void gemm16_lds_kernel(const uint16_t* __restr
                                                          int KB, int kbs, size_t slice_stride, int ldc) {
   static_assert(PF % KC == 0, "ring shape");
   __shared__ u32x4_t lds[2][KC * MT * 64];
-  constexpr int FPW = (KC * MT + 3) / 4;         // fragments each wave stages per chunk (surplus ones are skipped)
+  constexpr int FPW = (KC * MT + 3) / 4;         // 1 KiB pieces each wave stages per chunk (surplus ones are skipped)
   constexpr int CPR = PF / KC;                   // chunks per turn of the W ring
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int g = blockIdx.x * 4 + wave;
@@ -147,7 +146,7 @@ __global__ __launch_bounds__(256) void gemm16_lds_kernel(const uint16_t* __restr
 #pragma unroll
     for (int t = 0; t < NT; ++t) acc[i][t] = f32x4_t{0.f, 0.f, 0.f, 0.f};
 
-  const u32x4_t* wp = wt + ((size_t)gl * KB) * NT * 64 + lane;
+  const u32x4_t* wp = wt + ((size_t)gl * KB) * NT * 64 + lane;                   // + (kb*NT + t)*64
   const uint16_t* xp = x + (size_t)(m0 + (lane & 15)) * K + (lane >> 4) * 8;
 
   u32x4_t bq[PF][NT], areg[FPW];
@@ -157,7 +156,7 @@ __global__ __launch_bounds__(256) void gemm16_lds_kernel(const uint16_t* __restr
 #pragma unroll
     for (int t = 0; t < NT; ++t) bq[j][t] = __builtin_nontemporal_load(wp + ((size_t)kk * NT + t) * 64);
   }
-  auto load_a = [&](int chunk) {
+  auto load_a = [&](int chunk) {      // one fragment = 16 rows x 64 B per wave load
 #pragma unroll
     for (int j = 0; j < FPW; ++j) {
       const int f = min(wave + 4 * j, KC * MT - 1), kc = f / MT, i = f - kc * MT;
@@ -195,7 +194,8 @@ __global__ __launch_bounds__(256) void gemm16_lds_kernel(const uint16_t* __restr
           }
           const int kk = min(kb + PF, kb1 - 1);
 #pragma unroll
-          for (int t = 0; t < NT; ++t) bq[cc * KC + kc][t] = __builtin_nontemporal_load(wp + ((size_t)kk * NT + t) * 64);
+          for (int t = 0; t < NT; ++t)
+            bq[cc * KC + kc][t] = __builtin_nontemporal_load(wp + ((size_t)kk * NT + t) * 64);
         }
         if (more) store_a((c + 1) & 1);
         __syncthreads();
@@ -247,11 +247,6 @@ __global__ __launch_bounds__(256) void gemm32_kernel(const float* __restrict__ x
 
 // ---------------------------------------------------------------- host side
 
-static int tune_env(const char* name, int dflt) {
-  const char* v = getenv(name);
-  return v ? atoi(v) : dflt;
-}
-
 GemmPlan gemm_plan(int dtype, int N, int K) {
   GemmPlan p{};
   p.N = N;
@@ -270,11 +265,11 @@ GemmPlan gemm_plan(int dtype, int N, int K) {
   // Everything below is a function of (N, K) only, never of the number of live rows.  A wave owns 64 columns; K is
   // split just enough for about 800 waves (3 per CU, each streaming a contiguous run of W with a deep prefetch ring):
   // more slices would only add partial-sum traffic.
-  p.NT = tune_env("FLOVER_TUNE_NT", 4);
+  p.NT = 4;
   const int ngroups = p.Npad / (16 * p.NT);
-  const int target = tune_env("FLOVER_TUNE_WAVES", 800);
+  const int target = 800;
   int S = (target + ngroups / 2) / ngroups;
-  int maxS = std::min(tune_env("FLOVER_TUNE_MAXS", 16), p.KB / 8);
+  int maxS = std::min(16, p.KB / 8);
   if (maxS < 1) maxS = 1;
   if (S > maxS) S = maxS;
   if (S < 1) S = 1;
@@ -314,21 +309,15 @@ static void launch_lds(const void* x, const void* wt, float* part, int M, const 
   const int ngroups = p.Npad / (16 * NT);
   dim3 grid((ngroups + 3) / 4, p.S, (M + 16 * MT - 1) / (16 * MT));
   gemm16_lds_kernel<DT, MT, NT, 2, 4><<<grid, 256, 0, st>>>((const uint16_t*)x, (const u32x4_t*)wt, part, M, p.N, p.K, ngroups,
-                                                         p.KB, p.kbs, ss, p.ldc);
+                                                            p.KB, p.kbs, ss, p.ldc);
 }
 
 template <int DT, int NT>
 static void dispatch16(const void* x, const void* wt, float* part, int M, const GemmPlan& p, size_t ss, hipStream_t st) {
-  static const int bigm = tune_env("FLOVER_TUNE_BIGM_DIRECT", 0);
   if (M <= 16) launch_direct<DT, 1, NT, 8, 8>(x, wt, part, M, p, ss, st);
   else if (M <= 32) launch_lds<DT, 2, NT>(x, wt, part, M, p, ss, st);
-  else if (M <= 64) {
-    if (bigm) launch_direct<DT, 4, NT, 6, 3>(x, wt, part, M, p, ss, st);
-    else launch_lds<DT, 4, NT>(x, wt, part, M, p, ss, st);
-  } else {
-    if (bigm) launch_direct<DT, 8, NT, 4, 2>(x, wt, part, M, p, ss, st);
-    else launch_lds<DT, 8, NT>(x, wt, part, M, p, ss, st);
-  }
+  else if (M <= 64) launch_lds<DT, 4, NT>(x, wt, part, M, p, ss, st);
+  else launch_lds<DT, 8, NT>(x, wt, part, M, p, ss, st);
 }
 
 hipError_t gemm(int dtype, const void* x, const void* wt, int M, const GemmPlan& p, float* part, size_t slice_stride,
