@@ -53,43 +53,57 @@ def step_bytes(cfg, lens):
 
 def run_stream(srv, cfg, reqs, max_steps, cached=False):
     """Drives the stream; returns totals.  Steps are bracketed by host clocks; flover_step and flover_reorder_evict
-    both return only after their GPU work has completed."""
+    both return only after their GPU work has completed.  Per-step bookkeeping is kept to array operations so the
+    Python driver adds as little as possible between two steps."""
+    import numpy as np
     import torch
     pending = sorted(reqs, key=lambda r: (r.arrival_step, r.req_id))
+    idx_of = {r.req_id: k for k, r in enumerate(reqs)}
+    lens = np.zeros(len(reqs), np.int64)          # cached rows per request (by index in reqs)
     i = done = s = 0
     tokens = 0
     t_steps = t_pre = 0.0
     moves = 0
     bytes_moved = 0
-    per_step = []
-    lens = {}
+    rec_n, rec_t, rec_len = [], [], []
+    clock = time.perf_counter
     torch.cuda.synchronize()
     while done < len(reqs) and (max_steps <= 0 or s < max_steps):
-        t0 = time.perf_counter()
-        while i < len(pending) and pending[i].arrival_step <= s:
-            r = pending[i]
-            if cached:
-                srv.add_request_cached(r.req_id, len(r.prompt) - 1, int(r.prompt[-1]), r.gen_len)
-            else:
-                srv.add_request(r.req_id, r.prompt, r.gen_len)
-            lens[r.req_id] = len(r.prompt) - 1
-            i += 1
-        torch.cuda.synchronize()
-        t1 = time.perf_counter()
+        if i < len(pending) and pending[i].arrival_step <= s:
+            t0 = clock()
+            while i < len(pending) and pending[i].arrival_step <= s:
+                r = pending[i]
+                if cached:
+                    srv.add_request_cached(r.req_id, len(r.prompt) - 1, int(r.prompt[-1]), r.gen_len)
+                else:
+                    srv.add_request(r.req_id, r.prompt, r.gen_len)
+                lens[idx_of[r.req_id]] = len(r.prompt) - 1
+                i += 1
+            torch.cuda.synchronize()
+            t_pre += clock() - t0
+        t1 = clock()
         out = srv.step()
         rr = srv.reorder_evict()
-        t2 = time.perf_counter()
-        t_pre += t1 - t0
-        t_steps += t2 - t1
-        live_lens = [lens[int(r)] for r in out.req_id]
-        per_step.append((out.n_live, t2 - t1, step_bytes(cfg, live_lens) if out.n_live else 0))
-        for r in out.req_id:
-            lens[int(r)] += 1
-        tokens += out.n_live
-        done += int(out.finished.sum())
+        dt = clock() - t1
+        t_steps += dt
+        n = out.n_live
+        if n:
+            ids = np.fromiter((idx_of[int(r)] for r in out.req_id), np.int64, n)
+            rec_len.append(int(lens[ids].sum()))
+            lens[ids] += 1
+            done += int(out.finished.sum())
+        else:
+            rec_len.append(0)
+        rec_n.append(n)
+        rec_t.append(dt)
+        tokens += n
         moves += len(rr.moves)
         bytes_moved += rr.bytes_moved
         s += 1
+    e = __import__("flover_synth").DTYPE_BYTES[cfg.dtype]
+    kvb = cfg.kv_bytes_per_token()
+    per_step = [(n, t, (cfg.weight_bytes_per_step() + (sl + n) * kvb + n * kvb + n * cfg.H * e + n * cfg.V * 4) if n else 0)
+                for n, t, sl in zip(rec_n, rec_t, rec_len)]
     return {"steps": s, "tokens": tokens, "t_steps": t_steps, "t_pre": t_pre, "moves": moves,
             "bytes_moved": bytes_moved, "per_step": per_step, "all_done": done == len(reqs)}
 
@@ -200,12 +214,14 @@ def main():
     total = res["t_steps"]
     att = prof["attention"]
     roof = None
+    # the committed byte counters were taken on this workload (first 200 steps, see profiles/); not on the others
+    traffic = committed_traffic("attn_partial_kernel") if (a.workload == "c4" and not a.layers and not a.requests) else None
     if att["launches"]:
         ach = att["bytes"] / (att["ms"] * 1e-3) / 1e9
         roof = {"bound": "hbm", "kernel": "attn_partial_kernel (ragged decode attention, one launch per layer)",
                 "achieved": round(ach, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(ach / HBM_PEAK_GBS, 4),
-                "traffic": (committed_traffic("attn_partial_kernel") or {}).get("bytes_per_launch"),
-                "traffic_detail": committed_traffic("attn_partial_kernel"), "launches": att["launches"], "avg_launch_us": round(1e3 * att["ms"] / att["launches"], 2),
+                "traffic": (traffic or {}).get("bytes_per_launch"), "traffic_detail": traffic,
+                "launches": att["launches"], "avg_launch_us": round(1e3 * att["ms"] / att["launches"], 2),
                 "avg_bytes_per_launch": att["bytes"] // att["launches"]}
     per = res["per_step"]
     tot_bytes = sum(b for _, _, b in per)

@@ -233,3 +233,72 @@ def test_kernel_timing_profile_counts_step_launches():
     srv.step()
     assert srv.get_profile()["attention"]["launches"] == 0
     srv.close()
+
+
+def test_gpt1p3b_shape_reduced_depth():
+    """The GPT-1.3B layer shape (hidden 2048, 16 heads, FFN 8192, vocab 50257 -- not a multiple of 16 --, fp16, biases,
+    learned positions, tied output projection) at 2 layers against the oracle."""
+    cfg = synth.gpt_1p3b(L=2, C=8)
+    cfg = dataclasses.replace(cfg, S=96)
+    print(cfg.name, flush=True)
+    w = synth.make_weights(cfg, 13)
+    reqs = synth.stream_small(5, cfg.V, n=5, arrive_hi=2, p_lo=2, p_hi=12, g_lo=2, g_hi=5)
+    ls = Lockstep(cfg, w)
+    ls.run(reqs)
+    print("1.3b-shape: steps", ls.steps, "max rel err", ls.max_err, "ties", ls.ties)
+    assert ls.max_err <= 2e-2
+    ls.close()
+
+
+def test_window_wraps_below_when_the_top_is_reached():
+    """Placement at lo-1 once hi == max_concurrency, full occupancy, and a request arriving while none can be placed."""
+    cfg = dataclasses.replace(synth.tiny_gpt(), C=4)
+    w = synth.make_weights(cfg, 6)
+    ls = Lockstep(cfg, w)
+    rng = np.random.default_rng(3)
+    mk = lambda rid, g: synth.Request(rid, 0, rng.integers(0, cfg.V, size=3).astype(np.int32), g)
+    for rid, g in ((0, 2), (1, 9), (2, 9), (3, 2)):
+        ls.add(mk(rid, g))
+    for _ in range(2):
+        ls.step()
+        ls.reorder()                       # after step 2: requests 0 and 3 finish -> window [1,3)
+    st = ls.gpu.state()
+    assert (st["lo"], st["hi"]) == (1, 3)
+    ls.add(mk(4, 5))                       # takes slot 3 (hi)
+    ls.add(mk(5, 5))                       # hi == C: takes slot 0 (lo - 1)
+    ls.add(mk(6, 3))                       # nothing free: waits
+    st = ls.gpu.state()
+    assert (st["lo"], st["hi"], st["waiting"]) == (0, 4, 1)
+    done = 0
+    while done < 5:
+        g, _ = ls.step()
+        done += int(g.finished.sum())
+        ls.reorder()
+    assert len(ls.tokens[6]) == 3
+    ls.close()
+
+
+def test_request_filling_its_slot_to_the_last_row():
+    cfg = dataclasses.replace(synth.tiny_llama(synth.DT_BF16), S=300)      # crosses the 256-position chunk boundary
+    w = synth.make_weights(cfg, 7)
+    P = 40
+    req = synth.Request(0, 0, np.random.default_rng(2).integers(0, cfg.V, size=P).astype(np.int32), cfg.S - P)
+    ls = Lockstep(cfg, w)
+    ls.run([req])
+    assert len(ls.tokens[0]) == cfg.S - P and ls.gpu.state()["hi"] == 0
+    ls.close()
+
+
+def test_llama30b_shape_one_layer():
+    """The 30B layer shape (hidden 6656, 52 heads, FFN 17920, vocab 32000, bf16): dimensions that are not powers of two,
+    one layer, a few rows against the oracle."""
+    cfg = synth.llama_30b(L=1, C=4)
+    cfg = dataclasses.replace(cfg, S=64)
+    print(cfg.name, flush=True)
+    w = synth.make_weights(cfg, 14)
+    reqs = synth.stream_small(6, cfg.V, n=3, arrive_hi=1, p_lo=2, p_hi=6, g_lo=2, g_hi=3)
+    ls = Lockstep(cfg, w)
+    ls.run(reqs)
+    print("30b-shape: steps", ls.steps, "max rel err", ls.max_err, "ties", ls.ties)
+    assert ls.max_err <= 2e-2
+    ls.close()
