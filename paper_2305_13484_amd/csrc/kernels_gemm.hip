@@ -118,21 +118,28 @@ __global__ __launch_bounds__(256) void gemm16_direct_kernel(const uint16_t* __re
     }
 }
 
-// ---- larger M (17..128 rows per block): the rows' operand is staged through LDS once per block and shared by the
-// 4 waves (each wave owns its own NT n-tiles and streams their W tiles from HBM into registers, PF k-blocks ahead).
+// ---- larger M (17..128 rows per block): the rows' operand is staged through LDS once per block and shared by its
+// waves; a block covers 4 column groups (256 columns), each group by NT/NTW waves that own NTW of its n-tiles and stream
+// their W tiles from HBM into registers, PF k-blocks ahead.  From 33 rows up two waves share a group (8 waves per
+// block): a single wave issues MFMAs at about 60% of the unit's rate, two waves per SIMD interleave and also hide each
+// other's LDS and memory waits.
 // LDS holds the x tile in MFMA fragment order ([k-block][m-tile][lane] x 16 B), so every ds_read_b128 of a fragment
 // is 1 KiB contiguous and bank-conflict free.  Double-buffered chunks of KC k-blocks, one barrier per chunk.
 // The per-(m, n) arithmetic (MFMA sequence over k) is identical to the direct kernel's.
-template <int DT, int MT, int NT, int KC, int PF>
-__global__ __launch_bounds__(256) void gemm16_lds_kernel(const uint16_t* __restrict__ x, const u32x4_t* __restrict__ wt,
-                                                         float* __restrict__ part, int M, int N, int K, int ngroups,
-                                                         int KB, int kbs, size_t slice_stride, int ldc) {
-  static_assert(PF % KC == 0, "ring shape");
+template <int DT, int MT, int NT, int NTW, int KC, int PF>
+__global__ __launch_bounds__(64 * 4 * (NT / NTW)) void gemm16_lds_kernel(const uint16_t* __restrict__ x,
+                                                                         const u32x4_t* __restrict__ wt,
+                                                                         float* __restrict__ part, int M, int N, int K,
+                                                                         int ngroups, int KB, int kbs,
+                                                                         size_t slice_stride, int ldc) {
+  static_assert(PF % KC == 0 && NT % NTW == 0, "ring and tile shapes");
+  constexpr int WPG = NT / NTW;                  // waves that share one column group, each taking NTW of its n-tiles
+  constexpr int NW = 4 * WPG;                    // waves per block: 4 column groups
   __shared__ u32x4_t lds[2][KC * MT * 64];
-  constexpr int FPW = (KC * MT + 3) / 4;         // 1 KiB pieces each wave stages per chunk (surplus ones are skipped)
+  constexpr int FPW = (KC * MT + NW - 1) / NW;   // fragments each wave stages per chunk (surplus ones are skipped)
   constexpr int CPR = PF / KC;                   // chunks per turn of the W ring
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  const int g = blockIdx.x * 4 + wave;
+  const int g = blockIdx.x * 4 + wave / WPG, sub = wave % WPG;
   const int gl = min(g, ngroups - 1);            // surplus waves repeat the last group (they still serve the barriers)
   const int s = blockIdx.y;
   const int m0 = blockIdx.z * (16 * MT);
@@ -140,26 +147,26 @@ __global__ __launch_bounds__(256) void gemm16_lds_kernel(const uint16_t* __restr
   const int kb1 = min(KB, kb0 + kbs);
   const int nchunks = (kb1 - kb0 + KC - 1) / KC;
 
-  f32x4_t acc[MT][NT];
+  f32x4_t acc[MT][NTW];
 #pragma unroll
   for (int i = 0; i < MT; ++i)
 #pragma unroll
-    for (int t = 0; t < NT; ++t) acc[i][t] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+    for (int t = 0; t < NTW; ++t) acc[i][t] = f32x4_t{0.f, 0.f, 0.f, 0.f};
 
-  const u32x4_t* wp = wt + ((size_t)gl * KB) * NT * 64 + lane;                   // + (kb*NT + t)*64
+  const u32x4_t* wp = wt + (((size_t)gl * KB) * NT + sub * NTW) * 64 + lane;     // + (kb*NT + t)*64
   const uint16_t* xp = x + (size_t)(m0 + (lane & 15)) * K + (lane >> 4) * 8;
 
-  u32x4_t bq[PF][NT], areg[FPW];
+  u32x4_t bq[PF][NTW], areg[FPW];
 #pragma unroll
   for (int j = 0; j < PF; ++j) {
     const int kk = min(kb0 + j, kb1 - 1);
 #pragma unroll
-    for (int t = 0; t < NT; ++t) bq[j][t] = __builtin_nontemporal_load(wp + ((size_t)kk * NT + t) * 64);
+    for (int t = 0; t < NTW; ++t) bq[j][t] = __builtin_nontemporal_load(wp + ((size_t)kk * NT + t) * 64);
   }
   auto load_a = [&](int chunk) {      // one fragment = 16 rows x 64 B per wave load
 #pragma unroll
     for (int j = 0; j < FPW; ++j) {
-      const int f = min(wave + 4 * j, KC * MT - 1), kc = f / MT, i = f - kc * MT;
+      const int f = min(wave + NW * j, KC * MT - 1), kc = f / MT, i = f - kc * MT;
       const int kk = min(kb0 + chunk * KC + kc, kb1 - 1);
       areg[j] = *(const u32x4_t*)(xp + (size_t)i * 16 * K + kk * 32);
     }
@@ -167,7 +174,7 @@ __global__ __launch_bounds__(256) void gemm16_lds_kernel(const uint16_t* __restr
   auto store_a = [&](int buf) {
 #pragma unroll
     for (int j = 0; j < FPW; ++j)
-      if (wave + 4 * j < KC * MT) lds[buf][(wave + 4 * j) * 64 + lane] = areg[j];
+      if (wave + NW * j < KC * MT) lds[buf][(wave + NW * j) * 64 + lane] = areg[j];
   };
   load_a(0);
   store_a(0);
@@ -190,11 +197,11 @@ __global__ __launch_bounds__(256) void gemm16_lds_kernel(const uint16_t* __restr
 #pragma unroll
             for (int i = 0; i < MT; ++i)
 #pragma unroll
-              for (int t = 0; t < NT; ++t) acc[i][t] = mfma16<DT>(af[i], bq[cc * KC + kc][t], acc[i][t]);
+              for (int t = 0; t < NTW; ++t) acc[i][t] = mfma16<DT>(af[i], bq[cc * KC + kc][t], acc[i][t]);
           }
           const int kk = min(kb + PF, kb1 - 1);
 #pragma unroll
-          for (int t = 0; t < NT; ++t)
+          for (int t = 0; t < NTW; ++t)
             bq[cc * KC + kc][t] = __builtin_nontemporal_load(wp + ((size_t)kk * NT + t) * 64);
         }
         if (more) store_a((c + 1) & 1);
@@ -207,8 +214,8 @@ __global__ __launch_bounds__(256) void gemm16_lds_kernel(const uint16_t* __restr
 #pragma unroll
   for (int i = 0; i < MT; ++i)
 #pragma unroll
-    for (int t = 0; t < NT; ++t) {
-      const int n = (g * NT + t) * 16 + (lane & 15);
+    for (int t = 0; t < NTW; ++t) {
+      const int n = (g * NT + sub * NTW + t) * 16 + (lane & 15);
 #pragma unroll
       for (int r = 0; r < 4; ++r) {
         const int m = m0 + i * 16 + (lane >> 4) * 4 + r;
@@ -304,20 +311,20 @@ static void launch_direct(const void* x, const void* wt, float* part, int M, con
   gemm16_direct_kernel<DT, MT, NT, PFW, PFA><<<grid, 256, 0, st>>>((const uint16_t*)x, (const u32x4_t*)wt, part, M, p.N, p.K,
                                                              ngroups, p.KB, p.kbs, ss, p.ldc);
 }
-template <int DT, int MT, int NT>
+template <int DT, int MT, int NT, int NTW, int PF>
 static void launch_lds(const void* x, const void* wt, float* part, int M, const GemmPlan& p, size_t ss, hipStream_t st) {
   const int ngroups = p.Npad / (16 * NT);
   dim3 grid((ngroups + 3) / 4, p.S, (M + 16 * MT - 1) / (16 * MT));
-  gemm16_lds_kernel<DT, MT, NT, 2, 4><<<grid, 256, 0, st>>>((const uint16_t*)x, (const u32x4_t*)wt, part, M, p.N, p.K, ngroups,
-                                                            p.KB, p.kbs, ss, p.ldc);
+  gemm16_lds_kernel<DT, MT, NT, NTW, 2, PF><<<grid, 64 * 4 * (NT / NTW), 0, st>>>((const uint16_t*)x, (const u32x4_t*)wt, part,
+                                                                                  M, p.N, p.K, ngroups, p.KB, p.kbs, ss, p.ldc);
 }
 
 template <int DT, int NT>
 static void dispatch16(const void* x, const void* wt, float* part, int M, const GemmPlan& p, size_t ss, hipStream_t st) {
   if (M <= 16) launch_direct<DT, 1, NT, 8, 8>(x, wt, part, M, p, ss, st);
-  else if (M <= 32) launch_lds<DT, 2, NT>(x, wt, part, M, p, ss, st);
-  else if (M <= 64) launch_lds<DT, 4, NT>(x, wt, part, M, p, ss, st);
-  else launch_lds<DT, 8, NT>(x, wt, part, M, p, ss, st);
+  else if (M <= 32) launch_lds<DT, 2, NT, NT, 4>(x, wt, part, M, p, ss, st);     // 4 waves, one per column group
+  else if (M <= 64) launch_lds<DT, 4, NT, 2, 4>(x, wt, part, M, p, ss, st);      // 8 waves, two per column group
+  else launch_lds<DT, 8, NT, 2, 4>(x, wt, part, M, p, ss, st);
 }
 
 hipError_t gemm(int dtype, const void* x, const void* wt, int M, const GemmPlan& p, float* part, size_t slice_stride,
