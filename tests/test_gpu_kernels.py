@@ -54,13 +54,15 @@ def test_gemm_row_result_does_not_depend_on_other_rows(dtype):
     assert torch.equal(alone[0], full[77])
 
 
-def test_gemm_full_size_sampled_columns():
-    """The 7B shapes the benchmark runs (rows = 128 live requests), sampled output columns from the oracle."""
+@pytest.mark.parametrize("M", [8, 24, 48, 128])
+def test_gemm_full_size_sampled_columns(M):
+    """The 7B shapes the benchmark runs, at row counts that select each kernel variant (<=16 direct, <=32 / <=64 / <=128
+    LDS-staged with 4 or 8 waves); sampled output columns from the oracle."""
     dtype = synth.DT_BF16
-    for (N, K) in [(12288, 4096), (4096, 11008), (32000, 4096)]:
-        print("gemm full", N, K, flush=True)
-        g = torch.Generator(device="cuda").manual_seed(N)
-        x = torch.randn((128, K), generator=g, device="cuda").to(TDT[dtype])
+    for (N, K) in [(12288, 4096), (4096, 11008), (22016, 4096), (32000, 4096)]:
+        print("gemm full", M, N, K, flush=True)
+        g = torch.Generator(device="cuda").manual_seed(N + M)
+        x = torch.randn((M, K), generator=g, device="cuda").to(TDT[dtype])
         W = (torch.randn((N, K), generator=g, device="cuda") * 0.02).to(TDT[dtype])
         got = fl.k_gemm(x, W)
         cols = np.random.default_rng(N).choice(N, size=24, replace=False)
@@ -70,6 +72,7 @@ def test_gemm_full_size_sampled_columns():
         bound = (xh.double().abs() @ Wh.double().abs().T).numpy()
         err = np.abs(got[:, torch.as_tensor(cols, device="cuda").long()].cpu().double().numpy() - ref)
         assert np.all(err <= 4e-6 * bound)
+        del W
 
 
 # ---------------------------------------------------------------- ragged decode attention
