@@ -278,7 +278,9 @@ def main():
     # warm-up: a throwaway stream of a few short requests through the same context
     if a.warmup > 0:
         rng = np.random.default_rng(1)
-        warm = [synth.Request(10 ** 6 + i, 0, rng.integers(0, cfg.V, size=200).astype(np.int32), a.warmup) for i in range(8)]
+        wp = min(200, cfg.S // 2)
+        warm = [synth.Request(10 ** 6 + i, 0, rng.integers(0, cfg.V, size=wp).astype(np.int32),
+                              max(1, min(a.warmup, cfg.S - wp - 1))) for i in range(min(8, cfg.C))]
         run_stream(srv, cfg, warm, 0, cached=a.cached_context)
 
     srv.set_profile(a.profile_level)
