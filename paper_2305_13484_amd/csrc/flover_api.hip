@@ -181,7 +181,7 @@ size_t layout(flover_ctx* c, char* base) {
   for (const flk::GemmPlan* p : {&c->p_qkv, &c->p_o, &c->p_1, &c->p_2, &c->p_lm}) pw = std::max(pw, (size_t)p->S * p->ldc);
   c->part = (float*)b.take(pw * R * 4);
   c->tok_out = (int*)b.take((size_t)R * 4);
-  c->stage_ints = (size_t)6 * R + (size_t)2 * c->max_items;
+  c->stage_ints = (size_t)6 * R + (size_t)6 * c->max_items;   // row arrays, (row, chunk) items, context-pass blocks
   c->d_stage = (int*)b.take(c->stage_ints * 4);
   c->pml = (float*)b.take((size_t)c->max_items * f.n_head * 2 * 4);
   c->po = (float*)b.take((size_t)c->max_items * f.n_head * f.head_dim * 4);
@@ -238,7 +238,7 @@ hipError_t timed_gemm(flover_ctx* c, int kind, const void* x, const void* w, int
 
 // One pass of the decoder over n rows: a single launch per operation covers all of them.
 // With want_tokens the final norm, output projection and argmax run and tok_out (device) holds the choices.
-int run_rows(flover_ctx* c, const Row* rows, int n, bool want_tokens, float* logits_out) {
+int run_rows(flover_ctx* c, const Row* rows, int n, bool want_tokens, float* logits_out, bool context_pass) {
   const flover_config& f = c->cfg;
   const int H = f.hidden, F = f.ffn, V = f.vocab, nh = f.n_head, d = f.head_dim, L = f.n_layer, R = c->rows_cap;
   const bool gpt = f.arch == FLOVER_ARCH_GPT;
@@ -265,11 +265,32 @@ int run_rows(flover_ctx* c, const Row* rows, int n, bool want_tokens, float* log
       ++n_items;
     }
   }
-  HIPCHK(c, hipMemcpyAsync(c->d_stage, hs, ((size_t)6 * R + (size_t)2 * n_items) * 4, hipMemcpyHostToDevice, st));
+  // context pass: runs of consecutive positions of one slot are served kPrefillQB query rows per wave
+  int n_blocks = 0;
+  int* blk = items + 2 * n_items;
+  if (context_pass) {
+    for (int i = 0; i < n;) {
+      int nr = 1;
+      while (nr < flk::kPrefillQB && i + nr < n && rows[i + nr].slot == rows[i].slot && rows[i + nr].pos == rows[i].pos + nr)
+        ++nr;
+      for (int ch = 0; ch < nchunk[i + nr - 1]; ++ch) {
+        blk[4 * n_blocks] = i;
+        blk[4 * n_blocks + 1] = nr;
+        blk[4 * n_blocks + 2] = ch;
+        blk[4 * n_blocks + 3] = 0;
+        ++n_blocks;
+      }
+      i += nr;
+    }
+  }
+  HIPCHK(c, hipMemcpyAsync(c->d_stage, hs, ((size_t)6 * R + (size_t)2 * n_items + (size_t)4 * n_blocks) * 4,
+                           hipMemcpyHostToDevice, st));
   int* ds = c->d_stage;
   const int *d_tok = ds, *d_pos = ds + R, *d_slot = ds + 2 * R, *d_len = ds + 3 * R, *d_item0 = ds + 4 * R,
             *d_nchunk = ds + 5 * R;
   flk::AttnWork aw{(const int2*)(ds + 6 * R), d_slot, d_len, d_item0, d_nchunk, c->pml, c->po, n_items, flk::attn_chunk()};
+  aw.blocks = (const int4*)(ds + 6 * R + 2 * n_items);
+  aw.n_blocks = n_blocks;
 
   int launches = 0;
   const size_t ss_qkv = (size_t)n * c->p_qkv.ldc, ss_h = (size_t)n * c->p_o.ldc, ss_1 = (size_t)n * c->p_1.ldc,
@@ -287,7 +308,9 @@ int run_rows(flover_ctx* c, const Row* rows, int n, bool want_tokens, float* log
     char* vl = kl + c->plane_bytes;
     HIPCHK(c, flk::qkv_post(f.dtype, c->part, c->p_qkv.S, ss_qkv, c->p_qkv.ldc, w.bqkv, c->rope_cs, d_slot, d_pos, c->q, kl, vl, n, H, nh,
                             d, f.max_seq, st));
-    {
+    if (context_pass) {
+      HIPCHK(c, flk::prefill_attention(f.dtype, d, c->q, kl, vl, aw, n, nh, f.max_seq, c->att, st));
+    } else {
       const int pi = prof_begin(c, FLOVER_PROF_ATTENTION, attn_bytes);
       HIPCHK(c, flk::decode_attention(f.dtype, d, c->q, kl, vl, aw, n, nh, f.max_seq, c->att, st,
                                       pi >= 0 ? c->ev[2 * pi] : nullptr, pi >= 0 ? c->ev[2 * pi + 1] : nullptr));
@@ -326,7 +349,7 @@ int preprocess(flover_ctx* c, int slot, const Waiting& r) {
     const int n = std::min(c->rows_cap, P - 1 - p0);
     rows.resize(n);
     for (int i = 0; i < n; ++i) rows[i] = Row{slot, r.prompt[p0 + i], p0 + i};
-    int rc = run_rows(c, rows.data(), n, false, nullptr);
+    int rc = run_rows(c, rows.data(), n, false, nullptr, true);
     if (rc != FLOVER_OK) return rc;
   }
   s.len = P - 1;
@@ -589,7 +612,7 @@ int32_t flover_step(flover_ctx* c, flover_step_out* out) {
   c->last_launches = 0;
   if (n == 0) return FLOVER_OK;
   c->in_step = true;
-  int rc = run_rows(c, rows.data(), (int)rows.size(), true, out->logits);
+  int rc = run_rows(c, rows.data(), (int)rows.size(), true, out->logits, false);
   c->in_step = false;
   if (rc != FLOVER_OK) return rc;
   c->last_launches = c->launches;

@@ -54,12 +54,19 @@ struct AttnWork {          // all device pointers
   float* po;               // [n_items][nh][d]
   int n_items;
   int chunk;
+  const int4* blocks = nullptr;   // pre-processing passes: (first row, rows <= kPrefillQB, chunk, -)
+  int n_blocks = 0;
 };
+constexpr int kPrefillQB = 8;     // query rows one wave serves in a pre-processing pass
 int attn_chunk();   // positions per wave task; fixed for the process, so chunking depends on a request's own length only
 // ev0 / ev1 (optional) are recorded right before / after the streaming kernel (the merge kernel follows ev1).
 hipError_t decode_attention(int dtype, int d, const void* q, const void* kc, const void* vc, const AttnWork& w, int M,
                             int nh, int Smax, void* out, hipStream_t st, hipEvent_t ev0 = nullptr,
                             hipEvent_t ev1 = nullptr);
+
+// Attention of a pre-processing pass: rows listed in w.blocks are runs of consecutive positions of one slot.
+hipError_t prefill_attention(int dtype, int d, const void* q, const void* kc, const void* vc, const AttnWork& w, int M,
+                             int nh, int Smax, void* out, hipStream_t st);
 
 // ---- memory shuffle copy
 constexpr int kCompactPiece = 16384;   // bytes per block

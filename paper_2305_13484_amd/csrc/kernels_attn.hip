@@ -155,6 +155,131 @@ __global__ void attn_merge_kernel(const float* __restrict__ pml, const float* __
   st<DT>(out, ((size_t)row * nh + hd) * D + i, o / l);
 }
 
+// ---------------------------------------------------------------- pre-processing variant (context decoder)
+// Rows of one pre-processing pass are consecutive positions of ONE slot, so neighbouring rows read almost the same
+// K/V rows.  Here a wave serves QB consecutive query rows at once: every K/V row it loads is used by all of them
+// (causal mask per query), which divides the cache traffic of the context pass by up to QB.  Same chunking, same
+// partial layout and the same merge kernel as above.
+// grid = (n_blocks, n_head / 4), block = 256.  blocks[b] = (first row, rows in block (<= QB), chunk, -).
+template <int DT, int D, int QB>
+__global__ __launch_bounds__(256) void attn_prefill_kernel(const void* __restrict__ q, const void* __restrict__ kc,
+                                                           const void* __restrict__ vc, const int4* __restrict__ blocks,
+                                                           const int* __restrict__ row_slot,
+                                                           const int* __restrict__ row_len,
+                                                           const int* __restrict__ row_item0,
+                                                           const int* __restrict__ row_nchunk, int nh, int Smax, int chunk,
+                                                           float scale, float* __restrict__ pml, float* __restrict__ po) {
+  constexpr int EB = (DT == DT_F32) ? 4 : 2;
+  constexpr int EPL = 16 / EB;
+  constexpr int LPR = D / EPL;
+  constexpr int RPW = 64 / LPR;
+  constexpr int U = 2;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int4 bk = blocks[blockIdx.x];
+  const int first = bk.x, nr = bk.y, ch = bk.z;
+  const int hd = blockIdx.y * 4 + wave;
+  const int slot = row_slot[first];
+  const int len0 = row_len[first];                          // rows are consecutive positions: len_i = len0 + i
+  const int j0 = ch * chunk, j1 = min(len0 + nr - 1, j0 + chunk);
+  const int grp = lane / LPR, li = lane % LPR;
+
+  float qf[QB][EPL];
+#pragma unroll
+  for (int i = 0; i < QB; ++i) {
+    const int r = first + min(i, nr - 1);
+    const u32x4_t qr = *(const u32x4_t*)((const char*)q + ((size_t)(r * nh + hd) * D + li * EPL) * EB);
+    unpack16<DT>(qr, qf[i]);
+#pragma unroll
+    for (int e = 0; e < EPL; ++e) qf[i][e] *= scale;
+  }
+  const size_t head_off = ((size_t)slot * nh + hd) * Smax * D * EB + (size_t)li * 16;
+  const char* kb = (const char*)kc + head_off;
+  const char* vb = (const char*)vc + head_off;
+
+  float m[QB], l[QB], o[QB][EPL];
+#pragma unroll
+  for (int i = 0; i < QB; ++i) {
+    m[i] = -INFINITY;
+    l[i] = 0.f;
+#pragma unroll
+    for (int e = 0; e < EPL; ++e) o[i][e] = 0.f;
+  }
+  for (int jb = j0; jb < j1; jb += RPW * U) {
+    u32x4_t kr[U], vr[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const int r = min(jb + u * RPW + grp, j1 - 1);
+      kr[u] = *(const u32x4_t*)(kb + (size_t)r * D * EB);
+      vr[u] = *(const u32x4_t*)(vb + (size_t)r * D * EB);
+    }
+    float kf[U][EPL], vf[U][EPL];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      unpack16<DT>(kr[u], kf[u]);
+      unpack16<DT>(vr[u], vf[u]);
+    }
+#pragma unroll
+    for (int i = 0; i < QB; ++i) {
+      float sc[U];
+      float tmax = -INFINITY;
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        float d0 = 0.f;
+#pragma unroll
+        for (int e = 0; e < EPL; ++e) d0 = fmaf(qf[i][e], kf[u][e], d0);
+        d0 = group_sum<LPR>(d0);
+        sc[u] = (jb + u * RPW + grp < min(len0 + i, j1) && i < nr) ? d0 : -INFINITY;   // causal: key < len_i
+        tmax = fmaxf(tmax, sc[u]);
+      }
+      const float mn = fmaxf(m[i], tmax);
+      const float ms = (mn == -INFINITY) ? 0.f : mn;
+      const float alpha = __expf(m[i] - ms);
+      l[i] *= alpha;
+#pragma unroll
+      for (int e = 0; e < EPL; ++e) o[i][e] *= alpha;
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        const float p = __expf(sc[u] - ms);
+        l[i] += p;
+#pragma unroll
+        for (int e = 0; e < EPL; ++e) o[i][e] = fmaf(p, vf[u][e], o[i][e]);
+      }
+      m[i] = mn;
+    }
+  }
+#pragma unroll
+  for (int i = 0; i < QB; ++i) {
+    float mi = m[i], lv = l[i];
+    if constexpr (RPW > 1) {
+      float mt = mi;
+#pragma unroll
+      for (int dlt = LPR; dlt < 64; dlt <<= 1) mt = fmaxf(mt, __shfl_xor(mt, dlt, 64));
+      const float w = (mi == -INFINITY) ? 0.f : __expf(mi - mt);
+      lv *= w;
+#pragma unroll
+      for (int e = 0; e < EPL; ++e) o[i][e] *= w;
+#pragma unroll
+      for (int dlt = LPR; dlt < 64; dlt <<= 1) {
+        lv += __shfl_xor(lv, dlt, 64);
+#pragma unroll
+        for (int e = 0; e < EPL; ++e) o[i][e] += __shfl_xor(o[i][e], dlt, 64);
+      }
+      mi = mt;
+    }
+    const int r = first + i;
+    if (i < nr && ch < row_nchunk[r] && grp == 0) {          // this chunk holds keys this query may see
+      const size_t pi = (size_t)(row_item0[r] + ch) * nh + hd;
+      float* op = po + pi * D + li * EPL;
+#pragma unroll
+      for (int e = 0; e < EPL; ++e) op[e] = o[i][e];
+      if (li == 0) {
+        pml[pi * 2] = mi;
+        pml[pi * 2 + 1] = lv;
+      }
+    }
+  }
+}
+
 // ---------------------------------------------------------------- host side
 
 int attn_chunk() { return 256; }
@@ -181,6 +306,30 @@ hipError_t decode_attention(int dtype, int d, const void* q, const void* kc, con
     if (dtype == DT_F32) launch_attn<DT_F32, 64>(q, kc, vc, w, M, nh, Smax, out, st, ev0, ev1);
     else if (dtype == DT_F16) launch_attn<DT_F16, 64>(q, kc, vc, w, M, nh, Smax, out, st, ev0, ev1);
     else launch_attn<DT_BF16, 64>(q, kc, vc, w, M, nh, Smax, out, st, ev0, ev1);
+  }
+  return hipGetLastError();
+}
+
+template <int DT, int D>
+static void launch_prefill(const void* q, const void* kc, const void* vc, const AttnWork& w, int M, int nh, int Smax,
+                           void* out, hipStream_t st) {
+  const float scale = 1.0f / sqrtf((float)D);
+  attn_prefill_kernel<DT, D, kPrefillQB><<<dim3(w.n_blocks, nh / 4), 256, 0, st>>>(
+      q, kc, vc, w.blocks, w.row_slot, w.row_len, w.row_item0, w.row_nchunk, nh, Smax, w.chunk, scale, w.pml, w.po);
+  attn_merge_kernel<DT, D><<<dim3(M, nh), D, 0, st>>>(w.pml, w.po, w.row_item0, w.row_nchunk, nh, out);
+}
+
+hipError_t prefill_attention(int dtype, int d, const void* q, const void* kc, const void* vc, const AttnWork& w, int M,
+                             int nh, int Smax, void* out, hipStream_t st) {
+  if (M <= 0 || w.n_blocks <= 0) return hipSuccess;
+  if (d == 128) {
+    if (dtype == DT_F32) launch_prefill<DT_F32, 128>(q, kc, vc, w, M, nh, Smax, out, st);
+    else if (dtype == DT_F16) launch_prefill<DT_F16, 128>(q, kc, vc, w, M, nh, Smax, out, st);
+    else launch_prefill<DT_BF16, 128>(q, kc, vc, w, M, nh, Smax, out, st);
+  } else {
+    if (dtype == DT_F32) launch_prefill<DT_F32, 64>(q, kc, vc, w, M, nh, Smax, out, st);
+    else if (dtype == DT_F16) launch_prefill<DT_F16, 64>(q, kc, vc, w, M, nh, Smax, out, st);
+    else launch_prefill<DT_BF16, 64>(q, kc, vc, w, M, nh, Smax, out, st);
   }
   return hipGetLastError();
 }

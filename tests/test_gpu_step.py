@@ -315,3 +315,20 @@ def test_fused_equals_alone_at_7b_width_many_rows():
         t1, l1 = gpu_run_stream(cfg, w, [synth.Request(r.req_id, 0, r.prompt, r.gen_len)])
         assert t1[r.req_id] == toks[r.req_id]
         assert torch.equal(torch.stack(l1[r.req_id]), torch.stack(logits[r.req_id]))
+
+
+@pytest.mark.parametrize("make", [lambda: synth.tiny_llama(synth.DT_BF16, C=4, S=700), lambda: synth.tiny_gpt(C=4, S=700),
+                                  lambda: synth.small_gpt16(synth.DT_F16, C=4, S=300)])
+def test_long_prompts_through_the_context_pass(make):
+    """Prompts long enough for several 512-row context passes, several 256-position chunks and ragged last query
+    blocks; every generated token's logits are compared with the oracle (which fills its cache one token at a time)."""
+    cfg = make()
+    w = synth.make_weights(cfg, 17)
+    rng = np.random.default_rng(8)
+    lens = [cfg.S - 40, 259, 9, 130] if cfg.S >= 600 else [cfg.S - 10, 259, 9]
+    reqs = [synth.Request(i, 0, rng.integers(0, cfg.V, size=p).astype(np.int32), 3) for i, p in enumerate(lens)]
+    ls = Lockstep(cfg, w)
+    ls.run(reqs)
+    print(cfg.name, "max rel err", ls.max_err, "ties", ls.ties)
+    assert ls.max_err <= TOL[cfg.dtype]
+    ls.close()
