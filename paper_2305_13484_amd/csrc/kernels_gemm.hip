@@ -131,7 +131,8 @@ __global__ __launch_bounds__(64 * 4 * (NT / NTW)) void gemm16_lds_kernel(const u
                                                                          const u32x4_t* __restrict__ wt,
                                                                          float* __restrict__ part, int M, int N, int K,
                                                                          int ngroups, int KB, int kbs,
-                                                                         size_t slice_stride, int ldc) {
+                                                                         size_t slice_stride, int ldc, int nx,
+                                                                         int nslices, int nz) {
   static_assert(PF % KC == 0 && NT % NTW == 0, "ring and tile shapes");
   constexpr int WPG = NT / NTW;                  // waves that share one column group, each taking NTW of its n-tiles
   constexpr int NW = 4 * WPG;                    // waves per block: 4 column groups
@@ -139,10 +140,16 @@ __global__ __launch_bounds__(64 * 4 * (NT / NTW)) void gemm16_lds_kernel(const u
   constexpr int FPW = (KC * MT + NW - 1) / NW;   // fragments each wave stages per chunk (surplus ones are skipped)
   constexpr int CPR = PF / KC;                   // chunks per turn of the W ring
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  const int g = blockIdx.x * 4 + wave / WPG, sub = wave % WPG;
+  // 1-D grid, XCD-aware: workgroup ids go round-robin over the 8 XCDs (each with its own L2), so the row blocks of one
+  // (column block, K slice) task are given ids 8 apart -- same XCD, dispatched back to back -- and the W tiles one of
+  // them pulls from HBM are L2 hits for the others.  With a single row block this is the identity mapping.
+  const int xcd = blockIdx.x & 7, qq = blockIdx.x >> 3;
+  const int zb = qq % nz, task = (qq / nz) * 8 + xcd;
+  if (task >= nx * nslices) return;              // padding of the grid (whole block)
+  const int bx = task % nx, s = task / nx;
+  const int g = bx * 4 + wave / WPG, sub = wave % WPG;
   const int gl = min(g, ngroups - 1);            // surplus waves repeat the last group (they still serve the barriers)
-  const int s = blockIdx.y;
-  const int m0 = blockIdx.z * (16 * MT);
+  const int m0 = zb * (16 * MT);
   const int kb0 = s * kbs;
   const int kb1 = min(KB, kb0 + kbs);
   const int nchunks = (kb1 - kb0 + KC - 1) / KC;
@@ -314,9 +321,10 @@ static void launch_direct(const void* x, const void* wt, float* part, int M, con
 template <int DT, int MT, int NT, int NTW, int PF>
 static void launch_lds(const void* x, const void* wt, float* part, int M, const GemmPlan& p, size_t ss, hipStream_t st) {
   const int ngroups = p.Npad / (16 * NT);
-  dim3 grid((ngroups + 3) / 4, p.S, (M + 16 * MT - 1) / (16 * MT));
-  gemm16_lds_kernel<DT, MT, NT, NTW, 2, PF><<<grid, 64 * 4 * (NT / NTW), 0, st>>>((const uint16_t*)x, (const u32x4_t*)wt, part,
-                                                                                  M, p.N, p.K, ngroups, p.KB, p.kbs, ss, p.ldc);
+  const int nx = (ngroups + 3) / 4, nz = (M + 16 * MT - 1) / (16 * MT);
+  const int tasks8 = (nx * p.S + 7) / 8 * 8;
+  gemm16_lds_kernel<DT, MT, NT, NTW, 2, PF><<<dim3(tasks8 * nz), 64 * 4 * (NT / NTW), 0, st>>>(
+      (const uint16_t*)x, (const u32x4_t*)wt, part, M, p.N, p.K, ngroups, p.KB, p.kbs, ss, p.ldc, nx, p.S, nz);
 }
 
 template <int DT, int NT>
