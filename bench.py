@@ -27,7 +27,10 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=0, help="timed steps (0 = the whole stream)")
     ap.add_argument("--warmup", type=int, default=8)
-    ap.add_argument("--workload", default="c4", choices=["c4", "c3", "c1", "c2"])
+    ap.add_argument("--workload", default="c4", choices=["c4", "c3", "c1", "c2", "poisson32"])
+    ap.add_argument("--lambda-ms", type=float, default=500.0,
+                    help="poisson32: mean inter-arrival gap in the paper's milliseconds (Section VI-C); converted to "
+                         "decode steps with the paper's 5800 ms per 512 iterations")
     ap.add_argument("--layers", type=int, default=0, help="override the layer count (debug only; reported)")
     ap.add_argument("--requests", type=int, default=0, help="override the number of requests (debug only; reported)")
     ap.add_argument("--profile-level", type=int, default=1)
@@ -36,6 +39,8 @@ def parse():
     ap.add_argument("--cached-context", action="store_true",
                     help="profiler runs: requests join with their context cache taken as present (no pre-processing "
                          "kernels), so every launch in the trace is a fused-iteration launch")
+    ap.add_argument("--shuffle-off", action="store_true",
+                    help="the variant without memory shuffle (Section VI-D): finished slots stay inside the window as holes")
     ap.add_argument("--copy-probe", type=int, default=0, metavar="MiB",
                     help="only run the plain copy kernel on MiB mebibytes, 10 times (reference for profiler byte counters)")
     return ap.parse_args()
@@ -256,6 +261,15 @@ def main():
         cfg = synth.gpt_1p3b(L=a.layers or 24)
         reqs = synth.stream_c3(a.seed, cfg.V, n=a.requests or 64)
         wl = "c3: GPT-1.3B shape fp16, 64 requests, Poisson(0.25/step) arrivals, prompts U{64..512}, generation U{32..1024}"
+    elif a.workload == "poisson32":
+        # Section VI-C: 32 requests of 512 output tokens, exponential inter-arrival gaps; LLaMA-7B shape, 32 slots
+        cfg = synth.llama_7b(L=a.layers or 32, C=32, S=1024)
+        gap_steps = a.lambda_ms / (5800.0 / 512.0)
+        arr = synth.exponential_gap_arrivals(int(a.lambda_ms), 32, gap_steps)
+        rng = np.random.default_rng(a.seed)
+        reqs = [synth.Request(i, int(t), rng.integers(0, cfg.V, size=128).astype(np.int32), 512) for i, t in enumerate(arr)]
+        wl = "poisson32: LLaMA-7B shape bf16, 32 requests x 512 tokens, exponential gaps, mean %.0f ms = %.1f steps" % (
+            a.lambda_ms, gap_steps)
     elif a.workload == "c1":
         cfg = synth.tiny_gpt()
         reqs = synth.stream_c1(a.seed, cfg.V)
@@ -268,7 +282,7 @@ def main():
     weights = synth.make_weights(cfg, a.seed, device="cuda")
     torch.cuda.synchronize()
     t_w = time.perf_counter() - t0
-    srv = fl.Flover(cfg, weights)
+    srv = fl.Flover(cfg, weights, shuffle_off=a.shuffle_off)
     cpu = None
     if not a.no_cpu_baseline:
         cpu = cpu_baseline(cfg, weights, reqs)
@@ -324,11 +338,13 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": synth.DTYPE_NAME[cfg.dtype],
         "data": "synthetic",
         "config": {"workload": wl, "layers": cfg.L, "requests": len(reqs), "whole_stream": res["all_done"],
-                   "seed": a.seed, "cached_context": a.cached_context},
+                   "seed": a.seed, "cached_context": a.cached_context, "shuffle_off": a.shuffle_off},
         "tokens": res["tokens"], "mean_live": round(res["tokens"] / K, 2),
         "step_hbm_GBs": round(step_gbs, 1), "step_hbm_frac": round(step_gbs / HBM_PEAK_GBS, 4), "by_live_rows": buckets,
         "preprocess_s": round(res["t_pre"], 3), "tokens_per_s_incl_preprocess": round(res["tokens"] / (total + res["t_pre"]), 2),
         "shuffle_moves": res["moves"], "shuffle_bytes": res["bytes_moved"],
+        "total_iterations_from_first_token": K - min(r.arrival_step for r in reqs),
+        "overlap": round(res["tokens"] / max(1, K - min(r.arrival_step for r in reqs)) / len(reqs), 4),
         "roofline": roof, "other_kernels": gemms, "cpu_baseline": cpu, "weights_gen_s": round(t_w, 2),
         "context": "paper (A100 80GB, FasterTransformer base): 11x (GPT-J 6B) and 16x (LLaMA 65B, TP-4) speedup over "
                    "FasterTransformer at 32 parallel requests; no absolute tokens/s published",

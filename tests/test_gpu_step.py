@@ -332,3 +332,16 @@ def test_long_prompts_through_the_context_pass(make):
     print(cfg.name, "max rel err", ls.max_err, "ties", ls.ties)
     assert ls.max_err <= TOL[cfg.dtype]
     ls.close()
+
+
+def test_more_than_128_live_rows():
+    """max_concurrency above one GEMM row block: 150 requests live at once (two row blocks, XCD-mapped), against the
+    oracle on a tiny model, and the window bookkeeping with a large burst."""
+    cfg = dataclasses.replace(synth.tiny_llama(synth.DT_BF16), C=160, S=48)
+    w = synth.make_weights(cfg, 19)
+    reqs = synth.stream_small(10, cfg.V, n=150, arrive_hi=1, p_lo=1, p_hi=20, g_lo=2, g_hi=6)
+    ls = Lockstep(cfg, w)
+    live = ls.run(reqs)
+    print("150-live: steps", ls.steps, "max live", max(live), "max rel err", ls.max_err, "ties", ls.ties, "moves", ls.moves)
+    assert max(live) > 128 and ls.max_err <= TOL[cfg.dtype]
+    ls.close()
