@@ -168,7 +168,7 @@ size_t layout(flover_ctx* c, char* base) {
   c->plane_bytes = c->slot_bytes * C;
   c->kv_bytes = c->plane_bytes * 2 * L;
   c->kv = (char*)b.take(c->kv_bytes);
-  const int R = (std::max(C, 512) + 127) / 128 * 128;   // rows per pass: live rows of an iteration, or a chunk of a prompt
+  const int R = (std::max(C, 1024) + 127) / 128 * 128;   // rows per pass: live rows of an iteration, or a chunk of a prompt
   c->rows_cap = R;
   const int chunks = (S + flk::attn_chunk() - 1) / flk::attn_chunk();
   c->max_items = R * chunks;
