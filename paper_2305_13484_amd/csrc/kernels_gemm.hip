@@ -7,9 +7,11 @@
 //     lane l holds W[n0 + l%16][k0 + 8*(l/16) .. +8], so every wave load is one contiguous, fully used 1 KiB;
 //     tiles are ordered [column group of NT n-tiles][k-block][n-tile in group], so the K slice a wave streams is
 //     one contiguous run of memory (NT KiB per k-block).
-//   * a wave owns 32 or 64 output columns (2 or 4 n-tiles) x one K slice x all rows of its row block; up to 32 rows
-//     the rows' operand comes straight from L2/L1 (no LDS, no barriers); above that it is staged through LDS once
-//     per block and shared by the block's 4 waves.
+//   * a column group (64 columns = 4 n-tiles) x one K slice x all rows of a row block is the unit of work; up to 16
+//     rows one wave takes it and reads the rows' operand straight from L2/L1 (no LDS, no barriers); above that the
+//     rows' operand is staged through LDS once per block of 4 column groups and shared by the block's 4 or 8 waves.
+//   * more than 128 rows (context passes, very wide windows): row blocks of one (column block, K slice) get
+//     workgroup ids that land on the same XCD, so the weight tiles cross HBM once and are L2 hits for the others.
 //   * split-K: slice count and boundaries depend on (N, K) only -- never on M -- and partial sums are written per
 //     slice and added by the consumer in slice order, so a row's result does not depend on which other rows
 //     are live (the paper's premise that fused requests undergo identical operations).

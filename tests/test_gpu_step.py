@@ -345,3 +345,37 @@ def test_more_than_128_live_rows():
     print("150-live: steps", ls.steps, "max live", max(live), "max rel err", ls.max_err, "ties", ls.ties, "moves", ls.moves)
     assert max(live) > 128 and ls.max_err <= TOL[cfg.dtype]
     ls.close()
+
+
+@pytest.mark.parametrize("shuffle_off", [False, True])
+def test_randomised_scheduler_stress(shuffle_off):
+    """Many requests through few slots with random arrivals, waiting, forced finishes at seeded indices and bursts:
+    slot assignment, window, Algorithm 3 results, move lists, evictions and tokens agree with the oracle every step."""
+    cfg = dataclasses.replace(synth.tiny_gpt(), C=6, S=64)
+    w = synth.make_weights(cfg, 23)
+    rng = np.random.default_rng(99)
+    reqs = synth.stream_small(77, cfg.V, n=45, arrive_hi=60, p_lo=1, p_hi=12, g_lo=1, g_hi=20)
+    ls = Lockstep(cfg, w, shuffle_off=shuffle_off)
+    pending = sorted(reqs, key=lambda r: (r.arrival_step, r.req_id))
+    i = done = s = 0
+    max_wait = 0
+    while done < len(reqs):
+        while i < len(pending) and pending[i].arrival_step <= s:
+            ls.add(pending[i])
+            i += 1
+        g, c = ls.step()
+        done += int(g.finished.sum())
+        alive = [int(r) for r, f in zip(g.req_id, g.finished) if not f]
+        if alive and rng.random() < 0.25:                     # forced finish at a seeded index
+            victim = alive[int(rng.integers(len(alive)))]
+            ls.gpu.mark_finished(victim)
+            ls.cpu.mark_finished(victim)
+            done += 1
+        ls.reorder()
+        max_wait = max(max_wait, ls.gpu.state()["waiting"])
+        s += 1
+        assert s < 2000
+    print("stress: steps", s, "moves", ls.moves, "max waiting", max_wait, "ties", ls.ties)
+    assert max_wait > 0 and ls.ties == 0
+    assert (ls.moves > 0) != shuffle_off
+    ls.close()
