@@ -27,10 +27,16 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=0, help="timed steps (0 = the whole stream)")
     ap.add_argument("--warmup", type=int, default=8)
-    ap.add_argument("--workload", default="c4", choices=["c4", "c3", "c1", "c2", "poisson32"])
+    ap.add_argument("--workload", default="c4", choices=["c4", "c3", "c1", "c2", "poisson32", "const32", "shuffle32"])
     ap.add_argument("--lambda-ms", type=float, default=500.0,
                     help="poisson32: mean inter-arrival gap in the paper's milliseconds (Section VI-C); converted to "
                          "decode steps with the paper's 5800 ms per 512 iterations")
+    ap.add_argument("--interval-ms", type=float, default=500.0,
+                    help="const32 / shuffle32: constant gap between two requests in the paper's milliseconds (Section VI-B)")
+    ap.add_argument("--gen-max", type=int, default=512,
+                    help="shuffle32: generation lengths are uniform on [128, gen-max] (Section VI-D)")
+    ap.add_argument("--by-length", action="store_true",
+                    help="Algorithm 3 on entries weighted by cached length (fewest bytes moved) instead of 0/1 occupancy")
     ap.add_argument("--layers", type=int, default=0, help="override the layer count (debug only; reported)")
     ap.add_argument("--requests", type=int, default=0, help="override the number of requests (debug only; reported)")
     ap.add_argument("--profile-level", type=int, default=1)
@@ -270,6 +276,18 @@ def main():
         reqs = [synth.Request(i, int(t), rng.integers(0, cfg.V, size=128).astype(np.int32), 512) for i, t in enumerate(arr)]
         wl = "poisson32: LLaMA-7B shape bf16, 32 requests x 512 tokens, exponential gaps, mean %.0f ms = %.1f steps" % (
             a.lambda_ms, gap_steps)
+    elif a.workload in ("const32", "shuffle32"):
+        # Sections VI-B / VI-D: 32 requests a constant interval apart; 512 output tokens each (const32) or
+        # generation lengths uniform on [128, gen-max] (shuffle32); LLaMA-7B shape, 32 slots
+        gmax = 512 if a.workload == "const32" else a.gen_max
+        cfg = synth.llama_7b(L=a.layers or 32, C=32, S=128 + max(512, gmax) + 1)
+        gap_steps = max(1, int(round(a.interval_ms / (5800.0 / 512.0))))
+        rng = np.random.default_rng(a.seed)
+        gens = np.full(32, 512) if a.workload == "const32" else rng.integers(128, gmax + 1, size=32)
+        reqs = [synth.Request(i, i * gap_steps, rng.integers(0, cfg.V, size=128).astype(np.int32), int(g))
+                for i, g in enumerate(gens)]
+        wl = "%s: LLaMA-7B shape bf16, 32 requests %.0f ms = %d steps apart, generation %s" % (
+            a.workload, a.interval_ms, gap_steps, "512" if a.workload == "const32" else "U{128..%d}" % gmax)
     elif a.workload == "c1":
         cfg = synth.tiny_gpt()
         reqs = synth.stream_c1(a.seed, cfg.V)
@@ -282,7 +300,7 @@ def main():
     weights = synth.make_weights(cfg, a.seed, device="cuda")
     torch.cuda.synchronize()
     t_w = time.perf_counter() - t0
-    srv = fl.Flover(cfg, weights, shuffle_off=a.shuffle_off)
+    srv = fl.Flover(cfg, weights, shuffle_off=a.shuffle_off, by_length=a.by_length)
     cpu = None
     if not a.no_cpu_baseline:
         cpu = cpu_baseline(cfg, weights, reqs)
@@ -338,7 +356,7 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": synth.DTYPE_NAME[cfg.dtype],
         "data": "synthetic",
         "config": {"workload": wl, "layers": cfg.L, "requests": len(reqs), "whole_stream": res["all_done"],
-                   "seed": a.seed, "cached_context": a.cached_context, "shuffle_off": a.shuffle_off},
+                   "seed": a.seed, "cached_context": a.cached_context, "shuffle_off": a.shuffle_off, "by_length": a.by_length},
         "tokens": res["tokens"], "mean_live": round(res["tokens"] / K, 2),
         "step_hbm_GBs": round(step_gbs, 1), "step_hbm_frac": round(step_gbs / HBM_PEAK_GBS, 4), "by_live_rows": buckets,
         "preprocess_s": round(res["t_pre"], 3), "tokens_per_s_incl_preprocess": round(res["tokens"] / (total + res["t_pre"]), 2),

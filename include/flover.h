@@ -25,6 +25,9 @@ extern "C" {
 enum { FLOVER_OK = 0, FLOVER_E_INVAL = -1, FLOVER_E_FULL = -2, FLOVER_E_NOMEM = -3, FLOVER_E_STATE = -4, FLOVER_E_HIP = -5 };
 enum { FLOVER_ARCH_GPT = 0, FLOVER_ARCH_LLAMA = 1 };
 enum { FLOVER_F32 = 0, FLOVER_F16 = 1, FLOVER_BF16 = 2 };
+/* flover_config.shuffle_mode */
+enum { FLOVER_SHUFFLE_SLOTS = 0, FLOVER_SHUFFLE_OFF = 1, FLOVER_SHUFFLE_BY_LENGTH = 2 };
+
 /* slot states reported by flover_get_state */
 enum { FLOVER_SLOT_EMPTY = 0, FLOVER_SLOT_READY = 1, FLOVER_SLOT_LIVE = 2, FLOVER_SLOT_DEAD = 3 };
 
@@ -40,8 +43,11 @@ typedef struct flover_config {
   int32_t max_seq;         /* slot capacity in tokens */
   int32_t max_concurrency; /* number of slots = most requests generating at once (Section V-A) */
   int32_t eos_id;          /* token that ends a request; -1 = none (Section IV) */
-  int32_t shuffle_off;     /* non-zero: the variant without memory shuffle (Section VI-D): finished slots stay
-                              inside the window as holes that the kernels still cover */
+  int32_t shuffle_mode;    /* FLOVER_SHUFFLE_*: SLOTS = Algorithm 3 on the 0/1 occupancy array (fewest slots moved);
+                              OFF = the variant without memory shuffle (Section VI-D): finished slots stay inside the
+                              window as holes that the kernels still cover; BY_LENGTH = Algorithm 3 with every valid
+                              entry weighted by its cached rows + 1 (the listing sums arr[i], so it already allows
+                              weights): the window that leaves the fewest cached rows outside, i.e. fewest bytes moved */
   float norm_eps;
   float rope_theta;
   void* stream;            /* hipStream_t the library enqueues on; NULL = the null stream */
@@ -138,7 +144,7 @@ typedef struct flover_reorder_out {
  * (first window scored too, lowest offset on ties), the region of size #valid that leaves the fewest valid
  * slots outside; copies, in one launch, the KV rows [0,len) of each outside slot into a hole inside (i-th hole
  * ascending <- i-th outside slot ascending) and moves the scheduler's record with it.  Waits for the copy.
- * With shuffle_off only the empty ends of the window are dropped.  Safe to call after every step. */
+ * With FLOVER_SHUFFLE_OFF only the empty ends of the window are dropped.  Safe to call after every step. */
 int32_t flover_reorder_evict(flover_ctx* ctx, flover_reorder_out* out);
 
 /* Measurement hook (not in the paper): like flover_add_request, but the slot's context cache (KV rows

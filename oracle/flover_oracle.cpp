@@ -91,7 +91,7 @@ double rd32(double x) { return (double)(float)x; }
 // ---------------------------------------------------------------- configuration
 
 struct Config {
-  int32_t arch, dtype, L, H, nh, d, F, V, S, C, eos_id, shuffle_off;
+  int32_t arch, dtype, L, H, nh, d, F, V, S, C, eos_id, shuffle_mode;   // 0 shuffle by slots, 1 off, 2 by cached length
   double ln_eps, rope_theta;
 };
 struct Weights {   // every linear weight [out][in]; per-layer tensors stacked over layers
@@ -386,7 +386,7 @@ struct Server {
 extern "C" {
 
 struct orc_config {
-  int32_t arch, dtype, L, H, nh, d, F, V, S, C, eos_id, shuffle_off;
+  int32_t arch, dtype, L, H, nh, d, F, V, S, C, eos_id, shuffle_mode;
   double ln_eps, rope_theta;
 };
 struct orc_weights {
@@ -508,9 +508,13 @@ int orc_reorder_evict(void* h, int32_t* out6, uint64_t* evicted_req_id, int32_t*
   int n_moves = 0, off = 0, min_cost = 0, n1 = 0;
   int64_t bytes = 0;
   const int ebytes = c.dtype == DT_F32 ? 4 : 2;
-  if (!c.shuffle_off) {
+  if (c.shuffle_mode != 1) {
+    // occupancy array of Algorithm 3: 0/1, or (length-weighted variant) cached rows + 1 for a valid slot
     std::vector<int32_t> arr(std::max(n_old, 1), 0);
-    for (int i = 0; i < n_old; ++i) arr[i] = s->slots[old_lo + i].state != EMPTY ? 1 : 0;
+    for (int i = 0; i < n_old; ++i) {
+      const Slot& sl = s->slots[old_lo + i];
+      arr[i] = sl.state == EMPTY ? 0 : (c.shuffle_mode == 2 ? sl.len + 1 : 1);
+    }
     off = find_window(arr.data(), n_old, &min_cost, &n1);
     if (n1 == 0) {
       off = 0;

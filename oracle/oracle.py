@@ -29,7 +29,7 @@ def build(force: bool = False) -> str:
 
 class OrcConfig(C.Structure):
     _fields_ = [(n, C.c_int32) for n in
-                ["arch", "dtype", "L", "H", "nh", "d", "F", "V", "S", "C", "eos_id", "shuffle_off"]] + \
+                ["arch", "dtype", "L", "H", "nh", "d", "F", "V", "S", "C", "eos_id", "shuffle_mode"]] + \
                [("ln_eps", C.c_double), ("rope_theta", C.c_double)]
 
 
@@ -83,9 +83,9 @@ def _ptr(t) -> int:
     return t.data_ptr()
 
 
-def make_config(cfg, shuffle_off: bool = False) -> OrcConfig:
+def make_config(cfg, shuffle_off: bool = False, by_length: bool = False) -> OrcConfig:
     return OrcConfig(cfg.arch, cfg.dtype, cfg.L, cfg.H, cfg.nh, cfg.d, cfg.F, cfg.V, cfg.S, cfg.C, cfg.eos_id,
-                     1 if shuffle_off else 0, cfg.ln_eps, cfg.rope_theta)
+                     1 if shuffle_off else 2 if by_length else 0, cfg.ln_eps, cfg.rope_theta)
 
 
 def make_weights(weights: Dict[str, object]) -> OrcWeights:
@@ -113,10 +113,10 @@ class ReorderResult:
 class OracleServer:
     """The fused run: scheduler + slots + decoder + Algorithm 3 + shuffle, on the CPU."""
 
-    def __init__(self, cfg, weights: Dict[str, object], shuffle_off: bool = False):
+    def __init__(self, cfg, weights: Dict[str, object], shuffle_off: bool = False, by_length: bool = False):
         self.cfg = cfg
         self._weights = weights         # keep the host buffers alive
-        self._c = make_config(cfg, shuffle_off)
+        self._c = make_config(cfg, shuffle_off, by_length)
         self._w = make_weights(weights)
         self._h = lib().orc_create(C.byref(self._c), C.byref(self._w))
 

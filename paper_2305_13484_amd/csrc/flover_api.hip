@@ -605,7 +605,7 @@ int32_t flover_step(flover_ctx* c, flover_step_out* out) {
   }
   const int n = (int)live.size();
   if (out->capacity < n) return fail(c, FLOVER_E_INVAL, "flover_step_out.capacity too small");
-  if (c->cfg.shuffle_off)            // holes inside the window are still covered by the kernels (and ignored)
+  if (c->cfg.shuffle_mode == FLOVER_SHUFFLE_OFF)   // holes inside the window are still covered by the kernels (and ignored)
     for (int i = c->lo; i < c->hi; ++i)
       if (c->slots[i].state == FLOVER_SLOT_EMPTY || c->slots[i].state == FLOVER_SLOT_DEAD) rows.push_back(Row{i, 0, 0});
   out->n_live = n;
@@ -668,9 +668,12 @@ int32_t flover_reorder_evict(flover_ctx* c, flover_reorder_out* out) {
   const int old_lo = c->lo, n_old = c->hi - c->lo;
   int off = 0, min_cost = 0, n1 = 0, n_moves = 0;
   int64_t bytes = 0;
-  if (!f.shuffle_off) {
+  if (f.shuffle_mode != FLOVER_SHUFFLE_OFF) {
     std::vector<int32_t> arr(std::max(n_old, 1), 0);
-    for (int i = 0; i < n_old; ++i) arr[i] = c->slots[old_lo + i].state != FLOVER_SLOT_EMPTY ? 1 : 0;
+    for (int i = 0; i < n_old; ++i) {
+      const Slot& s = c->slots[old_lo + i];
+      arr[i] = s.state == FLOVER_SLOT_EMPTY ? 0 : f.shuffle_mode == FLOVER_SHUFFLE_BY_LENGTH ? s.len + 1 : 1;
+    }
     off = find_window(arr.data(), n_old, &min_cost, &n1);
     if (n1 == 0) {
       off = 0;

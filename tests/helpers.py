@@ -15,11 +15,11 @@ def to_device(weights):
 class Lockstep:
     """Feeds the same stream to both sides, compares every step, re-synchronises after a near tie."""
 
-    def __init__(self, cfg, weights, shuffle_off=False):
+    def __init__(self, cfg, weights, shuffle_off=False, by_length=False):
         import paper_2305_13484_amd as fl
         self.cfg = cfg
-        self.gpu = fl.Flover(cfg, to_device(weights), shuffle_off=shuffle_off)
-        self.cpu = orc.OracleServer(cfg, weights, shuffle_off=shuffle_off)
+        self.gpu = fl.Flover(cfg, to_device(weights), shuffle_off=shuffle_off, by_length=by_length)
+        self.cpu = orc.OracleServer(cfg, weights, shuffle_off=shuffle_off, by_length=by_length)
         self.tol = TOL[cfg.dtype]
         self.max_err = 0.0
         self.ties = 0

@@ -347,15 +347,16 @@ def test_more_than_128_live_rows():
     ls.close()
 
 
-@pytest.mark.parametrize("shuffle_off", [False, True])
-def test_randomised_scheduler_stress(shuffle_off):
+@pytest.mark.parametrize("mode", ["slots", "off", "by_length"])
+def test_randomised_scheduler_stress(mode):
     """Many requests through few slots with random arrivals, waiting, forced finishes at seeded indices and bursts:
-    slot assignment, window, Algorithm 3 results, move lists, evictions and tokens agree with the oracle every step."""
+    slot assignment, window, Algorithm 3 results (0/1 and length-weighted), move lists, evictions and tokens agree with
+    the oracle every step."""
     cfg = dataclasses.replace(synth.tiny_gpt(), C=6, S=64)
     w = synth.make_weights(cfg, 23)
     rng = np.random.default_rng(99)
     reqs = synth.stream_small(77, cfg.V, n=45, arrive_hi=60, p_lo=1, p_hi=12, g_lo=1, g_hi=20)
-    ls = Lockstep(cfg, w, shuffle_off=shuffle_off)
+    ls = Lockstep(cfg, w, shuffle_off=mode == "off", by_length=mode == "by_length")
     pending = sorted(reqs, key=lambda r: (r.arrival_step, r.req_id))
     i = done = s = 0
     max_wait = 0
@@ -377,5 +378,5 @@ def test_randomised_scheduler_stress(shuffle_off):
         assert s < 2000
     print("stress: steps", s, "moves", ls.moves, "max waiting", max_wait, "ties", ls.ties)
     assert max_wait > 0 and ls.ties == 0
-    assert (ls.moves > 0) != shuffle_off
+    assert (ls.moves > 0) != (mode == "off")
     ls.close()

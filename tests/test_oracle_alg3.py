@@ -101,3 +101,48 @@ def test_weighted_entries_follow_the_listing():
             continue
         costs = [sum(arr) - sum(arr[o:o + nz]) for o in range(n - nz + 1)]
         assert cost == min(costs) and off == costs.index(min(costs))
+
+
+def brute_force_weighted(arr):
+    """Definition of the length-weighted variant: among all windows of size (#valid), the lowest offset leaving the
+    least total weight outside (weights = the non-zero entries of arr, which Algorithm 3 sums as they are)."""
+    n1 = sum(1 for a in arr if a)
+    if n1 == 0:
+        return 0, 0
+    total = sum(arr)
+    best = None
+    for off in range(len(arr) - n1 + 1):
+        cost = total - sum(arr[off:off + n1])
+        if best is None or cost < best[1]:
+            best = (off, cost)
+    return best
+
+
+def test_weighted_arrays_against_brute_force():
+    # every array over {0,1,2,5} up to length 7, then random longer ones with length-like weights
+    for n in range(1, 8):
+        for a in itertools.product((0, 1, 2, 5), repeat=n):
+            off, cost, nz = orc.find_window(a)
+            assert nz == sum(1 for x in a if x)
+            assert (off, cost) == brute_force_weighted(a), a
+    rng = np.random.default_rng(3)
+    for _ in range(2000):
+        n = int(rng.integers(1, 60))
+        a = [int(x) for x in rng.integers(1, 2049, size=n) * (rng.random(n) < 0.6)]
+        off, cost, nz = orc.find_window(a)
+        assert (off, cost) == brute_force_weighted(a), a
+
+
+def test_weighted_window_never_moves_more_weight_than_the_unweighted_one():
+    rng = np.random.default_rng(4)
+    strictly_better = 0
+    for _ in range(500):
+        n = int(rng.integers(2, 40))
+        w = [int(x) for x in rng.integers(1, 1000, size=n) * (rng.random(n) < 0.7)]
+        b = [1 if x else 0 for x in w]
+        off_b, _, nz = orc.find_window(b)
+        off_w, cost_w, _ = orc.find_window(w)
+        outside_b = sum(w) - sum(w[off_b:off_b + nz])
+        assert cost_w <= outside_b
+        strictly_better += cost_w < outside_b
+    assert strictly_better > 0

@@ -73,6 +73,42 @@ def test_fused_equals_alone_and_shuffle_on_equals_off(tiny_gpt):
         assert np.array_equal(np.stack(logits_off[r.req_id]), np.stack(logits[r.req_id]))
 
 
+def test_length_weighted_shuffle_is_the_same_rescheduling_and_minimises_rows_moved(tiny_gpt):
+    # Algorithm 3 with entries weighted by cached length: results per request unchanged, and at every eviction the
+    # rows left outside the chosen window are the fewest any window allows.
+    cfg, w = tiny_gpt
+    cfg = dataclasses.replace(cfg, C=6)
+    reqs = synth.stream_small(21, cfg.V, n=14, arrive_hi=10, p_lo=2, p_hi=30, g_lo=2, g_hi=14)
+    ref, _, _, _ = run_stream(orc.OracleServer(cfg, w), reqs, want_logits=False)
+    srv = orc.OracleServer(cfg, w, by_length=True)
+    pending = sorted(reqs, key=lambda r: (r.arrival_step, r.req_id))
+    toks = {r.req_id: [] for r in reqs}
+    i = done = s = checked = 0
+    while done < len(reqs):
+        while i < len(pending) and pending[i].arrival_step <= s:
+            srv.add_request(pending[i].req_id, pending[i].prompt, pending[i].gen_len)
+            i += 1
+        out = srv.step(False)
+        for k in range(out.n_live):
+            toks[int(out.req_id[k])].append(int(out.token[k]))
+        done += int(out.finished.sum())
+        st = srv.state()
+        lo, hi = st["lo"], st["hi"]
+        weights = [0 if st["state"][j] in (0, 3) else int(st["len"][j]) + 1 for j in range(lo, hi)]
+        rr = srv.reorder_evict()
+        n1 = sum(1 for x in weights if x)
+        if n1:
+            best = min(sum(weights) - sum(weights[o:o + n1]) for o in range(len(weights) - n1 + 1))
+            assert rr.min_cost == best
+            outside = sum(weights) - sum(weights[rr.mem_offset:rr.mem_offset + n1])
+            assert outside == best
+            checked += len(rr.moves) > 0
+        s += 1
+    assert checked > 0
+    for r in reqs:
+        assert toks[r.req_id] == ref[r.req_id]
+
+
 def test_capacity_wait_and_slot_reuse(tiny_gpt):
     cfg, w = tiny_gpt
     cfg = dataclasses.replace(cfg, C=3)
