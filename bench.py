@@ -35,6 +35,9 @@ def parse():
                     help="const32 / shuffle32: constant gap between two requests in the paper's milliseconds (Section VI-B)")
     ap.add_argument("--gen-max", type=int, default=512,
                     help="shuffle32: generation lengths are uniform on [128, gen-max] (Section VI-D)")
+    ap.add_argument("--async-preprocess", action="store_true",
+                    help="pre-processing on the library's second stream, beside the fused iterations (Section V-B); "
+                         "flover_add_request then only enqueues, and tokens_per_s_incl_preprocess is the figure to read")
     ap.add_argument("--by-length", action="store_true",
                     help="Algorithm 3 on entries weighted by cached length (fewest bytes moved) instead of 0/1 occupancy")
     ap.add_argument("--layers", type=int, default=0, help="override the layer count (debug only; reported)")
@@ -62,7 +65,7 @@ def step_bytes(cfg, lens):
     return cfg.weight_bytes_per_step() + sum(l + 1 for l in lens) * kvb + M * kvb + M * cfg.H * e + M * cfg.V * 4
 
 
-def run_stream(srv, cfg, reqs, max_steps, cached=False):
+def run_stream(srv, cfg, reqs, max_steps, cached=False, async_pre=False):
     """Drives the stream; returns totals.  Steps are bracketed by host clocks; flover_step and flover_reorder_evict
     both return only after their GPU work has completed.  Per-step bookkeeping is kept to array operations so the
     Python driver adds as little as possible between two steps."""
@@ -90,7 +93,8 @@ def run_stream(srv, cfg, reqs, max_steps, cached=False):
                     srv.add_request(r.req_id, r.prompt, r.gen_len)
                 lens[idx_of[r.req_id]] = len(r.prompt) - 1
                 i += 1
-            torch.cuda.synchronize()
+            if not async_pre:
+                torch.cuda.synchronize()
             t_pre += clock() - t0
         t1 = clock()
         out = srv.step()
@@ -300,7 +304,7 @@ def main():
     weights = synth.make_weights(cfg, a.seed, device="cuda")
     torch.cuda.synchronize()
     t_w = time.perf_counter() - t0
-    srv = fl.Flover(cfg, weights, shuffle_off=a.shuffle_off, by_length=a.by_length)
+    srv = fl.Flover(cfg, weights, shuffle_off=a.shuffle_off, by_length=a.by_length, async_preprocess=a.async_preprocess)
     cpu = None
     if not a.no_cpu_baseline:
         cpu = cpu_baseline(cfg, weights, reqs)
@@ -313,10 +317,10 @@ def main():
         wp = min(200, cfg.S // 2)
         warm = [synth.Request(10 ** 6 + i, 0, rng.integers(0, cfg.V, size=wp).astype(np.int32),
                               max(1, min(a.warmup, cfg.S - wp - 1))) for i in range(min(8, cfg.C))]
-        run_stream(srv, cfg, warm, 0, cached=a.cached_context)
+        run_stream(srv, cfg, warm, 0, cached=a.cached_context, async_pre=a.async_preprocess)
 
     srv.set_profile(a.profile_level)
-    res = run_stream(srv, cfg, reqs, a.steps, cached=a.cached_context)
+    res = run_stream(srv, cfg, reqs, a.steps, cached=a.cached_context, async_pre=a.async_preprocess)
     prof = srv.get_profile()
     srv.close()
 
@@ -356,7 +360,8 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": synth.DTYPE_NAME[cfg.dtype],
         "data": "synthetic",
         "config": {"workload": wl, "layers": cfg.L, "requests": len(reqs), "whole_stream": res["all_done"],
-                   "seed": a.seed, "cached_context": a.cached_context, "shuffle_off": a.shuffle_off, "by_length": a.by_length},
+                   "seed": a.seed, "cached_context": a.cached_context, "shuffle_off": a.shuffle_off, "by_length": a.by_length,
+                   "async_preprocess": a.async_preprocess},
         "tokens": res["tokens"], "mean_live": round(res["tokens"] / K, 2),
         "step_hbm_GBs": round(step_gbs, 1), "step_hbm_frac": round(step_gbs / HBM_PEAK_GBS, 4), "by_live_rows": buckets,
         "preprocess_s": round(res["t_pre"], 3), "tokens_per_s_incl_preprocess": round(res["tokens"] / (total + res["t_pre"]), 2),

@@ -48,6 +48,13 @@ typedef struct flover_config {
                               window as holes that the kernels still cover; BY_LENGTH = Algorithm 3 with every valid
                               entry weighted by its cached rows + 1 (the listing sums arr[i], so it already allows
                               weights): the window that leaves the fewest cached rows outside, i.e. fewest bytes moved */
+  int32_t async_preprocess; /* 0: flover_add_request returns when the context cache is complete (pre-processing runs on
+                               `stream`).  Non-zero: the library creates a second stream (default priority) and a second set
+                               of row buffers for the context decoder, as the paper runs pre-processing beside the inference
+                               stream (Section V-B): flover_add_request returns once the passes are enqueued, the request
+                               joins the first flover_step that finds its cache complete, and flover_add_request may be
+                               called from another thread while flover_step / flover_reorder_evict run.  Tokens and logits
+                               of every request are the same in both modes; only the iteration a request joins differs. */
   float norm_eps;
   float rope_theta;
   void* stream;            /* hipStream_t the library enqueues on; NULL = the null stream */
@@ -102,6 +109,12 @@ const char* flover_last_error(const flover_ctx* ctx);
  * 0..prompt_len-2 -- and put the request into the inference queue.  It joins the fused stream at the next
  * flover_step, which feeds prompt[prompt_len-1].  If no adjacent slot is free the request waits in the
  * request queue (FIFO) and is pre-processed by a later flover_step; *out_slot = -1 then.
+ * With async_preprocess the context passes are only enqueued (on the library's second stream) and the request joins
+ * the first flover_step that finds them complete; a flover_step with nothing else to generate waits for the oldest
+ * one.  Threads: every call takes the context's scheduler lock; with async_preprocess flover_step releases it while
+ * the GPU works, so ONE other thread may call flover_add_request beside the thread that drives flover_step /
+ * flover_reorder_evict (the paper's pre-processing and inference threads, Section V-A).  Without async_preprocess
+ * calls from several threads are serialised.
  * The prompt is copied before return.  Errors: INVAL (prompt_len < 1, max_new_tokens < 1,
  * prompt_len + max_new_tokens > max_seq, token out of range, req_id already waiting or live). */
 int32_t flover_add_request(flover_ctx* ctx, uint64_t req_id, const int32_t* prompt, int32_t prompt_len,
@@ -218,8 +231,8 @@ int32_t flover_k_compact(void* cache, int32_t L, int32_t C, int32_t n_head, int3
 
 /* Weight GEMM of the fused rows: y[M][N] (fp32) = x[M][K] . W[N][K]^T, fp32 accumulation (MFMA for the 16-bit
  * dtypes).  W is first re-tiled into `w_tiled` (flover_k_gemm_tiled_bytes bytes, [device]) by flover_k_gemm_retile;
- * flover_k_gemm then streams the tiled copy.  x [device][Mpad][K]: rows up to M rounded up to a multiple of 128 must be
- * readable (their contents do not matter);
+ * flover_k_gemm then streams the tiled copy.  x [device][Mpad][K]: rows up to M rounded up to a multiple of 128 (of 256 when
+ * M > 128) must be readable (their contents do not matter);
  * workspace holds the split-K partial sums.  K % 32 == 0.  y == NULL leaves the result as partial sums in the
  * workspace (timing the streaming kernel alone). */
 int32_t flover_k_gemm_tiled_bytes(int32_t dtype, int32_t N, int32_t K, uint64_t* out);

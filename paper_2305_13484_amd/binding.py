@@ -37,7 +37,7 @@ class FloverError(RuntimeError):
 class _Config(C.Structure):
     _fields_ = [(n, C.c_int32) for n in
                 ["arch", "dtype", "n_layer", "hidden", "n_head", "head_dim", "ffn", "vocab", "max_seq",
-                 "max_concurrency", "eos_id", "shuffle_mode"]] + \
+                 "max_concurrency", "eos_id", "shuffle_mode", "async_preprocess"]] + \
                [("norm_eps", C.c_float), ("rope_theta", C.c_float), ("stream", C.c_void_p), ("arena", C.c_void_p),
                 ("arena_bytes", C.c_uint64)]
 
@@ -142,12 +142,13 @@ class Flover:
     cfg: any object with fields arch, dtype, L, H, nh, d, F, V, S, C, eos_id, ln_eps, rope_theta.
     weights: dict of device tensors (names of flover_weights), each [out][in] / stacked over layers."""
 
-    def __init__(self, cfg, weights: Dict[str, torch.Tensor], shuffle_off: bool = False, by_length: bool = False):
+    def __init__(self, cfg, weights: Dict[str, torch.Tensor], shuffle_off: bool = False, by_length: bool = False,
+                 async_preprocess: bool = False):
         L = load_library()
         self.cfg = cfg
         self._ctx = None
         c = _Config(cfg.arch, cfg.dtype, cfg.L, cfg.H, cfg.nh, cfg.d, cfg.F, cfg.V, cfg.S, cfg.C, cfg.eos_id,
-                    1 if shuffle_off else 2 if by_length else 0, cfg.ln_eps, cfg.rope_theta, None, None, 0)
+                    1 if shuffle_off else 2 if by_length else 0, 1 if async_preprocess else 0, cfg.ln_eps, cfg.rope_theta, None, None, 0)
         need = C.c_uint64(0)
         _check(L.flover_query_arena_bytes(C.byref(c), C.byref(need)))
         self.arena = torch.empty(int(need.value) + 256, dtype=torch.uint8, device="cuda")
@@ -323,7 +324,7 @@ def k_gemm(x: torch.Tensor, W, out: Optional[torch.Tensor] = None, workspace: Op
     tw = W if isinstance(W, TiledWeight) else TiledWeight(W)
     M, K = x.shape
     assert K == tw.K and _DT_OF[x.dtype] == tw.dtype
-    rows = (M + 127) // 128 * 128
+    rows = (M + 127) // 128 * 128 if M <= 128 else (M + 255) // 256 * 256
     xp = x
     if M != rows:
         xp = torch.zeros((rows, K), dtype=x.dtype, device=x.device)

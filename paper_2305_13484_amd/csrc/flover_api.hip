@@ -13,6 +13,7 @@
 #include <cstdio>
 #include <cstring>
 #include <deque>
+#include <mutex>
 #include <string>
 #include <vector>
 
@@ -29,6 +30,8 @@ struct Slot {
   int next_token = 0;
   int generated = 0;
   int max_new = 0;
+  bool pending = false;   // context cache still being written on the pre-processing stream (event prep_ev[ev])
+  int ev = -1;
 };
 struct Waiting {
   uint64_t req_id;
@@ -40,6 +43,26 @@ struct LayerW {
 };
 struct Row {
   int slot, tok, pos;
+};
+
+// One execution lane: a stream with the row buffers and staging a pass of the decoder needs.  The fused iteration
+// owns one; with asynchronous pre-processing the context decoder owns a second one (Section V-B: pre-processing runs
+// beside the inference stream), otherwise both names refer to the same lane.
+constexpr int kStageRing = 4;
+struct Lane {
+  hipStream_t st = nullptr;
+  float* x = nullptr;
+  void *h = nullptr, *q = nullptr, *att = nullptr, *act = nullptr;
+  float* part = nullptr;
+  int* tok_out = nullptr;
+  int* d_stage = nullptr;   // tok | pos | slot | len | item0 | nchunk | items(2x) | context-pass blocks(4x)
+  float *pml = nullptr, *po = nullptr;
+  // pinned host staging; a ring so that passes can be queued without waiting for the previous copy
+  int* h_stage[kStageRing] = {nullptr, nullptr, nullptr, nullptr};
+  hipEvent_t staged[kStageRing] = {nullptr, nullptr, nullptr, nullptr};   // copy of h_stage[i] has been consumed
+  bool staged_busy[kStageRing] = {false, false, false, false};
+  int ring = 1, next = 0;
+  int* h_tok = nullptr;
 };
 
 size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
@@ -71,20 +94,16 @@ struct flover_ctx {
   // KV cache [L][2][C][nh][S][d]
   char* kv;
   size_t kv_bytes, slot_bytes, plane_bytes;
-  // per-iteration buffers
+  // per-pass buffers
   int rows_cap, max_items;
-  float* x;
-  void *h, *q, *att, *act;
-  float* part;
-  int* tok_out;
-  int* d_stage;   // tok | pos | slot | len | item0 | nchunk | items(2x)
-  float *pml, *po;
+  Lane step_lane, prep_lane_own;
+  Lane* prep_lane = nullptr;   // == &step_lane unless pre-processing is asynchronous
   int4* d_moves;
-  // pinned host staging
-  int* h_stage;
-  int* h_tok;
-  int4* h_moves;
+  int4* h_moves;               // pinned
   size_t stage_ints;
+  size_t act_off = 0;          // arena offset where the row buffers start
+  std::vector<hipEvent_t> prep_ev;   // one per slot: the slot's context cache is complete
+  mutable std::mutex mu;             // scheduler state; see flover.h for which calls may run concurrently
   // scheduler
   std::vector<Slot> slots;
   std::deque<Waiting> reque;   // Q_R
@@ -168,23 +187,27 @@ size_t layout(flover_ctx* c, char* base) {
   c->plane_bytes = c->slot_bytes * C;
   c->kv_bytes = c->plane_bytes * 2 * L;
   c->kv = (char*)b.take(c->kv_bytes);
-  const int R = (std::max(C, 1024) + 127) / 128 * 128;   // rows per pass: live rows of an iteration, or a chunk of a prompt
+  const int R = (std::max(C, 1024) + 255) / 256 * 256;   // rows per pass: live rows of an iteration, or a chunk of a prompt
   c->rows_cap = R;
   const int chunks = (S + flk::attn_chunk() - 1) / flk::attn_chunk();
   c->max_items = R * chunks;
-  c->x = (float*)b.take((size_t)R * H * 4);
-  c->h = b.take((size_t)R * H * e);
-  c->q = b.take((size_t)R * H * e);
-  c->att = b.take((size_t)R * H * e);
-  c->act = b.take((size_t)R * F * e);
   size_t pw = 0;
   for (const flk::GemmPlan* p : {&c->p_qkv, &c->p_o, &c->p_1, &c->p_2, &c->p_lm}) pw = std::max(pw, (size_t)p->S * p->ldc);
-  c->part = (float*)b.take(pw * R * 4);
-  c->tok_out = (int*)b.take((size_t)R * 4);
   c->stage_ints = (size_t)6 * R + (size_t)6 * c->max_items;   // row arrays, (row, chunk) items, context-pass blocks
-  c->d_stage = (int*)b.take(c->stage_ints * 4);
-  c->pml = (float*)b.take((size_t)c->max_items * f.n_head * 2 * 4);
-  c->po = (float*)b.take((size_t)c->max_items * f.n_head * f.head_dim * 4);
+  c->act_off = align_up(b.off, 256);
+  for (Lane* ln : {&c->step_lane, &c->prep_lane_own}) {
+    if (ln == &c->prep_lane_own && !f.async_preprocess) break;
+    ln->x = (float*)b.take((size_t)R * H * 4);
+    ln->h = b.take((size_t)R * H * e);
+    ln->q = b.take((size_t)R * H * e);
+    ln->att = b.take((size_t)R * H * e);
+    ln->act = b.take((size_t)R * F * e);
+    ln->part = (float*)b.take(pw * R * 4);
+    ln->tok_out = (int*)b.take((size_t)R * 4);
+    ln->d_stage = (int*)b.take(c->stage_ints * 4);
+    ln->pml = (float*)b.take((size_t)c->max_items * f.n_head * 2 * 4);
+    ln->po = (float*)b.take((size_t)c->max_items * f.n_head * f.head_dim * 4);
+  }
   c->d_moves = (int4*)b.take((size_t)C * sizeof(int4));
   return align_up(b.off, 256);
 }
@@ -227,25 +250,34 @@ void prof_collect(flover_ctx* c) {   // after the stream has been synchronised
   c->ev_kind.clear();
   c->ev_bytes.clear();
 }
-hipError_t timed_gemm(flover_ctx* c, int kind, const void* x, const void* w, int n, const flk::GemmPlan& p, size_t ss) {
+hipError_t timed_gemm(flover_ctx* c, Lane& ln, int kind, const void* x, const void* w, int n, const flk::GemmPlan& p,
+                      size_t ss) {
   const int64_t bytes = (int64_t)flk::gemm_tiled_bytes(c->cfg.dtype, p.N, p.K);
-  const int pi = prof_begin(c, kind, bytes);
-  if (pi >= 0) (void)hipEventRecord(c->ev[2 * pi], c->st);
-  hipError_t e = flk::gemm(c->cfg.dtype, x, w, n, p, c->part, ss, c->st);
-  if (pi >= 0) (void)hipEventRecord(c->ev[2 * pi + 1], c->st);
+  const int pi = &ln == &c->step_lane ? prof_begin(c, kind, bytes) : -1;
+  if (pi >= 0) (void)hipEventRecord(c->ev[2 * pi], ln.st);
+  hipError_t e = flk::gemm(c->cfg.dtype, x, w, n, p, ln.part, ss, ln.st);
+  if (pi >= 0) (void)hipEventRecord(c->ev[2 * pi + 1], ln.st);
   return e;
 }
 
-// One pass of the decoder over n rows: a single launch per operation covers all of them.
-// With want_tokens the final norm, output projection and argmax run and tok_out (device) holds the choices.
-int run_rows(flover_ctx* c, const Row* rows, int n, bool want_tokens, float* logits_out, bool context_pass) {
+// One pass of the decoder over n rows on lane `ln`: a single launch per operation covers all of them.
+// With want_tokens the final norm, output projection and argmax run and ln.h_tok (host) holds the choices.
+// With wait the call returns after the lane's stream has drained; otherwise the pass is only enqueued.
+int run_rows(flover_ctx* c, Lane& ln, const Row* rows, int n, bool want_tokens, float* logits_out, bool context_pass,
+             bool wait) {
   const flover_config& f = c->cfg;
   const int H = f.hidden, F = f.ffn, V = f.vocab, nh = f.n_head, d = f.head_dim, L = f.n_layer, R = c->rows_cap;
   const bool gpt = f.arch == FLOVER_ARCH_GPT;
-  hipStream_t st = c->st;
+  hipStream_t st = ln.st;
   if (n <= 0) return FLOVER_OK;
-  // row descriptors and the attention work list, one host-to-device copy
-  int* hs = c->h_stage;
+  // row descriptors and the attention work list, one host-to-device copy from the next staging buffer of the ring
+  const int ri = ln.next;
+  ln.next = (ln.next + 1) % ln.ring;
+  if (ln.staged_busy[ri]) {
+    HIPCHK(c, hipEventSynchronize(ln.staged[ri]));
+    ln.staged_busy[ri] = false;
+  }
+  int* hs = ln.h_stage[ri];
   int *tok = hs, *pos = hs + R, *slot = hs + 2 * R, *len = hs + 3 * R, *item0 = hs + 4 * R, *nchunk = hs + 5 * R;
   int* items = hs + 6 * R;
   int n_items = 0;
@@ -283,74 +315,98 @@ int run_rows(flover_ctx* c, const Row* rows, int n, bool want_tokens, float* log
       i += nr;
     }
   }
-  HIPCHK(c, hipMemcpyAsync(c->d_stage, hs, ((size_t)6 * R + (size_t)2 * n_items + (size_t)4 * n_blocks) * 4,
+  HIPCHK(c, hipMemcpyAsync(ln.d_stage, hs, ((size_t)6 * R + (size_t)2 * n_items + (size_t)4 * n_blocks) * 4,
                            hipMemcpyHostToDevice, st));
-  int* ds = c->d_stage;
+  if (!wait) {
+    HIPCHK(c, hipEventRecord(ln.staged[ri], st));
+    ln.staged_busy[ri] = true;
+  }
+  int* ds = ln.d_stage;
   const int *d_tok = ds, *d_pos = ds + R, *d_slot = ds + 2 * R, *d_len = ds + 3 * R, *d_item0 = ds + 4 * R,
             *d_nchunk = ds + 5 * R;
-  flk::AttnWork aw{(const int2*)(ds + 6 * R), d_slot, d_len, d_item0, d_nchunk, c->pml, c->po, n_items, flk::attn_chunk()};
+  flk::AttnWork aw{(const int2*)(ds + 6 * R), d_slot, d_len, d_item0, d_nchunk, ln.pml, ln.po, n_items, flk::attn_chunk()};
   aw.blocks = (const int4*)(ds + 6 * R + 2 * n_items);
   aw.n_blocks = n_blocks;
+  const bool prof = &ln == &c->step_lane;
 
   int launches = 0;
-  const size_t ss_qkv = (size_t)n * c->p_qkv.ldc, ss_h = (size_t)n * c->p_o.ldc, ss_1 = (size_t)n * c->p_1.ldc,
+  // K slicing: the iteration's is fixed by the matrix shape; a context pass holds rows of one request only and may
+  // slice by that request's row count as well (still independent of what else is in flight)
+  const flk::GemmPlan p_qkv = context_pass ? flk::context_plan(c->p_qkv, f.dtype, n) : c->p_qkv;
+  const flk::GemmPlan p_o = context_pass ? flk::context_plan(c->p_o, f.dtype, n) : c->p_o;
+  const flk::GemmPlan p_1 = context_pass ? flk::context_plan(c->p_1, f.dtype, n) : c->p_1;
+  const flk::GemmPlan p_2 = context_pass ? flk::context_plan(c->p_2, f.dtype, n) : c->p_2;
+  const size_t ss_qkv = (size_t)n * p_qkv.ldc, ss_h = (size_t)n * p_o.ldc, ss_1 = (size_t)n * p_1.ldc,
                ss_v = (size_t)n * c->p_lm.ldc;
-  HIPCHK(c, flk::embed(f.dtype, c->wte, c->wpe, d_tok, d_pos, c->x, n, H, st));
+  HIPCHK(c, flk::embed(f.dtype, c->wte, c->wpe, d_tok, d_pos, ln.x, n, H, st));
   ++launches;
   for (int l = 0; l < L; ++l) {
     const LayerW& w = c->lw[l];
     const bool first = l == 0;
-    HIPCHK(c, flk::add_norm(f.dtype, !gpt, c->x, first ? nullptr : c->part, c->p_2.S, ss_h, c->p_2.ldc,
+    HIPCHK(c, flk::add_norm(f.dtype, !gpt, ln.x, first ? nullptr : ln.part, p_2.S, ss_h, p_2.ldc,
                             first ? nullptr : c->lw[l - 1].b2,
-                            w.ln1_g, w.ln1_b, c->h, n, H, f.norm_eps, st));
-    HIPCHK(c, timed_gemm(c, FLOVER_PROF_GEMM_QKV, c->h, w.wqkv, n, c->p_qkv, ss_qkv));
+                            w.ln1_g, w.ln1_b, ln.h, n, H, f.norm_eps, st));
+    HIPCHK(c, timed_gemm(c, ln, FLOVER_PROF_GEMM_QKV, ln.h, w.wqkv, n, p_qkv, ss_qkv));
     char* kl = c->kv + (size_t)(2 * l) * c->plane_bytes;
     char* vl = kl + c->plane_bytes;
-    HIPCHK(c, flk::qkv_post(f.dtype, c->part, c->p_qkv.S, ss_qkv, c->p_qkv.ldc, w.bqkv, c->rope_cs, d_slot, d_pos, c->q, kl, vl, n, H, nh,
+    HIPCHK(c, flk::qkv_post(f.dtype, ln.part, p_qkv.S, ss_qkv, p_qkv.ldc, w.bqkv, c->rope_cs, d_slot, d_pos, ln.q, kl, vl, n, H, nh,
                             d, f.max_seq, st));
     if (context_pass) {
-      HIPCHK(c, flk::prefill_attention(f.dtype, d, c->q, kl, vl, aw, n, nh, f.max_seq, c->att, st));
+      HIPCHK(c, flk::prefill_attention(f.dtype, d, ln.q, kl, vl, aw, n, nh, f.max_seq, ln.att, st));
     } else {
-      const int pi = prof_begin(c, FLOVER_PROF_ATTENTION, attn_bytes);
-      HIPCHK(c, flk::decode_attention(f.dtype, d, c->q, kl, vl, aw, n, nh, f.max_seq, c->att, st,
+      const int pi = prof ? prof_begin(c, FLOVER_PROF_ATTENTION, attn_bytes) : -1;
+      HIPCHK(c, flk::decode_attention(f.dtype, d, ln.q, kl, vl, aw, n, nh, f.max_seq, ln.att, st,
                                       pi >= 0 ? c->ev[2 * pi] : nullptr, pi >= 0 ? c->ev[2 * pi + 1] : nullptr));
     }
-    HIPCHK(c, timed_gemm(c, FLOVER_PROF_GEMM_OUT, c->att, w.wo, n, c->p_o, ss_h));
-    HIPCHK(c, flk::add_norm(f.dtype, !gpt, c->x, c->part, c->p_o.S, ss_h, c->p_o.ldc, w.bo, w.ln2_g, w.ln2_b, c->h, n, H, f.norm_eps, st));
-    HIPCHK(c, timed_gemm(c, FLOVER_PROF_GEMM_FF1, c->h, w.w1, n, c->p_1, ss_1));
-    HIPCHK(c, flk::activation(f.dtype, !gpt, c->part, c->p_1.S, ss_1, c->p_1.ldc, w.b1, c->act, n, F, st));
-    HIPCHK(c, timed_gemm(c, FLOVER_PROF_GEMM_FF2, c->act, w.w2, n, c->p_2, ss_h));
+    HIPCHK(c, timed_gemm(c, ln, FLOVER_PROF_GEMM_OUT, ln.att, w.wo, n, p_o, ss_h));
+    HIPCHK(c, flk::add_norm(f.dtype, !gpt, ln.x, ln.part, p_o.S, ss_h, p_o.ldc, w.bo, w.ln2_g, w.ln2_b, ln.h, n, H, f.norm_eps, st));
+    HIPCHK(c, timed_gemm(c, ln, FLOVER_PROF_GEMM_FF1, ln.h, w.w1, n, p_1, ss_1));
+    HIPCHK(c, flk::activation(f.dtype, !gpt, ln.part, p_1.S, ss_1, p_1.ldc, w.b1, ln.act, n, F, st));
+    HIPCHK(c, timed_gemm(c, ln, FLOVER_PROF_GEMM_FF2, ln.act, w.w2, n, p_2, ss_h));
     launches += 10;
   }
   if (want_tokens) {
-    HIPCHK(c, flk::add_norm(f.dtype, !gpt, c->x, c->part, c->p_2.S, ss_h, c->p_2.ldc, c->lw[L - 1].b2, c->lnf_g, c->lnf_b, c->h, n, H,
+    HIPCHK(c, flk::add_norm(f.dtype, !gpt, ln.x, ln.part, c->p_2.S, ss_h, c->p_2.ldc, c->lw[L - 1].b2, c->lnf_g, c->lnf_b, ln.h, n, H,
                             f.norm_eps, st));
-    HIPCHK(c, timed_gemm(c, FLOVER_PROF_GEMM_LM, c->h, c->wlm, n, c->p_lm, ss_v));
-    HIPCHK(c, flk::logits_argmax(c->part, c->p_lm.S, ss_v, c->p_lm.ldc, logits_out, c->tok_out, n, V, st));
-    HIPCHK(c, hipMemcpyAsync(c->h_tok, c->tok_out, (size_t)n * 4, hipMemcpyDeviceToHost, st));
+    HIPCHK(c, timed_gemm(c, ln, FLOVER_PROF_GEMM_LM, ln.h, c->wlm, n, c->p_lm, ss_v));
+    HIPCHK(c, flk::logits_argmax(ln.part, c->p_lm.S, ss_v, c->p_lm.ldc, logits_out, ln.tok_out, n, V, st));
+    HIPCHK(c, hipMemcpyAsync(ln.h_tok, ln.tok_out, (size_t)n * 4, hipMemcpyDeviceToHost, st));
     launches += 3;
   }
-  HIPCHK(c, hipStreamSynchronize(st));   // staging buffers are reused by the next call
-  prof_collect(c);
-  c->launches += launches;
+  if (wait) {
+    HIPCHK(c, hipStreamSynchronize(st));
+    if (prof) prof_collect(c);
+  }
+  if (prof) c->launches += launches;
   return FLOVER_OK;
 }
 
 // Pre-processing (Section V-B): the context decoder caches K/V of prompt positions 0..P-2 in the assigned slot.
+// Synchronous mode: returns when the cache is complete.  Asynchronous mode: the passes are enqueued on the
+// pre-processing lane and the slot's event marks their end; the request joins the first iteration that finds it done.
 int preprocess(flover_ctx* c, int slot, const Waiting& r) {
   Slot& s = c->slots[slot];
   s.state = FLOVER_SLOT_READY;
   s.req_id = r.req_id;
   s.generated = 0;
   s.max_new = r.max_new;
+  s.pending = false;
+  s.ev = -1;
+  const bool async = c->cfg.async_preprocess != 0;
+  Lane& ln = *c->prep_lane;
   const int P = (int)r.prompt.size();
   std::vector<Row> rows;
   for (int p0 = 0; p0 + 1 < P; p0 += c->rows_cap) {
     const int n = std::min(c->rows_cap, P - 1 - p0);
     rows.resize(n);
     for (int i = 0; i < n; ++i) rows[i] = Row{slot, r.prompt[p0 + i], p0 + i};
-    int rc = run_rows(c, rows.data(), n, false, nullptr, true);
+    int rc = run_rows(c, ln, rows.data(), n, false, nullptr, true, !async);
     if (rc != FLOVER_OK) return rc;
+  }
+  if (async && P > 1) {
+    HIPCHK(c, hipEventRecord(c->prep_ev[slot], ln.st));
+    s.pending = true;
+    s.ev = slot;
   }
   s.len = P - 1;
   s.next_token = r.prompt[P - 1];
@@ -397,6 +453,31 @@ int copy_in(flover_ctx* c, void* dst, const void* src, size_t bytes, const char*
   return FLOVER_OK;
 }
 
+// Frees what the context owns outside the arena (pinned staging, events, the pre-processing stream).
+void release(flover_ctx* c) {
+  for (Lane* ln : {&c->step_lane, &c->prep_lane_own}) {
+    for (int i = 0; i < kStageRing; ++i) {
+      if (ln->h_stage[i]) (void)hipHostFree(ln->h_stage[i]);
+      if (ln->staged[i]) (void)hipEventDestroy(ln->staged[i]);
+    }
+    if (ln->h_tok) (void)hipHostFree(ln->h_tok);
+  }
+  if (c->h_moves) (void)hipHostFree(c->h_moves);
+  for (hipEvent_t e : c->prep_ev)
+    if (e) (void)hipEventDestroy(e);
+  for (hipEvent_t e : c->ev) (void)hipEventDestroy(e);
+  if (c->prep_lane_own.st) (void)hipStreamDestroy(c->prep_lane_own.st);
+}
+
+// True once the slot's context cache is complete; makes the iteration's stream wait for it.
+bool context_ready(flover_ctx* c, Slot& s) {
+  if (!s.pending) return true;
+  if (hipEventQuery(c->prep_ev[s.ev]) != hipSuccess) return false;
+  (void)hipStreamWaitEvent(c->st, c->prep_ev[s.ev], 0);
+  s.pending = false;
+  return true;
+}
+
 }  // namespace
 
 // ===================================================================== public API
@@ -433,9 +514,7 @@ int32_t flover_init(const flover_config* cfg, const flover_weights* w, flover_ct
   }
   auto bail = [&](int code) {
     g_err = c->err;
-    if (c->h_stage) (void)hipHostFree(c->h_stage);
-    if (c->h_tok) (void)hipHostFree(c->h_tok);
-    if (c->h_moves) (void)hipHostFree(c->h_moves);
+    release(c);
     delete c;
     return code;
   };
@@ -452,20 +531,30 @@ int32_t flover_init(const flover_config* cfg, const flover_weights* w, flover_ct
       return bail(FLOVER_E_HIP);                                                      \
     }                                                                                 \
   } while (0)
-  c->h_stage = nullptr;
-  c->h_tok = nullptr;
   c->h_moves = nullptr;
-  HIPTRY(hipHostMalloc((void**)&c->h_stage, c->stage_ints * 4, hipHostMallocDefault));
-  HIPTRY(hipHostMalloc((void**)&c->h_tok, (size_t)c->rows_cap * 4, hipHostMallocDefault));
+  c->step_lane.st = c->st;
+  c->prep_lane = cfg->async_preprocess ? &c->prep_lane_own : &c->step_lane;
+  HIPTRY(hipHostMalloc((void**)&c->step_lane.h_stage[0], c->stage_ints * 4, hipHostMallocDefault));
+  HIPTRY(hipHostMalloc((void**)&c->step_lane.h_tok, (size_t)c->rows_cap * 4, hipHostMallocDefault));
   HIPTRY(hipHostMalloc((void**)&c->h_moves, (size_t)cfg->max_concurrency * sizeof(int4), hipHostMallocDefault));
+  if (cfg->async_preprocess) {
+    Lane& pl = c->prep_lane_own;
+    HIPTRY(hipStreamCreateWithFlags(&pl.st, hipStreamNonBlocking));   // default priority
+    pl.ring = kStageRing;
+    for (int i = 0; i < kStageRing; ++i) {
+      HIPTRY(hipHostMalloc((void**)&pl.h_stage[i], c->stage_ints * 4, hipHostMallocDefault));
+      HIPTRY(hipEventCreateWithFlags(&pl.staged[i], hipEventDisableTiming));
+    }
+    c->prep_ev.assign(cfg->max_concurrency, nullptr);
+    for (int i = 0; i < cfg->max_concurrency; ++i) HIPTRY(hipEventCreateWithFlags(&c->prep_ev[i], hipEventDisableTiming));
+  }
 
   const flover_config& f = c->cfg;
   const int e = esize(f.dtype), L = f.n_layer, H = f.hidden, F = f.ffn, V = f.vocab, S = f.max_seq;
   const bool gpt = f.arch == FLOVER_ARCH_GPT;
   hipStream_t st = c->st;
   // everything the kernels may read before it is written starts at zero (padding tiles, cache, row buffers)
-  const size_t act_off = (char*)c->x - (char*)cfg->arena;
-  HIPTRY(flk::zero_fill(c->x, need - act_off, st));
+  HIPTRY(flk::zero_fill((char*)cfg->arena + c->act_off, need - c->act_off, st));
   for (int l = 0; l < L; ++l) {
     LayerW& lw = c->lw[l];
     const size_t o1 = (size_t)l * H * e;
@@ -531,10 +620,8 @@ int32_t flover_init(const flover_config* cfg, const flover_weights* w, flover_ct
 int32_t flover_destroy(flover_ctx* ctx) {
   if (!ctx) return FLOVER_OK;
   (void)hipStreamSynchronize(ctx->st);
-  (void)hipHostFree(ctx->h_stage);
-  (void)hipHostFree(ctx->h_tok);
-  (void)hipHostFree(ctx->h_moves);
-  for (hipEvent_t e : ctx->ev) (void)hipEventDestroy(e);
+  if (ctx->prep_lane_own.st) (void)hipStreamSynchronize(ctx->prep_lane_own.st);
+  release(ctx);
   delete ctx;
   return FLOVER_OK;
 }
@@ -546,6 +633,7 @@ int32_t flover_add_request(flover_ctx* c, uint64_t req_id, const int32_t* prompt
   if (P < 1 || max_new < 1 || P + max_new > f.max_seq) return fail(c, FLOVER_E_INVAL, "prompt_len / max_new_tokens out of range");
   for (int i = 0; i < P; ++i)
     if (prompt[i] < 0 || prompt[i] >= f.vocab) return fail(c, FLOVER_E_INVAL, "prompt token out of range");
+  std::lock_guard<std::mutex> lock(c->mu);
   if (known(c, req_id)) return fail(c, FLOVER_E_INVAL, "req_id already waiting or live");
   Waiting r{req_id, std::vector<int32_t>(prompt, prompt + P), max_new};
   int slot = -1;
@@ -567,6 +655,7 @@ int32_t flover_add_request_cached(flover_ctx* c, uint64_t req_id, int32_t contex
   if (context_len < 0 || max_new < 1 || context_len + 1 + max_new > f.max_seq)
     return fail(c, FLOVER_E_INVAL, "context_len / max_new_tokens out of range");
   if (next_token < 0 || next_token >= f.vocab) return fail(c, FLOVER_E_INVAL, "token out of range");
+  std::lock_guard<std::mutex> lock(c->mu);
   if (known(c, req_id)) return fail(c, FLOVER_E_INVAL, "req_id already waiting or live");
   if (!c->reque.empty()) return fail(c, FLOVER_E_FULL, "requests are waiting for a slot");
   const int slot = place(c);
@@ -578,12 +667,14 @@ int32_t flover_add_request_cached(flover_ctx* c, uint64_t req_id, int32_t contex
   s.max_new = max_new;
   s.len = context_len;
   s.next_token = next_token;
+  s.pending = false;
   if (out_slot) *out_slot = slot;
   return FLOVER_OK;
 }
 
 int32_t flover_step(flover_ctx* c, flover_step_out* out) {
   if (!c || !out) return fail(c, FLOVER_E_INVAL, "null argument");
+  std::unique_lock<std::mutex> lock(c->mu);
   c->launches = 0;
   while (!c->reque.empty()) {        // waiting requests take freed adjacent slots in arrival order
     int slot = place(c);
@@ -595,13 +686,25 @@ int32_t flover_step(flover_ctx* c, flover_step_out* out) {
   c->launches = 0;                   // pre-processing is not part of the fused iteration's count
   std::vector<Row> rows;
   std::vector<int> live;
-  for (int i = c->lo; i < c->hi; ++i) {   // Update(offset,size): every ready request joins
-    Slot& s = c->slots[i];
-    if (s.state == FLOVER_SLOT_READY) s.state = FLOVER_SLOT_LIVE;
-    if (s.state == FLOVER_SLOT_LIVE) {
-      live.push_back(i);
-      rows.push_back(Row{i, s.next_token, s.len});
+  for (;;) {
+    int oldest_pending = -1;
+    for (int i = c->lo; i < c->hi; ++i) {   // Update(offset,size): every ready request joins
+      Slot& s = c->slots[i];
+      if (s.state == FLOVER_SLOT_READY) {
+        if (context_ready(c, s)) s.state = FLOVER_SLOT_LIVE;
+        else if (oldest_pending < 0) oldest_pending = s.ev;
+      }
+      if (s.state == FLOVER_SLOT_LIVE) {
+        live.push_back(i);
+        rows.push_back(Row{i, s.next_token, s.len});
+      }
     }
+    if (!live.empty() || oldest_pending < 0) break;
+    // nothing to generate yet but a context cache is being written: wait for one instead of returning empty-handed
+    hipEvent_t e = c->prep_ev[oldest_pending];
+    lock.unlock();
+    HIPCHK(c, hipEventSynchronize(e));
+    lock.lock();
   }
   const int n = (int)live.size();
   if (out->capacity < n) return fail(c, FLOVER_E_INVAL, "flover_step_out.capacity too small");
@@ -612,13 +715,18 @@ int32_t flover_step(flover_ctx* c, flover_step_out* out) {
   c->last_launches = 0;
   if (n == 0) return FLOVER_OK;
   c->in_step = true;
-  int rc = run_rows(c, rows.data(), (int)rows.size(), true, out->logits, false);
+  // with its own pre-processing lane flover_add_request may run beside the iteration: the scheduler lock is not
+  // held while the GPU works
+  const bool async = c->cfg.async_preprocess != 0;
+  if (async) lock.unlock();
+  int rc = run_rows(c, c->step_lane, rows.data(), (int)rows.size(), true, out->logits, false, true);
+  if (async) lock.lock();
   c->in_step = false;
   if (rc != FLOVER_OK) return rc;
   c->last_launches = c->launches;
   for (int j = 0; j < n; ++j) {
     Slot& s = c->slots[live[j]];
-    const int t = c->h_tok[j];
+    const int t = c->step_lane.h_tok[j];
     s.len += 1;
     s.generated += 1;
     s.next_token = t;
@@ -634,6 +742,7 @@ int32_t flover_step(flover_ctx* c, flover_step_out* out) {
 
 int32_t flover_mark_finished(flover_ctx* c, uint64_t req_id) {
   if (!c) return FLOVER_E_INVAL;
+  std::lock_guard<std::mutex> lock(c->mu);
   for (Slot& s : c->slots)
     if ((s.state == FLOVER_SLOT_LIVE || s.state == FLOVER_SLOT_READY) && s.req_id == req_id) {
       s.state = FLOVER_SLOT_DEAD;
@@ -645,6 +754,7 @@ int32_t flover_mark_finished(flover_ctx* c, uint64_t req_id) {
 int32_t flover_set_next_token(flover_ctx* c, uint64_t req_id, int32_t token) {
   if (!c) return FLOVER_E_INVAL;
   if (token < 0 || token >= c->cfg.vocab) return fail(c, FLOVER_E_INVAL, "token out of range");
+  std::lock_guard<std::mutex> lock(c->mu);
   for (Slot& s : c->slots)
     if ((s.state == FLOVER_SLOT_LIVE || s.state == FLOVER_SLOT_READY) && s.req_id == req_id) {
       s.next_token = token;
@@ -658,10 +768,13 @@ int32_t flover_reorder_evict(flover_ctx* c, flover_reorder_out* out) {
   const flover_config& f = c->cfg;
   const int C = f.max_concurrency;
   if (out->capacity < C) return fail(c, FLOVER_E_INVAL, "flover_reorder_out.capacity must be >= max_concurrency");
+  std::lock_guard<std::mutex> lock(c->mu);
   int n_ev = 0;
   for (int i = 0; i < C; ++i)
     if (c->slots[i].state == FLOVER_SLOT_DEAD) {
       if (out->evicted_req_id) out->evicted_req_id[n_ev] = c->slots[i].req_id;
+      if (c->slots[i].pending)   // a context pass may still be writing this slot: later copies into it wait
+        HIPCHK(c, hipStreamWaitEvent(c->st, c->prep_ev[c->slots[i].ev], 0));
       ++n_ev;
       c->slots[i] = Slot();
     }
@@ -694,6 +807,8 @@ int32_t flover_reorder_evict(flover_ctx* c, flover_reorder_out* out) {
         if (out->move_src) out->move_src[i] = a;
         if (out->move_dst) out->move_dst[i] = b;
         const int len = c->slots[a].len;
+        if (c->slots[a].pending)   // its context cache is still being written: the copy waits for it
+          HIPCHK(c, hipStreamWaitEvent(c->st, c->prep_ev[c->slots[a].ev], 0));
         bytes += 2LL * len * 2 * f.n_layer * f.hidden * esize(f.dtype);
         if (len > 0) {
           const int seg_bytes = len * row_bytes;
@@ -712,6 +827,7 @@ int32_t flover_reorder_evict(flover_ctx* c, flover_reorder_out* out) {
                                flk::kCompactPiece, c->st));
         if (pi >= 0) (void)hipEventRecord(c->ev[2 * pi + 1], c->st);
         HIPCHK(c, hipStreamSynchronize(c->st));   // following iterations wait until memory is in order (Section V-D)
+        for (int i = 0; i < n_moves; ++i) c->slots[holes[i]].pending = false;   // the copy waited for their caches
         prof_collect(c);
       }
       c->lo = old_lo + off;
@@ -736,6 +852,7 @@ int32_t flover_reorder_evict(flover_ctx* c, flover_reorder_out* out) {
 int32_t flover_get_state(const flover_ctx* c, int32_t* lo_hi_wait, int32_t* state, uint64_t* req_id, int32_t* len,
                          int32_t* next_token, int32_t* generated) {
   if (!c) return FLOVER_E_INVAL;
+  std::lock_guard<std::mutex> lock(c->mu);
   if (lo_hi_wait) {
     lo_hi_wait[0] = c->lo;
     lo_hi_wait[1] = c->hi;

@@ -19,6 +19,9 @@ struct GemmPlan {
 inline int part_ld(int N) { return (N + 3) / 4 * 4; }
 GemmPlan gemm_plan(int dtype, int N, int K);
 size_t gemm_tiled_bytes(int dtype, int N, int K);
+// Slicing for a context pass of M rows of one request (a function of the matrix shape and of that request's own row
+// count only): same tiling, fewer K slices.
+GemmPlan context_plan(const GemmPlan& p, int dtype, int M);
 // Re-tile W [N][K] into `tiled` starting at output column n_off (multiple of 16) of a possibly larger matrix whose
 // plan uses NT n-tiles per column group.
 hipError_t retile(int dtype, const void* W, int N, int K, void* tiled, int n_off, int NT, hipStream_t st);
@@ -27,7 +30,9 @@ hipError_t zero_fill(void* p, size_t bytes, hipStream_t st);
 hipError_t gemm(int dtype, const void* x, const void* w_tiled, int M, const GemmPlan& p, float* part,
                 size_t slice_stride, hipStream_t st);
 // rows of x that gemm() may read for M live rows
-inline int gemm_rows_read(int M) { return M <= 16 ? 16 : M <= 32 ? 32 : M <= 64 ? 64 : (M + 127) / 128 * 128; }
+inline int gemm_rows_read(int M) {
+  return M <= 16 ? 16 : M <= 32 ? 32 : M <= 64 ? 64 : M <= 128 ? 128 : (M + 255) / 256 * 256;
+}
 
 // ---- row-wise kernels
 hipError_t embed(int dtype, const void* wte, const void* wpe, const int* tok, const int* pos, float* x, int M, int H,

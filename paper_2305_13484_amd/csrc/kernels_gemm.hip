@@ -233,6 +233,111 @@ __global__ __launch_bounds__(64 * 4 * (NT / NTW)) void gemm16_lds_kernel(const u
     }
 }
 
+// ---- context passes (hundreds of rows): the contraction is MFMA-bound there, so each wave keeps a 128 x 64 output
+// tile (MTW = 8 row tiles x NT = 4 n-tiles, 128 accumulator registers): per k-block 32 MFMAs for 8 KiB of LDS reads and
+// 4 KiB of W loads, which halves the operand traffic per flop of the 128-row kernel above (whose waves own 128 x 32).
+// A block is 4 column groups x 2 row halves = 8 waves over 256 rows x 256 columns; x tile and W ring as above.
+// The per-(m, n) arithmetic is again the same MFMA sequence over k.
+template <int DT, int MTW, int NT, int KC, int PF>
+__global__ __launch_bounds__(512) void gemm16_rows_kernel(const uint16_t* __restrict__ x, const u32x4_t* __restrict__ wt,
+                                                          float* __restrict__ part, int M, int N, int K, int ngroups,
+                                                          int KB, int kbs, size_t slice_stride, int ldc, int nx,
+                                                          int nslices, int nz) {
+  static_assert(PF % KC == 0, "ring shape");
+  constexpr int MTB = 2 * MTW;                   // row tiles per block
+  constexpr int NW = 8;
+  __shared__ u32x4_t lds[2][KC * MTB * 64];
+  constexpr int FPW = (KC * MTB + NW - 1) / NW;
+  constexpr int CPR = PF / KC;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int xcd = blockIdx.x & 7, qq = blockIdx.x >> 3;     // row blocks of one task share an XCD (see above)
+  const int zb = qq % nz, task = (qq / nz) * 8 + xcd;
+  if (task >= nx * nslices) return;
+  const int bx = task % nx, s = task / nx;
+  const int g = bx * 4 + (wave >> 1), half = wave & 1;
+  const int gl = min(g, ngroups - 1);
+  const int m0 = zb * (16 * MTB);
+  const int kb0 = s * kbs;
+  const int kb1 = min(KB, kb0 + kbs);
+  const int nchunks = (kb1 - kb0 + KC - 1) / KC;
+  const int live_tiles = min(MTW, max(0, (M - m0 - half * (16 * MTW) + 15) / 16));   // of this wave's MTW row tiles
+
+  f32x4_t acc[MTW][NT];
+#pragma unroll
+  for (int i = 0; i < MTW; ++i)
+#pragma unroll
+    for (int t = 0; t < NT; ++t) acc[i][t] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+
+  const u32x4_t* wp = wt + ((size_t)gl * KB) * NT * 64 + lane;     // + (kb*NT + t)*64
+  const uint16_t* xp = x + (size_t)(m0 + (lane & 15)) * K + (lane >> 4) * 8;
+
+  u32x4_t bq[PF][NT], areg[FPW];
+#pragma unroll
+  for (int j = 0; j < PF; ++j) {
+    const int kk = min(kb0 + j, kb1 - 1);
+#pragma unroll
+    for (int t = 0; t < NT; ++t) bq[j][t] = wp[((size_t)kk * NT + t) * 64];
+  }
+  auto load_a = [&](int chunk) {
+#pragma unroll
+    for (int j = 0; j < FPW; ++j) {
+      const int f = min(wave + NW * j, KC * MTB - 1), kc = f / MTB, i = f - kc * MTB;
+      const int kk = min(kb0 + chunk * KC + kc, kb1 - 1);
+      areg[j] = *(const u32x4_t*)(xp + (size_t)i * 16 * K + kk * 32);
+    }
+  };
+  auto store_a = [&](int buf) {
+#pragma unroll
+    for (int j = 0; j < FPW; ++j)
+      if (wave + NW * j < KC * MTB) lds[buf][(wave + NW * j) * 64 + lane] = areg[j];
+  };
+  load_a(0);
+  store_a(0);
+  __syncthreads();
+  for (int c0 = 0; c0 < nchunks; c0 += CPR) {
+#pragma unroll
+    for (int cc = 0; cc < CPR; ++cc) {
+      const int c = c0 + cc;
+      if (c < nchunks) {
+        const bool more = c + 1 < nchunks;
+        if (more) load_a(c + 1);
+        const u32x4_t* la = lds[c & 1];
+#pragma unroll
+        for (int kc = 0; kc < KC; ++kc) {
+          const int kb = kb0 + c * KC + kc;
+          if (kb < kb1) {
+#pragma unroll
+            for (int i = 0; i < MTW; ++i)
+              if (i < live_tiles) {               // wave-uniform: row tiles past M are skipped
+                const u32x4_t af = la[(kc * MTB + half * MTW + i) * 64 + lane];
+#pragma unroll
+                for (int t = 0; t < NT; ++t) acc[i][t] = mfma16<DT>(af, bq[cc * KC + kc][t], acc[i][t]);
+              }
+          }
+          const int kk = min(kb + PF, kb1 - 1);
+#pragma unroll
+          for (int t = 0; t < NT; ++t) bq[cc * KC + kc][t] = wp[((size_t)kk * NT + t) * 64];
+        }
+        if (more) store_a((c + 1) & 1);
+        __syncthreads();
+      }
+    }
+  }
+  if (g >= ngroups) return;
+  float* out = part + (size_t)s * slice_stride;
+#pragma unroll
+  for (int i = 0; i < MTW; ++i)
+#pragma unroll
+    for (int t = 0; t < NT; ++t) {
+      const int n = (g * NT + t) * 16 + (lane & 15);
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        const int m = m0 + (half * MTW + i) * 16 + (lane >> 4) * 4 + r;
+        if (m < M && n < N) out[(size_t)m * ldc + n] = acc[i][t][r];
+      }
+    }
+}
+
 // ---------------------------------------------------------------- fp32 FMA kernel (tiny models)
 
 // one wave per output column, 8 rows at a time; lanes stride K, fixed butterfly reduction.
@@ -300,6 +405,20 @@ size_t gemm_tiled_bytes(int dtype, int N, int K) {
   return Npad * K * 2;
 }
 
+// Context passes: fewer K slices, just enough for the (column block, row block, slice) tasks to fill the chip; the
+// partial sums written and re-read per slice are what limits a many-row contraction otherwise.
+GemmPlan context_plan(const GemmPlan& p, int dtype, int M) {
+  GemmPlan q = p;
+  if (dtype == DT_F32 || M <= 128) return q;
+  const int ngroups = p.Npad / (16 * p.NT);
+  const int nx = (ngroups + 3) / 4, nz = (M + 255) / 256;
+  const int want = (256 + (nx * nz) / 2) / (nx * nz);
+  q.S = std::max(1, std::min(p.S, want));
+  q.kbs = (p.KB + q.S - 1) / q.S;
+  q.S = (p.KB + q.kbs - 1) / q.kbs;
+  return q;
+}
+
 hipError_t retile(int dtype, const void* W, int N, int K, void* tiled, int n_off, int NT, hipStream_t st) {
   if (dtype == DT_F32)
     return hipMemcpyAsync((char*)tiled + (size_t)n_off * K * 4, W, (size_t)N * K * 4, hipMemcpyDeviceToDevice, st);
@@ -330,11 +449,21 @@ static void launch_lds(const void* x, const void* wt, float* part, int M, const 
 }
 
 template <int DT, int NT>
+static void launch_rows(const void* x, const void* wt, float* part, int M, const GemmPlan& p, size_t ss, hipStream_t st) {
+  const int ngroups = p.Npad / (16 * NT);
+  const int nx = (ngroups + 3) / 4, nz = (M + 255) / 256;
+  const int tasks8 = (nx * p.S + 7) / 8 * 8;
+  gemm16_rows_kernel<DT, 8, NT, 2, 2><<<dim3(tasks8 * nz), 512, 0, st>>>(
+      (const uint16_t*)x, (const u32x4_t*)wt, part, M, p.N, p.K, ngroups, p.KB, p.kbs, ss, p.ldc, nx, p.S, nz);
+}
+
+template <int DT, int NT>
 static void dispatch16(const void* x, const void* wt, float* part, int M, const GemmPlan& p, size_t ss, hipStream_t st) {
   if (M <= 16) launch_direct<DT, 1, NT, 8, 8>(x, wt, part, M, p, ss, st);
   else if (M <= 32) launch_lds<DT, 2, NT, NT, 4>(x, wt, part, M, p, ss, st);     // 4 waves, one per column group
   else if (M <= 64) launch_lds<DT, 4, NT, 2, 4>(x, wt, part, M, p, ss, st);      // 8 waves, two per column group
-  else launch_lds<DT, 8, NT, 2, 4>(x, wt, part, M, p, ss, st);
+  else if (M <= 128) launch_lds<DT, 8, NT, 2, 4>(x, wt, part, M, p, ss, st);
+  else launch_rows<DT, NT>(x, wt, part, M, p, ss, st);             // row blocks of 256
 }
 
 hipError_t gemm(int dtype, const void* x, const void* wt, int M, const GemmPlan& p, float* part, size_t slice_stride,

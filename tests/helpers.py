@@ -99,10 +99,13 @@ class Lockstep:
         self.cpu.close()
 
 
-def gpu_run_stream(cfg, weights_dev, reqs, shuffle_off=False, want_logits=True):
-    """The HIP path alone over a stream; returns per-request token lists and logits (device tensors)."""
+def gpu_run_stream(cfg, weights_dev, reqs, shuffle_off=False, want_logits=True, async_preprocess=False,
+                   finish_at=None, stats=None):
+    """The HIP path alone over a stream; returns per-request token lists and logits (device tensors).
+    finish_at: {req_id: n} forces the request to finish after its n-th token (so that the shuffle has work)."""
     import paper_2305_13484_amd as fl
-    srv = fl.Flover(cfg, weights_dev, shuffle_off=shuffle_off)
+    srv = fl.Flover(cfg, weights_dev, shuffle_off=shuffle_off, async_preprocess=async_preprocess)
+    finish_at = finish_at or {}
     pending = sorted(reqs, key=lambda r: (r.arrival_step, r.req_id))
     toks, logits = {}, {}
     i, done, s = 0, 0, 0
@@ -116,8 +119,14 @@ def gpu_run_stream(cfg, weights_dev, reqs, shuffle_off=False, want_logits=True):
             toks.setdefault(rid, []).append(int(out.token[j]))
             if want_logits:
                 logits.setdefault(rid, []).append(out.logits[j].clone())
+            if not out.finished[j] and finish_at.get(rid) == len(toks[rid]):
+                srv.mark_finished(rid)
+                done += 1
         done += int(out.finished.sum())
-        srv.reorder_evict()
+        rr = srv.reorder_evict()
+        if stats is not None:
+            stats["moves"] = stats.get("moves", 0) + len(rr.moves)
+            stats["steps"] = stats.get("steps", 0) + 1
         s += 1
     srv.close()
     return toks, logits

@@ -41,7 +41,7 @@ def test_host_only_entry_point_and_argument_errors():
     assert b"bad argument" in lib.flover_last_error(None)
     assert lib.flover_k_attention_workspace_bytes(4, 8, 96, 100, ctypes.byref(n)) == -1   # head_dim 96 unsupported
     from paper_2305_13484_amd.binding import _Config
-    cfg = _Config(1, 2, 2, 512, 4, 128, 1376, 2000, 160, 16, -1, 0, 1e-6, 10000.0, None, None, 0)
+    cfg = _Config(1, 2, 2, 512, 4, 128, 1376, 2000, 160, 16, -1, 0, 0, 1e-6, 10000.0, None, None, 0)
     assert lib.flover_query_arena_bytes(ctypes.byref(cfg), ctypes.byref(n)) == 0 and n.value > 0
     cfg.hidden = 500
     assert lib.flover_query_arena_bytes(ctypes.byref(cfg), ctypes.byref(n)) == -1

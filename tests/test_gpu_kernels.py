@@ -27,7 +27,8 @@ TDT = synth.TORCH_DTYPE
 
 @pytest.mark.parametrize("dtype", [synth.DT_BF16, synth.DT_F16, synth.DT_F32])
 @pytest.mark.parametrize("M,N,K", [(1, 64, 64), (5, 100, 96), (16, 256, 512), (17, 1000, 256), (33, 130, 1024),
-                                   (70, 320, 2048), (128, 192, 4096), (200, 64, 160)])
+                                   (70, 320, 2048), (128, 192, 4096), (200, 64, 160), (300, 320, 1024),
+                                   (513, 130, 512)])
 def test_gemm_matches_oracle(dtype, M, N, K):
     print("gemm", dtype, M, N, K, flush=True)
     g = torch.Generator().manual_seed(100 + M + N)
@@ -43,11 +44,11 @@ def test_gemm_matches_oracle(dtype, M, N, K):
 def test_gemm_row_result_does_not_depend_on_other_rows(dtype):
     g = torch.Generator().manual_seed(5)
     K, N = 1024, 448
-    x = torch.randn((150, K), generator=g).to(TDT[dtype]).cuda()
+    x = torch.randn((600, K), generator=g).to(TDT[dtype]).cuda()
     W = (torch.randn((N, K), generator=g) * 0.05).to(TDT[dtype]).cuda()
     tw = fl.binding.TiledWeight(W)
     full = fl.k_gemm(x, tw)
-    for M in (1, 16, 17, 32, 64, 65, 128, 129):
+    for M in (1, 16, 17, 32, 64, 65, 128, 129, 256, 257, 400, 513):
         part = fl.k_gemm(x[:M].contiguous(), tw)
         assert torch.equal(part, full[:M]), M
     alone = fl.k_gemm(x[77:78].contiguous(), tw)

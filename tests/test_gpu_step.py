@@ -380,3 +380,73 @@ def test_randomised_scheduler_stress(mode):
     assert max_wait > 0 and ls.ties == 0
     assert (ls.moves > 0) != (mode == "off")
     ls.close()
+
+
+def _same_results(a, b, reqs):
+    toks_a, logits_a = a
+    toks_b, logits_b = b
+    for r in reqs:
+        assert toks_a[r.req_id] == toks_b[r.req_id], r.req_id
+        la, lb = torch.stack(logits_a[r.req_id]), torch.stack(logits_b[r.req_id])
+        assert torch.equal(la, lb), r.req_id
+
+
+@pytest.mark.parametrize("name", ["tiny_gpt", "small_llama16"])
+def test_async_preprocess_gives_the_same_tokens_and_logits_bitwise(name):
+    """Pre-processing on the library's second stream (Section V-B) changes only the iteration a request joins:
+    every request's tokens and logits equal the synchronous run's bit for bit, with shuffles in between."""
+    cfg = getattr(synth, name)()
+    cfg = dataclasses.replace(cfg, C=6)
+    w = to_device(synth.make_weights(cfg, 31))
+    reqs = synth.stream_small(41, cfg.V, n=16, arrive_hi=14, p_lo=1, p_hi=min(90, cfg.S - 20), g_lo=2, g_hi=16)
+    finish_at = {r.req_id: max(1, r.gen_len // 2) for r in reqs[::3]}
+    st_s, st_a = {}, {}
+    sync = gpu_run_stream(cfg, w, reqs, finish_at=finish_at, stats=st_s)
+    asyn = gpu_run_stream(cfg, w, reqs, finish_at=finish_at, stats=st_a, async_preprocess=True)
+    print("sync", st_s, "async", st_a)
+    _same_results(sync, asyn, reqs)
+    assert st_s["moves"] > 0 and st_a["moves"] > 0
+
+
+def test_add_request_from_a_second_thread_while_steps_run():
+    """The paper's pre-processing thread beside its inference thread (Section V-A): one thread submits requests while
+    another drives the fused iterations; results equal the single-threaded synchronous run bit for bit."""
+    import threading
+    import time
+    import paper_2305_13484_amd as fl
+    cfg = dataclasses.replace(synth.small_llama16(), C=5)
+    w = to_device(synth.make_weights(cfg, 32))
+    reqs = synth.stream_small(43, cfg.V, n=14, arrive_hi=10, p_lo=2, p_hi=min(80, cfg.S - 20), g_lo=3, g_hi=14)
+    ref = gpu_run_stream(cfg, w, reqs)
+    srv = fl.Flover(cfg, w, async_preprocess=True)
+    errors = []
+
+    def producer():
+        try:
+            for k, r in enumerate(sorted(reqs, key=lambda r: (r.arrival_step, r.req_id))):
+                srv.add_request(r.req_id, r.prompt, r.gen_len)
+                if k % 3 == 2:
+                    time.sleep(0.002)
+        except Exception as e:      # surfaced in the main thread
+            errors.append(e)
+
+    th = threading.Thread(target=producer)
+    th.start()
+    toks, logits = {}, {}
+    done = steps = 0
+    deadline = time.time() + 60
+    while done < len(reqs):
+        assert time.time() < deadline and not errors, errors
+        out = srv.step(True)
+        for j in range(out.n_live):
+            rid = int(out.req_id[j])
+            toks.setdefault(rid, []).append(int(out.token[j]))
+            logits.setdefault(rid, []).append(out.logits[j].clone())
+        done += int(out.finished.sum())
+        srv.reorder_evict()
+        steps += 1
+    th.join()
+    srv.close()
+    assert not errors
+    print("two threads: iterations", steps)
+    _same_results(ref, (toks, logits), reqs)
