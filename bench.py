@@ -38,6 +38,10 @@ def parse():
     ap.add_argument("--async-preprocess", action="store_true",
                     help="pre-processing on the library's second stream, beside the fused iterations (Section V-B); "
                          "flover_add_request then only enqueues, and tokens_per_s_incl_preprocess is the figure to read")
+    ap.add_argument("--pipeline", type=int, default=2, metavar="D",
+                    help="pipelined token return: keep up to D (1..3) iterations submitted before collecting the oldest "
+                         "(flover_step_submit / flover_step_collect); 0 = the synchronous flover_step, which also gives the "
+                         "per-live-row-count breakdown")
     ap.add_argument("--by-length", action="store_true",
                     help="Algorithm 3 on entries weighted by cached length (fewest bytes moved) instead of 0/1 occupancy")
     ap.add_argument("--layers", type=int, default=0, help="override the layer count (debug only; reported)")
@@ -121,6 +125,75 @@ def run_stream(srv, cfg, reqs, max_steps, cached=False, async_pre=False):
                 for n, t, sl in zip(rec_n, rec_t, rec_len)]
     return {"steps": s, "tokens": tokens, "t_steps": t_steps, "t_pre": t_pre, "moves": moves,
             "bytes_moved": bytes_moved, "per_step": per_step, "all_done": done == len(reqs)}
+
+
+def run_stream_pipelined(srv, cfg, reqs, max_steps, depth, async_pre=False):
+    """Same stream with pipelined token return.  Iterations overlap, so only totals are timed: the clock runs from
+    the first submission to the last collection, minus the time spent in flover_add_request (pre-processing; the
+    pipeline is drained before each arrival burst so that no iteration time is booked there)."""
+    import collections
+    import numpy as np
+    import torch
+    pending = sorted(reqs, key=lambda r: (r.arrival_step, r.req_id))
+    lens = {}
+    q = collections.deque()
+    i = done = s = tokens = moves = bytes_moved = 0
+    t_pre = 0.0
+    tot_bytes = 0
+    clock = time.perf_counter
+    e = __import__("flover_synth").DTYPE_BYTES[cfg.dtype]
+    kvb = cfg.kv_bytes_per_token()
+
+    def collect():
+        nonlocal done, tokens
+        out = srv.step_collect()
+        q.popleft()
+        tokens += out.n_live
+        for rid, fin in zip(out.req_id, out.finished):
+            if fin:
+                done += 1
+
+    torch.cuda.synchronize()
+    t_begin = clock()
+    live_lens = {}
+    while done < len(reqs) and (max_steps <= 0 or s < max_steps):
+        if i < len(pending) and pending[i].arrival_step <= s:
+            if not async_pre:
+                while q:
+                    collect()
+            t0 = clock()
+            while i < len(pending) and pending[i].arrival_step <= s:
+                r = pending[i]
+                srv.add_request(r.req_id, r.prompt, r.gen_len)
+                live_lens[r.req_id] = [len(r.prompt) - 1, r.gen_len]
+                i += 1
+            if not async_pre:
+                torch.cuda.synchronize()
+            t_pre += clock() - t0
+        n = srv.step_submit()
+        rr = srv.reorder_evict()
+        moves += len(rr.moves)
+        bytes_moved += rr.bytes_moved
+        s += 1
+        if n:
+            q.append(n)
+            if not async_pre:      # lengths of the rows are known on the host: every admitted request that still has budget
+                sl = 0
+                for rid in list(live_lens):
+                    ln = live_lens[rid]
+                    sl += ln[0]
+                    ln[0] += 1
+                    ln[1] -= 1
+                    if ln[1] == 0:
+                        del live_lens[rid]
+                tot_bytes += cfg.weight_bytes_per_step() + (sl + n) * kvb + n * kvb + n * cfg.H * e + n * cfg.V * 4
+        while q and (len(q) >= depth or n == 0):
+            collect()
+    while q:
+        collect()
+    total = clock() - t_begin - t_pre
+    return {"steps": s, "tokens": tokens, "t_steps": total, "t_pre": t_pre, "moves": moves, "bytes_moved": bytes_moved,
+            "per_step": [(1, total, tot_bytes)], "all_done": done == len(reqs)}
 
 
 def cpu_baseline(cfg_full, weights_dev, reqs, budget_rows=14):
@@ -320,7 +393,11 @@ def main():
         run_stream(srv, cfg, warm, 0, cached=a.cached_context, async_pre=a.async_preprocess)
 
     srv.set_profile(a.profile_level)
-    res = run_stream(srv, cfg, reqs, a.steps, cached=a.cached_context, async_pre=a.async_preprocess)
+    piped = a.pipeline if (not a.cached_context and cfg.eos_id < 0) else 0
+    if piped:
+        res = run_stream_pipelined(srv, cfg, reqs, a.steps, piped, async_pre=a.async_preprocess)
+    else:
+        res = run_stream(srv, cfg, reqs, a.steps, cached=a.cached_context, async_pre=a.async_preprocess)
     prof = srv.get_profile()
     srv.close()
 
@@ -335,14 +412,15 @@ def main():
         roof = {"bound": "hbm", "kernel": "attn_partial_kernel (ragged decode attention, one launch per layer)",
                 "achieved": round(ach, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(ach / HBM_PEAK_GBS, 4),
                 "traffic": (traffic or {}).get("bytes_per_launch"), "traffic_detail": traffic,
-                "launches": att["launches"], "avg_launch_us": round(1e3 * att["ms"] / att["launches"], 2),
+                "timed_launches": att["launches"], "timing": "HIP events around the launch, one layer in four at profile level 1",
+                "avg_launch_us": round(1e3 * att["ms"] / att["launches"], 2),
                 "avg_bytes_per_launch": att["bytes"] // att["launches"]}
     per = res["per_step"]
     tot_bytes = sum(b for _, _, b in per)
     step_gbs = tot_bytes / total / 1e9 if total > 0 else 0.0
     buckets = {}
     for lo, hi in ((1, 16), (17, 32), (33, 64), (65, 10 ** 9)):
-        sel = [(n, t, b) for n, t, b in per if lo <= n <= hi]
+        sel = [(n, t, b) for n, t, b in per if lo <= n <= hi] if not piped else []
         if sel:
             tt = sum(t for _, t, _ in sel)
             buckets["live_%d_%s" % (lo, hi if hi < 10 ** 9 else "up")] = {
@@ -361,7 +439,7 @@ def main():
         "data": "synthetic",
         "config": {"workload": wl, "layers": cfg.L, "requests": len(reqs), "whole_stream": res["all_done"],
                    "seed": a.seed, "cached_context": a.cached_context, "shuffle_off": a.shuffle_off, "by_length": a.by_length,
-                   "async_preprocess": a.async_preprocess},
+                   "async_preprocess": a.async_preprocess, "pipeline": piped},
         "tokens": res["tokens"], "mean_live": round(res["tokens"] / K, 2),
         "step_hbm_GBs": round(step_gbs, 1), "step_hbm_frac": round(step_gbs / HBM_PEAK_GBS, 4), "by_live_rows": buckets,
         "preprocess_s": round(res["t_pre"], 3), "tokens_per_s_incl_preprocess": round(res["tokens"] / (total + res["t_pre"]), 2),

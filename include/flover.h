@@ -152,6 +152,21 @@ typedef struct flover_reorder_out {
   int64_t bytes_moved;     /* out: read + written bytes of KV rows [0,len) of the moved slots */
 } flover_reorder_out;
 
+/* Pipelined form of flover_step (token return without a host wait per iteration; Algorithm 2's loop keeps the GPU
+ * busy while the previous iteration's tokens travel back).  flover_step_submit admits ready requests and enqueues one
+ * iteration; the tokens it will choose stay on the device as the next iteration's inputs.  Only without an
+ * end-of-sequence token (eos_id < 0) is it known at submission who finishes (budget exhausted), so the scheduler
+ * state -- lengths, budgets, DEAD marks -- advances at once and flover_reorder_evict / flover_add_request /
+ * the next flover_step_submit may follow immediately (all work is ordered on the stream; flover_reorder_evict does not
+ * wait then).  *n_live_out = rows of the iteration; 0 means nothing was enqueued (and nothing is to be collected).
+ * logits: optional [device][n_live][vocab] fp32, written by this iteration; must stay valid until it is collected.
+ * flover_step_collect waits for the OLDEST submitted iteration and returns what flover_step would have: rows in
+ * ascending slot order at submission time, their tokens, and the finished flags decided at submission.
+ * At most 3 iterations may be outstanding.  Errors: STATE (eos_id >= 0; flover_step while iterations are outstanding;
+ * collect with nothing submitted), FULL (4th outstanding iteration), INVAL, HIP. */
+int32_t flover_step_submit(flover_ctx* ctx, float* logits, int32_t* n_live_out);
+int32_t flover_step_collect(flover_ctx* ctx, flover_step_out* out);
+
 /* FindAndEvict's removal, Algorithm 3 and the memory shuffle (Algorithm 2's last lines, Section V-D).
  * Frees DEAD slots; over the 0/1 occupancy of the old window finds, with the sliding window of Algorithm 3
  * (first window scored too, lowest offset on ties), the region of size #valid that leaves the fewest valid
@@ -189,9 +204,12 @@ int32_t flover_get_kv_cache(const flover_ctx* ctx, void** base, uint64_t* bytes)
 int32_t flover_last_step_launches(const flover_ctx* ctx, int32_t* n);
 
 /* Kernel timing with HIP events on the context's stream (measurement aid, not in the paper).
- * level 0 = off, 1 = the attention streaming kernel of every layer, 2 = also every weight GEMM; the shuffle copy is
- * timed at levels 1 and 2.  Setting the level clears the totals.  flover_get_profile returns, for one kind, the summed
- * duration (ms), the number of launches and the summed algorithmic bytes of those launches: for attention the K and V
+ * level 0 = off, 1 = the attention streaming kernel of one layer in four (layers 0, 4, 8, ...: two event records per
+ * launch cost about as much as a small kernel, and the layers' launches are alike), 2 = the attention kernel of every
+ * layer and every weight GEMM; the shuffle copy is timed at levels 1 and 2.  Iterations submitted with
+ * flover_step_submit are timed too (added up when they are collected).  Setting the level clears the totals.
+ * flover_get_profile returns, for one kind, the summed duration (ms), the number of TIMED launches and the summed
+ * algorithmic bytes of those launches: for attention the K and V
  * rows [0,len) of every row; for a GEMM the weight matrix; for the shuffle copy bytes read + written. */
 enum { FLOVER_PROF_ATTENTION = 0, FLOVER_PROF_GEMM_QKV = 1, FLOVER_PROF_GEMM_OUT = 2, FLOVER_PROF_GEMM_FF1 = 3,
        FLOVER_PROF_GEMM_FF2 = 4, FLOVER_PROF_GEMM_LM = 5, FLOVER_PROF_COMPACT = 6, FLOVER_PROF_KINDS = 7 };

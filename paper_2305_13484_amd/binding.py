@@ -18,7 +18,7 @@ _LIB_PATH = os.path.join(_HERE, "libflover.so")
 EXPORTED_SYMBOLS = [
     "flover_query_arena_bytes", "flover_init", "flover_destroy", "flover_last_error", "flover_add_request",
     "flover_step", "flover_reorder_evict", "flover_mark_finished", "flover_set_next_token", "flover_get_state",
-    "flover_get_kv_cache", "flover_last_step_launches", "flover_set_profile", "flover_get_profile", "flover_k_find_window", "flover_k_attention_workspace_bytes",
+    "flover_get_kv_cache", "flover_last_step_launches", "flover_step_submit", "flover_step_collect", "flover_set_profile", "flover_get_profile", "flover_k_find_window", "flover_k_attention_workspace_bytes",
     "flover_k_decode_attention", "flover_k_compact_workspace_bytes", "flover_k_compact", "flover_k_gemm_tiled_bytes",
     "flover_k_gemm_workspace_bytes", "flover_k_gemm_retile", "flover_k_gemm", "flover_add_request_cached",
     "flover_k_copy_probe",
@@ -82,6 +82,8 @@ def load_library():
                                             C.POINTER(C.c_int32)]
     L.flover_k_copy_probe.argtypes = [C.c_void_p, C.c_void_p, C.c_uint64, C.c_void_p]
     L.flover_step.argtypes = [C.c_void_p, C.POINTER(_StepOut)]
+    L.flover_step_submit.argtypes = [C.c_void_p, C.c_void_p, C.POINTER(C.c_int32)]
+    L.flover_step_collect.argtypes = [C.c_void_p, C.POINTER(_StepOut)]
     L.flover_reorder_evict.argtypes = [C.c_void_p, C.POINTER(_ReorderOut)]
     L.flover_mark_finished.argtypes = [C.c_void_p, C.c_uint64]
     L.flover_set_next_token.argtypes = [C.c_void_p, C.c_uint64, C.c_int32]
@@ -207,6 +209,22 @@ class Flover:
         n = so.n_live
         return StepOut(self._rid[:n].copy(), self._slot[:n].copy(), self._tok[:n].copy(), self._fin[:n].copy(),
                        self._logits[:n] if want_logits else None)
+
+    def step_submit(self, logits: Optional[torch.Tensor] = None) -> int:
+        """Enqueue one iteration (pipelined token return); returns its row count (0: nothing enqueued)."""
+        n = C.c_int32(0)
+        _check(load_library().flover_step_submit(self._ctx, logits.data_ptr() if logits is not None else None,
+                                                 C.byref(n)), self._ctx)
+        return n.value
+
+    def step_collect(self) -> StepOut:
+        """Tokens of the oldest submitted iteration."""
+        Cn = self.cfg.C
+        so = _StepOut(Cn, 0, self._rid.ctypes.data, self._slot.ctypes.data, self._tok.ctypes.data,
+                      self._fin.ctypes.data, None)
+        _check(load_library().flover_step_collect(self._ctx, C.byref(so)), self._ctx)
+        n = so.n_live
+        return StepOut(self._rid[:n].copy(), self._slot[:n].copy(), self._tok[:n].copy(), self._fin[:n].copy(), None)
 
     def reorder_evict(self) -> ReorderOut:
         Cn = self.cfg.C

@@ -32,6 +32,8 @@ struct Slot {
   int max_new = 0;
   bool pending = false;   // context cache still being written on the pre-processing stream (event prep_ev[ev])
   int ev = -1;
+  int dev_row = -1;       // >= 0: the next token is row dev_row of submitted iteration dev_step, not yet on the host
+  int64_t dev_step = -1;
 };
 struct Waiting {
   uint64_t req_id;
@@ -62,7 +64,9 @@ struct Lane {
   hipEvent_t staged[kStageRing] = {nullptr, nullptr, nullptr, nullptr};   // copy of h_stage[i] has been consumed
   bool staged_busy[kStageRing] = {false, false, false, false};
   int ring = 1, next = 0;
-  int* h_tok = nullptr;
+  int tok_next = 0;         // ring of token buffers: advanced only by passes that return tokens
+  int* h_tok = nullptr;     // [kStageRing][rows_cap]
+  hipEvent_t done[kStageRing] = {nullptr, nullptr, nullptr, nullptr};     // submitted iteration's tokens are in h_tok
 };
 
 size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
@@ -99,9 +103,22 @@ struct flover_ctx {
   Lane step_lane, prep_lane_own;
   Lane* prep_lane = nullptr;   // == &step_lane unless pre-processing is asynchronous
   int4* d_moves;
-  int4* h_moves;               // pinned
   size_t stage_ints;
   size_t act_off = 0;          // arena offset where the row buffers start
+  struct InFlight {                  // an iteration submitted with flover_step_submit and not collected yet
+    int64_t id;
+    int ring, n;
+    size_t ev_end;                   // profiling pairs recorded up to here belong to this or earlier iterations
+    std::vector<uint64_t> req_id;
+    std::vector<int32_t> slot;
+    std::vector<uint8_t> fin;
+  };
+  std::deque<InFlight> inflight;
+  int64_t next_step_id = 0;
+  int4* h_moves_ring[kStageRing] = {nullptr, nullptr, nullptr, nullptr};
+  hipEvent_t moves_ev[kStageRing] = {nullptr, nullptr, nullptr, nullptr};
+  bool moves_busy[kStageRing] = {false, false, false, false};
+  int moves_next = 0;
   std::vector<hipEvent_t> prep_ev;   // one per slot: the slot's context cache is complete
   mutable std::mutex mu;             // scheduler state; see flover.h for which calls may run concurrently
   // scheduler
@@ -111,11 +128,13 @@ struct flover_ctx {
   int last_launches = 0;
   int launches = 0;
   // optional timing of the kernels with HIP events on the library's stream
-  int profile = 0;                         // 0 off, 1 attention only, 2 every GEMM too
+  int profile = 0;                         // 0 off, 1 attention of every 4th layer + shuffle copy, 2 every launch of every kind
   bool in_step = false;                    // only the fused iteration is timed, not pre-processing
-  std::vector<hipEvent_t> ev;              // pairs, reused every pass
-  std::vector<int> ev_kind;                // kind of each recorded pair in this pass
-  std::vector<int64_t> ev_bytes;           // algorithmic bytes of each recorded pair
+  bool prof_now = false;                   // the pass being enqueued on the iteration's lane is a timed one
+  std::vector<hipEvent_t> ev;              // pool of pairs
+  std::deque<int> ev_kind;                 // kind of each recorded pair not yet added up
+  std::deque<int64_t> ev_bytes;            // its algorithmic bytes
+  size_t ev_base = 0;                      // number of the pair at the front
   double prof_ms[FLOVER_PROF_KINDS] = {0};
   int64_t prof_launches[FLOVER_PROF_KINDS] = {0};
   int64_t prof_bytes[FLOVER_PROF_KINDS] = {0};
@@ -224,36 +243,43 @@ int place(flover_ctx* c) {
   return -1;
 }
 
-// Event pair for a profiled launch; returns the pair index or -1 when profiling of `kind` is off.
+// Event pair for a profiled launch; returns its index in the event pool or -1 when profiling of `kind` is off.
+// Pairs are numbered in recording order; pair g lives in pool entry g % kEvPool until it has been added up.
+constexpr size_t kEvPool = 4096;
 int prof_begin(flover_ctx* c, int kind, int64_t bytes) {
   if (c->profile == 0 || (c->profile == 1 && kind != FLOVER_PROF_ATTENTION && kind != FLOVER_PROF_COMPACT)) return -1;
   if (!c->in_step && kind != FLOVER_PROF_COMPACT) return -1;
-  const size_t i = c->ev_kind.size();
-  while (c->ev.size() < 2 * (i + 1)) {
+  if (c->ev_kind.size() >= kEvPool) return -1;            // every pool entry is waiting to be added up
+  const size_t p = (c->ev_base + c->ev_kind.size()) % kEvPool;
+  while (c->ev.size() < 2 * (p + 1)) {
     hipEvent_t e;
     if (hipEventCreate(&e) != hipSuccess) return -1;
     c->ev.push_back(e);
   }
   c->ev_kind.push_back(kind);
   c->ev_bytes.push_back(bytes);
-  return (int)i;
+  return (int)p;
 }
-void prof_collect(flover_ctx* c) {   // after the stream has been synchronised
-  for (size_t i = 0; i < c->ev_kind.size(); ++i) {
+// Adds up the recorded pairs numbered below `upto` -- all of them when the stream has been synchronised, those of
+// the oldest submitted iteration when that one is collected.
+void prof_collect(flover_ctx* c, size_t upto = (size_t)-1) {
+  while (c->ev_base < upto && !c->ev_kind.empty()) {
+    const size_t p = c->ev_base % kEvPool;
     float ms = 0.f;
-    if (hipEventElapsedTime(&ms, c->ev[2 * i], c->ev[2 * i + 1]) == hipSuccess) {
-      c->prof_ms[c->ev_kind[i]] += ms;
-      c->prof_launches[c->ev_kind[i]] += 1;
-      c->prof_bytes[c->ev_kind[i]] += c->ev_bytes[i];
+    if (hipEventElapsedTime(&ms, c->ev[2 * p], c->ev[2 * p + 1]) == hipSuccess) {
+      c->prof_ms[c->ev_kind.front()] += ms;
+      c->prof_launches[c->ev_kind.front()] += 1;
+      c->prof_bytes[c->ev_kind.front()] += c->ev_bytes.front();
     }
+    c->ev_kind.pop_front();
+    c->ev_bytes.pop_front();
+    c->ev_base += 1;
   }
-  c->ev_kind.clear();
-  c->ev_bytes.clear();
 }
 hipError_t timed_gemm(flover_ctx* c, Lane& ln, int kind, const void* x, const void* w, int n, const flk::GemmPlan& p,
                       size_t ss) {
   const int64_t bytes = (int64_t)flk::gemm_tiled_bytes(c->cfg.dtype, p.N, p.K);
-  const int pi = &ln == &c->step_lane ? prof_begin(c, kind, bytes) : -1;
+  const int pi = (&ln == &c->step_lane && c->prof_now) ? prof_begin(c, kind, bytes) : -1;
   if (pi >= 0) (void)hipEventRecord(c->ev[2 * pi], ln.st);
   hipError_t e = flk::gemm(c->cfg.dtype, x, w, n, p, ln.part, ss, ln.st);
   if (pi >= 0) (void)hipEventRecord(c->ev[2 * pi + 1], ln.st);
@@ -264,7 +290,7 @@ hipError_t timed_gemm(flover_ctx* c, Lane& ln, int kind, const void* x, const vo
 // With want_tokens the final norm, output projection and argmax run and ln.h_tok (host) holds the choices.
 // With wait the call returns after the lane's stream has drained; otherwise the pass is only enqueued.
 int run_rows(flover_ctx* c, Lane& ln, const Row* rows, int n, bool want_tokens, float* logits_out, bool context_pass,
-             bool wait) {
+             bool wait, int* ring_used = nullptr) {
   const flover_config& f = c->cfg;
   const int H = f.hidden, F = f.ffn, V = f.vocab, nh = f.n_head, d = f.head_dim, L = f.n_layer, R = c->rows_cap;
   const bool gpt = f.arch == FLOVER_ARCH_GPT;
@@ -327,7 +353,8 @@ int run_rows(flover_ctx* c, Lane& ln, const Row* rows, int n, bool want_tokens, 
   flk::AttnWork aw{(const int2*)(ds + 6 * R), d_slot, d_len, d_item0, d_nchunk, ln.pml, ln.po, n_items, flk::attn_chunk()};
   aw.blocks = (const int4*)(ds + 6 * R + 2 * n_items);
   aw.n_blocks = n_blocks;
-  const bool prof = &ln == &c->step_lane;
+  const bool prof = &ln == &c->step_lane && (wait || want_tokens);
+  if (&ln == &c->step_lane) c->prof_now = prof;
 
   int launches = 0;
   // K slicing: the iteration's is fixed by the matrix shape; a context pass holds rows of one request only and may
@@ -338,7 +365,7 @@ int run_rows(flover_ctx* c, Lane& ln, const Row* rows, int n, bool want_tokens, 
   const flk::GemmPlan p_2 = context_pass ? flk::context_plan(c->p_2, f.dtype, n) : c->p_2;
   const size_t ss_qkv = (size_t)n * p_qkv.ldc, ss_h = (size_t)n * p_o.ldc, ss_1 = (size_t)n * p_1.ldc,
                ss_v = (size_t)n * c->p_lm.ldc;
-  HIPCHK(c, flk::embed(f.dtype, c->wte, c->wpe, d_tok, d_pos, ln.x, n, H, st));
+  HIPCHK(c, flk::embed(f.dtype, c->wte, c->wpe, d_tok, d_pos, ln.tok_out, ln.x, n, H, st));
   ++launches;
   for (int l = 0; l < L; ++l) {
     const LayerW& w = c->lw[l];
@@ -354,7 +381,9 @@ int run_rows(flover_ctx* c, Lane& ln, const Row* rows, int n, bool want_tokens, 
     if (context_pass) {
       HIPCHK(c, flk::prefill_attention(f.dtype, d, ln.q, kl, vl, aw, n, nh, f.max_seq, ln.att, st));
     } else {
-      const int pi = prof ? prof_begin(c, FLOVER_PROF_ATTENTION, attn_bytes) : -1;
+      // level 1 times the attention launch of one layer in four: two event records per launch cost about as much
+      // as a small kernel, and the layers' launches are alike
+      const int pi = (prof && (c->profile >= 2 || l % 4 == 0)) ? prof_begin(c, FLOVER_PROF_ATTENTION, attn_bytes) : -1;
       HIPCHK(c, flk::decode_attention(f.dtype, d, ln.q, kl, vl, aw, n, nh, f.max_seq, ln.att, st,
                                       pi >= 0 ? c->ev[2 * pi] : nullptr, pi >= 0 ? c->ev[2 * pi + 1] : nullptr));
     }
@@ -370,14 +399,18 @@ int run_rows(flover_ctx* c, Lane& ln, const Row* rows, int n, bool want_tokens, 
                             f.norm_eps, st));
     HIPCHK(c, timed_gemm(c, ln, FLOVER_PROF_GEMM_LM, ln.h, c->wlm, n, c->p_lm, ss_v));
     HIPCHK(c, flk::logits_argmax(ln.part, c->p_lm.S, ss_v, c->p_lm.ldc, logits_out, ln.tok_out, n, V, st));
-    HIPCHK(c, hipMemcpyAsync(ln.h_tok, ln.tok_out, (size_t)n * 4, hipMemcpyDeviceToHost, st));
+    const int ti = ln.tok_next;       // at most kStageRing - 1 iterations are outstanding, so this entry is free
+    ln.tok_next = (ln.tok_next + 1) % kStageRing;
+    if (ring_used) *ring_used = ti;
+    HIPCHK(c, hipMemcpyAsync(ln.h_tok + (size_t)ti * R, ln.tok_out, (size_t)n * 4, hipMemcpyDeviceToHost, st));
+    if (!wait) HIPCHK(c, hipEventRecord(ln.done[ti], st));
     launches += 3;
   }
   if (wait) {
     HIPCHK(c, hipStreamSynchronize(st));
     if (prof) prof_collect(c);
   }
-  if (prof) c->launches += launches;
+  if (&ln == &c->step_lane) c->launches += launches;
   return FLOVER_OK;
 }
 
@@ -392,9 +425,12 @@ int preprocess(flover_ctx* c, int slot, const Waiting& r) {
   s.max_new = r.max_new;
   s.pending = false;
   s.ev = -1;
+  s.dev_row = -1;
   const bool async = c->cfg.async_preprocess != 0;
   Lane& ln = *c->prep_lane;
   const int P = (int)r.prompt.size();
+  if (async && !c->inflight.empty())   // a submitted iteration may still read the slot's previous tenant
+    HIPCHK(c, hipStreamWaitEvent(ln.st, c->step_lane.done[c->inflight.back().ring], 0));
   std::vector<Row> rows;
   for (int p0 = 0; p0 + 1 < P; p0 += c->rows_cap) {
     const int n = std::min(c->rows_cap, P - 1 - p0);
@@ -459,10 +495,14 @@ void release(flover_ctx* c) {
     for (int i = 0; i < kStageRing; ++i) {
       if (ln->h_stage[i]) (void)hipHostFree(ln->h_stage[i]);
       if (ln->staged[i]) (void)hipEventDestroy(ln->staged[i]);
+      if (ln->done[i]) (void)hipEventDestroy(ln->done[i]);
     }
     if (ln->h_tok) (void)hipHostFree(ln->h_tok);
   }
-  if (c->h_moves) (void)hipHostFree(c->h_moves);
+  for (int i = 0; i < kStageRing; ++i) {
+    if (c->h_moves_ring[i]) (void)hipHostFree(c->h_moves_ring[i]);
+    if (c->moves_ev[i]) (void)hipEventDestroy(c->moves_ev[i]);
+  }
   for (hipEvent_t e : c->prep_ev)
     if (e) (void)hipEventDestroy(e);
   for (hipEvent_t e : c->ev) (void)hipEventDestroy(e);
@@ -531,12 +571,17 @@ int32_t flover_init(const flover_config* cfg, const flover_weights* w, flover_ct
       return bail(FLOVER_E_HIP);                                                      \
     }                                                                                 \
   } while (0)
-  c->h_moves = nullptr;
   c->step_lane.st = c->st;
   c->prep_lane = cfg->async_preprocess ? &c->prep_lane_own : &c->step_lane;
-  HIPTRY(hipHostMalloc((void**)&c->step_lane.h_stage[0], c->stage_ints * 4, hipHostMallocDefault));
-  HIPTRY(hipHostMalloc((void**)&c->step_lane.h_tok, (size_t)c->rows_cap * 4, hipHostMallocDefault));
-  HIPTRY(hipHostMalloc((void**)&c->h_moves, (size_t)cfg->max_concurrency * sizeof(int4), hipHostMallocDefault));
+  c->step_lane.ring = kStageRing;
+  for (int i = 0; i < kStageRing; ++i) {
+    HIPTRY(hipHostMalloc((void**)&c->step_lane.h_stage[i], c->stage_ints * 4, hipHostMallocDefault));
+    HIPTRY(hipEventCreateWithFlags(&c->step_lane.staged[i], hipEventDisableTiming));
+    HIPTRY(hipEventCreateWithFlags(&c->step_lane.done[i], hipEventDisableTiming));
+    HIPTRY(hipHostMalloc((void**)&c->h_moves_ring[i], (size_t)cfg->max_concurrency * sizeof(int4), hipHostMallocDefault));
+    HIPTRY(hipEventCreateWithFlags(&c->moves_ev[i], hipEventDisableTiming));
+  }
+  HIPTRY(hipHostMalloc((void**)&c->step_lane.h_tok, (size_t)kStageRing * c->rows_cap * 4, hipHostMallocDefault));
   if (cfg->async_preprocess) {
     Lane& pl = c->prep_lane_own;
     HIPTRY(hipStreamCreateWithFlags(&pl.st, hipStreamNonBlocking));   // default priority
@@ -668,6 +713,7 @@ int32_t flover_add_request_cached(flover_ctx* c, uint64_t req_id, int32_t contex
   s.len = context_len;
   s.next_token = next_token;
   s.pending = false;
+  s.dev_row = -1;
   if (out_slot) *out_slot = slot;
   return FLOVER_OK;
 }
@@ -675,6 +721,7 @@ int32_t flover_add_request_cached(flover_ctx* c, uint64_t req_id, int32_t contex
 int32_t flover_step(flover_ctx* c, flover_step_out* out) {
   if (!c || !out) return fail(c, FLOVER_E_INVAL, "null argument");
   std::unique_lock<std::mutex> lock(c->mu);
+  if (!c->inflight.empty()) return fail(c, FLOVER_E_STATE, "submitted iterations are outstanding: collect them first");
   c->launches = 0;
   while (!c->reque.empty()) {        // waiting requests take freed adjacent slots in arrival order
     int slot = place(c);
@@ -719,14 +766,15 @@ int32_t flover_step(flover_ctx* c, flover_step_out* out) {
   // held while the GPU works
   const bool async = c->cfg.async_preprocess != 0;
   if (async) lock.unlock();
-  int rc = run_rows(c, c->step_lane, rows.data(), (int)rows.size(), true, out->logits, false, true);
+  int ring = 0;
+  int rc = run_rows(c, c->step_lane, rows.data(), (int)rows.size(), true, out->logits, false, true, &ring);
   if (async) lock.lock();
   c->in_step = false;
   if (rc != FLOVER_OK) return rc;
   c->last_launches = c->launches;
   for (int j = 0; j < n; ++j) {
     Slot& s = c->slots[live[j]];
-    const int t = c->step_lane.h_tok[j];
+    const int t = c->step_lane.h_tok[(size_t)ring * c->rows_cap + j];
     s.len += 1;
     s.generated += 1;
     s.next_token = t;
@@ -737,6 +785,100 @@ int32_t flover_step(flover_ctx* c, flover_step_out* out) {
     if (out->finished) out->finished[j] = fin ? 1 : 0;
     if (fin) s.state = FLOVER_SLOT_DEAD;
   }
+  return FLOVER_OK;
+}
+
+// Pipelined form of flover_step: the iteration is only enqueued.  Without an end-of-sequence token the scheduler
+// knows from the budgets alone who finishes, so its state advances at submission; the chosen tokens stay on the
+// device as the next iteration's input and reach the host when the iteration is collected.
+int32_t flover_step_submit(flover_ctx* c, float* logits, int32_t* n_live_out) {
+  if (!c) return fail(c, FLOVER_E_INVAL, "null argument");
+  std::unique_lock<std::mutex> lock(c->mu);
+  if (c->cfg.eos_id >= 0) return fail(c, FLOVER_E_STATE, "pipelined iterations need eos_id < 0");
+  if ((int)c->inflight.size() >= kStageRing - 1) return fail(c, FLOVER_E_FULL, "too many iterations outstanding: collect one first");
+  c->launches = 0;
+  while (!c->reque.empty()) {
+    int slot = place(c);
+    if (slot < 0) break;
+    int rc = preprocess(c, slot, c->reque.front());
+    if (rc != FLOVER_OK) return rc;
+    c->reque.pop_front();
+  }
+  c->launches = 0;
+  std::vector<Row> rows;
+  std::vector<int> live;
+  for (int i = c->lo; i < c->hi; ++i) {
+    Slot& s = c->slots[i];
+    if (s.state == FLOVER_SLOT_READY && context_ready(c, s)) s.state = FLOVER_SLOT_LIVE;
+    if (s.state == FLOVER_SLOT_LIVE) {
+      live.push_back(i);
+      rows.push_back(Row{i, s.dev_row >= 0 ? -1 - s.dev_row : s.next_token, s.len});
+    }
+  }
+  const int n = (int)live.size();
+  if (c->cfg.shuffle_mode == FLOVER_SHUFFLE_OFF)
+    for (int i = c->lo; i < c->hi; ++i)
+      if (c->slots[i].state == FLOVER_SLOT_EMPTY || c->slots[i].state == FLOVER_SLOT_DEAD) rows.push_back(Row{i, 0, 0});
+  if (n_live_out) *n_live_out = n;
+  c->last_launches = 0;
+  if (n == 0) return FLOVER_OK;     // nothing enqueued, nothing to collect
+  int ring = 0;
+  c->in_step = true;
+  int rc = run_rows(c, c->step_lane, rows.data(), (int)rows.size(), true, logits, false, false, &ring);
+  c->in_step = false;
+  if (rc != FLOVER_OK) return rc;
+  c->last_launches = c->launches;
+  flover_ctx::InFlight fl;
+  fl.id = c->next_step_id++;
+  fl.ring = ring;
+  fl.n = n;
+  fl.ev_end = c->ev_base + c->ev_kind.size();
+  fl.req_id.resize(n);
+  fl.slot.resize(n);
+  fl.fin.resize(n);
+  for (int j = 0; j < n; ++j) {
+    Slot& s = c->slots[live[j]];
+    s.len += 1;
+    s.generated += 1;
+    s.dev_row = j;
+    s.dev_step = fl.id;
+    const bool fin = s.generated >= s.max_new;
+    fl.req_id[j] = s.req_id;
+    fl.slot[j] = live[j];
+    fl.fin[j] = fin ? 1 : 0;
+    if (fin) s.state = FLOVER_SLOT_DEAD;
+  }
+  c->inflight.push_back(std::move(fl));
+  return FLOVER_OK;
+}
+
+int32_t flover_step_collect(flover_ctx* c, flover_step_out* out) {
+  if (!c || !out) return fail(c, FLOVER_E_INVAL, "null argument");
+  std::unique_lock<std::mutex> lock(c->mu);
+  if (c->inflight.empty()) return fail(c, FLOVER_E_STATE, "no submitted iteration to collect");
+  flover_ctx::InFlight& fl = c->inflight.front();
+  if (out->capacity < fl.n) return fail(c, FLOVER_E_INVAL, "flover_step_out.capacity too small");
+  hipEvent_t done = c->step_lane.done[fl.ring];
+  lock.unlock();
+  HIPCHK(c, hipEventSynchronize(done));
+  lock.lock();
+  prof_collect(c, fl.ev_end);
+  const int* tok = c->step_lane.h_tok + (size_t)fl.ring * c->rows_cap;
+  out->n_live = fl.n;
+  for (int j = 0; j < fl.n; ++j) {
+    if (out->req_id) out->req_id[j] = fl.req_id[j];
+    if (out->slot) out->slot[j] = fl.slot[j];
+    if (out->token) out->token[j] = tok[j];
+    if (out->finished) out->finished[j] = fl.fin[j];
+  }
+  // the host copy of each request's last token; a slot whose device-resident token was this iteration's is back on
+  // host tokens (the request may have been moved by a shuffle since: found by id)
+  for (Slot& s : c->slots)
+    if (s.state != FLOVER_SLOT_EMPTY && s.dev_step == fl.id && s.dev_row >= 0) {
+      s.next_token = tok[s.dev_row];
+      s.dev_row = -1;
+    }
+  c->inflight.pop_front();
   return FLOVER_OK;
 }
 
@@ -758,6 +900,7 @@ int32_t flover_set_next_token(flover_ctx* c, uint64_t req_id, int32_t token) {
   for (Slot& s : c->slots)
     if ((s.state == FLOVER_SLOT_LIVE || s.state == FLOVER_SLOT_READY) && s.req_id == req_id) {
       s.next_token = token;
+      s.dev_row = -1;
       return FLOVER_OK;
     }
   return fail(c, FLOVER_E_INVAL, "no such live request");
@@ -802,6 +945,14 @@ int32_t flover_reorder_evict(flover_ctx* c, flover_reorder_out* out) {
       const int row_bytes = f.head_dim * esize(f.dtype);
       const int nseg = 2 * f.n_layer * f.n_head;
       int n_dev = 0, blocks = 0;
+      const bool piped = !c->inflight.empty();   // submitted iterations still run: everything stays stream-ordered
+      const int mi = c->moves_next;
+      c->moves_next = (c->moves_next + 1) % kStageRing;
+      if (c->moves_busy[mi]) {
+        HIPCHK(c, hipEventSynchronize(c->moves_ev[mi]));
+        c->moves_busy[mi] = false;
+      }
+      int4* h_moves = c->h_moves_ring[mi];
       for (int i = 0; i < n_moves; ++i) {
         const int a = outside[i], b = holes[i];
         if (out->move_src) out->move_src[i] = a;
@@ -812,7 +963,7 @@ int32_t flover_reorder_evict(flover_ctx* c, flover_reorder_out* out) {
         bytes += 2LL * len * 2 * f.n_layer * f.hidden * esize(f.dtype);
         if (len > 0) {
           const int seg_bytes = len * row_bytes;
-          c->h_moves[n_dev] = make_int4(a, b, seg_bytes, blocks);
+          h_moves[n_dev] = make_int4(a, b, seg_bytes, blocks);
           blocks += nseg * ((seg_bytes + flk::kCompactPiece - 1) / flk::kCompactPiece);
           ++n_dev;
         }
@@ -820,15 +971,19 @@ int32_t flover_reorder_evict(flover_ctx* c, flover_reorder_out* out) {
         c->slots[a] = Slot();
       }
       if (n_dev > 0) {
-        HIPCHK(c, hipMemcpyAsync(c->d_moves, c->h_moves, (size_t)n_dev * sizeof(int4), hipMemcpyHostToDevice, c->st));
+        HIPCHK(c, hipMemcpyAsync(c->d_moves, h_moves, (size_t)n_dev * sizeof(int4), hipMemcpyHostToDevice, c->st));
+        HIPCHK(c, hipEventRecord(c->moves_ev[mi], c->st));
+        c->moves_busy[mi] = true;
         const int pi = prof_begin(c, FLOVER_PROF_COMPACT, bytes);
         if (pi >= 0) (void)hipEventRecord(c->ev[2 * pi], c->st);
         HIPCHK(c, flk::compact(c->kv, 2 * f.n_layer, C, f.n_head, c->slot_bytes, c->d_moves, n_dev, blocks,
                                flk::kCompactPiece, c->st));
         if (pi >= 0) (void)hipEventRecord(c->ev[2 * pi + 1], c->st);
-        HIPCHK(c, hipStreamSynchronize(c->st));   // following iterations wait until memory is in order (Section V-D)
-        for (int i = 0; i < n_moves; ++i) c->slots[holes[i]].pending = false;   // the copy waited for their caches
-        prof_collect(c);
+        if (!piped) {
+          HIPCHK(c, hipStreamSynchronize(c->st));   // following iterations wait until memory is in order (Section V-D)
+          for (int i = 0; i < n_moves; ++i) c->slots[holes[i]].pending = false;   // the copy waited for their caches
+          prof_collect(c);
+        }
       }
       c->lo = old_lo + off;
       c->hi = c->lo + n1;

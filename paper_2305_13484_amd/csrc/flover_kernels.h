@@ -35,8 +35,9 @@ inline int gemm_rows_read(int M) {
 }
 
 // ---- row-wise kernels
-hipError_t embed(int dtype, const void* wte, const void* wpe, const int* tok, const int* pos, float* x, int M, int H,
-                 hipStream_t st);
+// tok[m] < 0: the token is tok_prev[-1 - tok[m]] (device-resident choice of the previous iteration).
+hipError_t embed(int dtype, const void* wte, const void* wpe, const int* tok, const int* pos, const int* tok_prev,
+                 float* x, int M, int H, hipStream_t st);
 // `part` is the preceding GEMM's split-K output: S slices, `stride` floats apart, rows of `ldp` floats (ldp % 4 == 0).
 hipError_t add_norm(int dtype, bool rms, float* x, const float* part, int S, size_t stride, int ldp, const void* bias,
                     const void* g, const void* b, void* h, int M, int H, float eps, hipStream_t st);

@@ -53,12 +53,15 @@ template <int DT> __device__ __forceinline__ void stv4(void* p, size_t i, f32x4_
 
 // ---------------------------------------------------------------- embedding
 // x[m][i] = wte[tok[m]][i] (+ wpe[pos[m]][i])            grid = M, block = 256
+// tok[m] < 0 feeds the token the previous iteration chose for its row -1 - tok[m] (still on the device).
 template <int DT>
 __global__ __launch_bounds__(256) void embed_kernel(const void* __restrict__ wte, const void* __restrict__ wpe,
                                                     const int* __restrict__ tok, const int* __restrict__ pos,
-                                                    float* __restrict__ x, int H) {
+                                                    const int* __restrict__ tok_prev, float* __restrict__ x, int H) {
   const int m = blockIdx.x;
-  const size_t t = (size_t)tok[m] * H;
+  int tk = tok[m];
+  if (tk < 0) tk = tok_prev[-1 - tk];
+  const size_t t = (size_t)tk * H;
   const size_t p = wpe ? (size_t)pos[m] * H : 0;
   for (int i = threadIdx.x * 4; i < H; i += 1024) {
     f32x4_t v = ldv4<DT>(wte, t + i);
@@ -261,10 +264,10 @@ __global__ __launch_bounds__(1024) void argmax_kernel(const float* __restrict__ 
     default: { constexpr int DT = DT_BF16; CALL; } break;     \
   }
 
-hipError_t embed(int dtype, const void* wte, const void* wpe, const int* tok, const int* pos, float* x, int M, int H,
-                 hipStream_t st) {
+hipError_t embed(int dtype, const void* wte, const void* wpe, const int* tok, const int* pos, const int* tok_prev,
+                 float* x, int M, int H, hipStream_t st) {
   if (M <= 0) return hipSuccess;
-  FLK_DT_SWITCH(dtype, (embed_kernel<DT><<<M, 256, 0, st>>>(wte, wpe, tok, pos, x, H)));
+  FLK_DT_SWITCH(dtype, (embed_kernel<DT><<<M, 256, 0, st>>>(wte, wpe, tok, pos, tok_prev, x, H)));
   return hipGetLastError();
 }
 

@@ -130,3 +130,44 @@ def gpu_run_stream(cfg, weights_dev, reqs, shuffle_off=False, want_logits=True, 
         s += 1
     srv.close()
     return toks, logits
+
+
+def gpu_run_stream_pipelined(cfg, weights_dev, reqs, depth=2, shuffle_off=False, async_preprocess=False, want_logits=True,
+                             stats=None):
+    """The HIP path with pipelined token return: up to `depth` iterations submitted before the oldest is collected."""
+    import collections
+    import time
+    import torch
+    import paper_2305_13484_amd as fl
+    srv = fl.Flover(cfg, weights_dev, shuffle_off=shuffle_off, async_preprocess=async_preprocess)
+    bufs = [torch.empty((cfg.C, cfg.V), dtype=torch.float32, device="cuda") for _ in range(depth + 1)]
+    pending = sorted(reqs, key=lambda r: (r.arrival_step, r.req_id))
+    toks, logits = {}, {}
+    q = collections.deque()
+    i = done = s = k = 0
+    deadline = time.time() + 120
+    while done < len(reqs):
+        assert time.time() < deadline
+        while i < len(pending) and pending[i].arrival_step <= s:
+            srv.add_request(pending[i].req_id, pending[i].prompt, pending[i].gen_len)
+            i += 1
+        n = srv.step_submit(bufs[k] if want_logits else None)
+        rr = srv.reorder_evict()
+        if stats is not None:
+            stats["moves"] = stats.get("moves", 0) + len(rr.moves)
+            stats["max_outstanding"] = max(stats.get("max_outstanding", 0), len(q) + (1 if n else 0))
+        s += 1
+        if n:
+            q.append(k)
+            k = (k + 1) % len(bufs)
+        while q and (len(q) >= depth or n == 0):
+            b = q.popleft()
+            out = srv.step_collect()
+            for j in range(out.n_live):
+                rid = int(out.req_id[j])
+                toks.setdefault(rid, []).append(int(out.token[j]))
+                if want_logits:
+                    logits.setdefault(rid, []).append(bufs[b][j].clone())
+            done += int(out.finished.sum())
+    srv.close()
+    return toks, logits

@@ -8,7 +8,7 @@ import torch
 
 import flover_synth as synth
 from oracle import oracle as orc
-from helpers import Lockstep, gpu_run_stream, to_device, TOL
+from helpers import Lockstep, gpu_run_stream, gpu_run_stream_pipelined, to_device, TOL
 
 pytestmark = pytest.mark.gpu
 
@@ -235,6 +235,35 @@ def test_kernel_timing_profile_counts_step_launches():
     srv.close()
 
 
+def test_kernel_timing_profile_with_pipelined_iterations():
+    import paper_2305_13484_amd as fl
+    cfg = synth.small_llama16(synth.DT_BF16)
+    w = to_device(synth.make_weights(cfg, 22))
+    srv = fl.Flover(cfg, w)
+    srv.set_profile(2)
+    srv.add_request(1, [5, 6, 7, 8], 40)
+    srv.add_request(2, [9], 40)
+    outstanding = 0
+    for _ in range(30):                       # two iterations outstanding most of the time
+        assert srv.step_submit() == 2
+        srv.reorder_evict()
+        outstanding += 1
+        if outstanding == 3:
+            srv.step_collect()
+            outstanding -= 1
+    while outstanding:
+        srv.step_collect()
+        outstanding -= 1
+    p = srv.get_profile()
+    e = 2
+    assert p["attention"]["launches"] == 30 * cfg.L
+    lens = [(3 + i + 1) + (0 + i + 1) for i in range(30)]
+    assert p["attention"]["bytes"] == cfg.L * sum(lens) * 2 * cfg.H * e
+    assert p["gemm_ff2"]["launches"] == 30 * cfg.L and p["gemm_lm"]["launches"] == 30
+    assert p["attention"]["ms"] > 0
+    srv.close()
+
+
 def test_gpt1p3b_shape_reduced_depth():
     """The GPT-1.3B layer shape (hidden 2048, 16 heads, FFN 8192, vocab 50257 -- not a multiple of 16 --, fp16, biases,
     learned positions, tied output projection) at 2 layers against the oracle."""
@@ -450,3 +479,49 @@ def test_add_request_from_a_second_thread_while_steps_run():
     assert not errors
     print("two threads: iterations", steps)
     _same_results(ref, (toks, logits), reqs)
+
+
+@pytest.mark.parametrize("name,depth,async_pre,shuffle_off", [("tiny_gpt", 2, False, False), ("tiny_gpt", 3, False, True),
+                                                               ("small_llama16", 3, False, False),
+                                                               ("small_llama16", 2, True, False)])
+def test_pipelined_token_return_matches_the_synchronous_step_bitwise(name, depth, async_pre, shuffle_off):
+    """flover_step_submit / flover_step_collect: tokens stay on the device between iterations and the host runs ahead;
+    every request's tokens and logits equal those of the synchronous flover_step run bit for bit."""
+    cfg = dataclasses.replace(getattr(synth, name)(), C=6)
+    w = to_device(synth.make_weights(cfg, 35))
+    reqs = synth.stream_small(47, cfg.V, n=18, arrive_hi=16, p_lo=1, p_hi=min(70, cfg.S - 24), g_lo=1, g_hi=20)
+    ref = gpu_run_stream(cfg, w, reqs, shuffle_off=shuffle_off)
+    st = {}
+    got = gpu_run_stream_pipelined(cfg, w, reqs, depth=depth, shuffle_off=shuffle_off, async_preprocess=async_pre, stats=st)
+    print("pipelined", name, depth, st)
+    _same_results(ref, got, reqs)
+    assert st["max_outstanding"] == depth
+    assert (st["moves"] > 0) != shuffle_off
+
+
+def test_pipelined_abi_errors():
+    import paper_2305_13484_amd as fl
+    cfg = dataclasses.replace(synth.tiny_gpt(), C=4, eos_id=5)
+    w = to_device(synth.make_weights(cfg, 3))
+    srv = fl.Flover(cfg, w)
+    srv.add_request(1, [1, 2, 3], 4)
+    with pytest.raises(fl.FloverError):          # an end-of-sequence token decides finishes on the host
+        srv.step_submit()
+    srv.close()
+    cfg = dataclasses.replace(cfg, eos_id=-1)
+    srv = fl.Flover(cfg, w)
+    with pytest.raises(fl.FloverError):
+        srv.step_collect()                       # nothing submitted
+    assert srv.step_submit() == 0                # nothing live: nothing enqueued
+    srv.add_request(1, [1, 2, 3], 10)
+    for _ in range(3):
+        assert srv.step_submit() == 1
+    with pytest.raises(fl.FloverError):
+        srv.step_submit()                        # a fourth outstanding iteration
+    with pytest.raises(fl.FloverError):
+        srv.step()                               # the synchronous step refuses while iterations are outstanding
+    for _ in range(3):
+        assert srv.step_collect().n_live == 1
+    out = srv.step()                             # and works again afterwards, continuing from the host token
+    assert out.n_live == 1
+    srv.close()
