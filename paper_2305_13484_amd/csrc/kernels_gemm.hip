@@ -10,11 +10,14 @@
 //   * a column group (64 columns = 4 n-tiles) x one K slice x all rows of a row block is the unit of work; up to 16
 //     rows one wave takes it and reads the rows' operand straight from L2/L1 (no LDS, no barriers); above that the
 //     rows' operand is staged through LDS once per block of 4 column groups and shared by the block's 4 or 8 waves.
-//   * more than 128 rows (context passes, very wide windows): row blocks of one (column block, K slice) get
+//   * more than 128 rows (context passes, very wide windows): the contraction turns MFMA-bound, so a wave keeps a
+//     128 x 64 output tile and a block covers 256 rows x 256 columns; row blocks of one (column block, K slice) get
 //     workgroup ids that land on the same XCD, so the weight tiles cross HBM once and are L2 hits for the others.
-//   * split-K: slice count and boundaries depend on (N, K) only -- never on M -- and partial sums are written per
-//     slice and added by the consumer in slice order, so a row's result does not depend on which other rows
-//     are live (the paper's premise that fused requests undergo identical operations).
+//   * split-K: for the fused iteration slice count and boundaries depend on (N, K) only -- never on M -- and partial
+//     sums are written per slice and added by the consumer in slice order, so a row's result does not depend on which
+//     other rows are live (the paper's premise that fused requests undergo identical operations).  A context pass
+//     holds rows of one request and is sliced by that request's row count too (context_plan): fewer slices, because
+//     at hundreds of rows the fp32 partial sums would outweigh the weights.
 //   * MFMA v_mfma_f32_16x16x32_{bf16,f16}: A = 16 rows of x, B = 16 columns of W, 32-deep.
 // fp32 models (tiny configurations only) use a plain FMA kernel on the untiled matrix.
 #include <algorithm>
