@@ -27,7 +27,7 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=0, help="timed steps (0 = the whole stream)")
     ap.add_argument("--warmup", type=int, default=8)
-    ap.add_argument("--workload", default="c4", choices=["c4", "c3", "c1", "c2", "poisson32", "const32", "shuffle32"])
+    ap.add_argument("--workload", default="c4", choices=["c4", "c3", "c1", "c2", "c5", "poisson32", "const32", "shuffle32"])
     ap.add_argument("--lambda-ms", type=float, default=500.0,
                     help="poisson32: mean inter-arrival gap in the paper's milliseconds (Section VI-C); converted to "
                          "decode steps with the paper's 5800 ms per 512 iterations")
@@ -365,6 +365,24 @@ def main():
                 for i, g in enumerate(gens)]
         wl = "%s: LLaMA-7B shape bf16, 32 requests %.0f ms = %d steps apart, generation %s" % (
             a.workload, a.interval_ms, gap_steps, "512" if a.workload == "const32" else "U{128..%d}" % gmax)
+    elif a.workload == "c5":
+        # LLaMA-30B shape: 512 requests contend for as many 2048-token slots (3.05 GiB each) as fit beside the 65 GB of
+        # weights; the weights are generated and handed over layer by layer
+        import dataclasses
+        free = torch.cuda.mem_get_info()[0]
+        cfg = None
+        for slots in range(64, 7, -4):
+            cand = synth.llama_30b(L=a.layers or 60, C=slots)
+            if fl.arena_bytes(cand) + (6 << 30) <= free:
+                cfg = cand
+                break
+        assert cfg is not None, "not enough free device memory for the 30B shape"
+        reqs = synth.stream_c5(a.seed, cfg.V, n=a.requests or 512)
+        if not a.steps:
+            a.steps = 1200
+        wl = ("c5: LLaMA-30B shape bf16, 512 requests, bursty Poisson arrivals (1 / 8 per step alternating every 200 "
+              "steps), prompts U{16..512}, generation U{8..2048}, max_concurrency %d (what fits in device memory), "
+              "first %d steps" % (cfg.C, a.steps))
     elif a.workload == "c1":
         cfg = synth.tiny_gpt()
         reqs = synth.stream_c1(a.seed, cfg.V)
@@ -374,14 +392,23 @@ def main():
         return
 
     t0 = time.perf_counter()
-    weights = synth.make_weights(cfg, a.seed, device="cuda")
-    torch.cuda.synchronize()
-    t_w = time.perf_counter() - t0
-    srv = fl.Flover(cfg, weights, shuffle_off=a.shuffle_off, by_length=a.by_length, async_preprocess=a.async_preprocess)
     cpu = None
-    if not a.no_cpu_baseline:
-        cpu = cpu_baseline(cfg, weights, reqs)
-    del weights
+    if a.workload == "c5":
+        glob, layers = synth.make_weights_layerwise(cfg, a.seed, device="cuda")
+        srv = fl.Flover(cfg, glob, shuffle_off=a.shuffle_off, by_length=a.by_length, async_preprocess=a.async_preprocess)
+        for l, wl_ in enumerate(layers):
+            srv.set_layer_weights(l, wl_)
+        del glob, layers, wl_
+        t_w = time.perf_counter() - t0
+        a.pipeline = 0          # requests wait for slots here: the synchronous driver keeps the per-row byte accounting
+    else:
+        weights = synth.make_weights(cfg, a.seed, device="cuda")
+        torch.cuda.synchronize()
+        t_w = time.perf_counter() - t0
+        srv = fl.Flover(cfg, weights, shuffle_off=a.shuffle_off, by_length=a.by_length, async_preprocess=a.async_preprocess)
+        if not a.no_cpu_baseline:
+            cpu = cpu_baseline(cfg, weights, reqs)
+        del weights
     torch.cuda.empty_cache()
 
     # warm-up: a throwaway stream of a few short requests through the same context

@@ -152,6 +152,23 @@ def make_weights(cfg: ModelConfig, seed: int, device: str = "cpu") -> Dict[str, 
     return out
 
 
+PER_LAYER_NAMES = ("ln1_g", "ln1_b", "wqkv", "bqkv", "wo", "bo", "ln2_g", "ln2_b", "w1", "b1", "wu", "w2", "b2")
+
+
+def make_weights_layerwise(cfg: ModelConfig, seed: int, device: str = "cpu"):
+    """For models too large to hold as one stacked copy: (global tensors, iterator over per-layer dicts).  Layer l is
+    drawn from its own seed, so layers can be produced (and dropped) one at a time; same distributions as make_weights."""
+    one = dataclasses.replace(cfg, L=1)
+    glob = {k: v for k, v in make_weights(one, seed, device).items() if k not in PER_LAYER_NAMES}
+
+    def layers():
+        for l in range(cfg.L):
+            w = make_weights(one, seed * 1009 + 17 + l, device)
+            yield {k: w[k][0].contiguous() for k in PER_LAYER_NAMES if k in w}
+
+    return glob, layers()
+
+
 # --------------------------------------------------------------------------- request streams
 
 @dataclasses.dataclass

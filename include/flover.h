@@ -97,6 +97,15 @@ int32_t flover_query_arena_bytes(const flover_config* cfg, uint64_t* out_bytes);
 int32_t flover_init(const flover_config* cfg, const flover_weights* w, flover_ctx** out_ctx);
 
 /* Waits for the stream, releases host resources.  The arena is the caller's. */
+/* Layer-by-layer hand-over, for models whose natural-layout copy would not fit in device memory beside the arena
+ * (the Buffer Manager sizes everything from the model configuration, Section V-A; the 30B shape holds 65 GB of weights).
+ * flover_init with EVERY per-layer pointer of `weights` NULL (ln1_g .. b2; the global tensors wte, wpe, lnf_*, wlm are
+ * still taken) leaves the layers unloaded; flover_set_layer_weights then copies and re-tiles layer `layer` from w, whose
+ * per-layer pointers address that ONE layer's tensors (its global pointers are ignored), and returns when the copy is
+ * complete, so the caller may reuse its buffers.  Requests are refused (STATE) until every layer has been set; a layer
+ * may be set again while no request is in flight.  Errors: INVAL (layer out of range, missing tensor), STATE, HIP. */
+int32_t flover_set_layer_weights(flover_ctx* ctx, int32_t layer, const flover_weights* w);
+
 int32_t flover_destroy(flover_ctx* ctx);
 
 /* Text of the last error on ctx (ctx == NULL: of the last failed flover_init / query / kernel-level call).

@@ -18,7 +18,7 @@ _LIB_PATH = os.path.join(_HERE, "libflover.so")
 EXPORTED_SYMBOLS = [
     "flover_query_arena_bytes", "flover_init", "flover_destroy", "flover_last_error", "flover_add_request",
     "flover_step", "flover_reorder_evict", "flover_mark_finished", "flover_set_next_token", "flover_get_state",
-    "flover_get_kv_cache", "flover_last_step_launches", "flover_step_submit", "flover_step_collect", "flover_set_profile", "flover_get_profile", "flover_k_find_window", "flover_k_attention_workspace_bytes",
+    "flover_get_kv_cache", "flover_last_step_launches", "flover_step_submit", "flover_step_collect", "flover_set_layer_weights", "flover_set_profile", "flover_get_profile", "flover_k_find_window", "flover_k_attention_workspace_bytes",
     "flover_k_decode_attention", "flover_k_compact_workspace_bytes", "flover_k_compact", "flover_k_gemm_tiled_bytes",
     "flover_k_gemm_workspace_bytes", "flover_k_gemm_retile", "flover_k_gemm", "flover_add_request_cached",
     "flover_k_copy_probe",
@@ -82,6 +82,7 @@ def load_library():
                                             C.POINTER(C.c_int32)]
     L.flover_k_copy_probe.argtypes = [C.c_void_p, C.c_void_p, C.c_uint64, C.c_void_p]
     L.flover_step.argtypes = [C.c_void_p, C.POINTER(_StepOut)]
+    L.flover_set_layer_weights.argtypes = [C.c_void_p, C.c_int32, C.POINTER(_Weights)]
     L.flover_step_submit.argtypes = [C.c_void_p, C.c_void_p, C.POINTER(C.c_int32)]
     L.flover_step_collect.argtypes = [C.c_void_p, C.POINTER(_StepOut)]
     L.flover_reorder_evict.argtypes = [C.c_void_p, C.POINTER(_ReorderOut)]
@@ -174,6 +175,17 @@ class Flover:
         self._src = np.zeros(Cn, np.int32)
         self._dst = np.zeros(Cn, np.int32)
         self._logits = None
+
+    def set_layer_weights(self, layer: int, weights: Dict[str, torch.Tensor]):
+        """Hand over ONE layer's tensors (names of flover_weights, without the leading layer dimension or with a
+        leading dimension of 1) to a context created with no per-layer tensors."""
+        w = _Weights()
+        for n in WEIGHT_FIELDS:
+            t = weights.get(n)
+            if t is not None:
+                assert t.is_cuda and t.is_contiguous() and t.dtype == _TORCH_DT[self.cfg.dtype], n
+            setattr(w, n, t.data_ptr() if t is not None else None)
+        _check(load_library().flover_set_layer_weights(self._ctx, layer, C.byref(w)), self._ctx)
 
     def close(self):
         if self._ctx is not None:
@@ -278,6 +290,15 @@ class Flover:
 
 
 # ------------------------------------------------------------------ operation-level entry points
+
+def arena_bytes(cfg, async_preprocess: bool = False) -> int:
+    """flover_query_arena_bytes for a config object (fields as for Flover)."""
+    c = _Config(cfg.arch, cfg.dtype, cfg.L, cfg.H, cfg.nh, cfg.d, cfg.F, cfg.V, cfg.S, cfg.C, cfg.eos_id, 0,
+                1 if async_preprocess else 0, cfg.ln_eps, cfg.rope_theta, None, None, 0)
+    need = C.c_uint64(0)
+    _check(load_library().flover_query_arena_bytes(C.byref(c), C.byref(need)))
+    return int(need.value)
+
 
 def k_find_window(arr) -> Tuple[int, int, int]:
     a = _i32(arr)

@@ -92,6 +92,8 @@ struct flover_ctx {
   std::string err;
   // weights in the arena
   std::vector<LayerW> lw;
+  std::vector<bool> layer_loaded;
+  int layers_loaded = 0;
   void *wte, *wpe, *lnf_g, *lnf_b, *wlm;
   float* rope_cs;
   flk::GemmPlan p_qkv, p_o, p_1, p_2, p_lm;
@@ -489,6 +491,46 @@ int copy_in(flover_ctx* c, void* dst, const void* src, size_t bytes, const char*
   return FLOVER_OK;
 }
 
+// Copies (and re-tiles) layer l from w, whose per-layer tensors start at layer src_l of their stacks.
+int load_layer(flover_ctx* c, int l, const flover_weights* w, int src_l) {
+  const flover_config& f = c->cfg;
+  const size_t e = esize(f.dtype), H = f.hidden, F = f.ffn, sl = src_l;
+  const bool gpt = f.arch == FLOVER_ARCH_GPT;
+  hipStream_t st = c->st;
+  LayerW& lw = c->lw[l];
+  auto at = [&](const void* p, size_t per_layer_elems) -> const char* {
+    return p ? (const char*)p + sl * per_layer_elems * e : nullptr;
+  };
+  if (!w->wqkv || !w->wo || !w->w1 || !w->w2 || (!gpt && !w->wu)) return fail(c, FLOVER_E_INVAL, "missing weight matrix");
+  int rc;
+  if ((rc = copy_in(c, lw.ln1_g, at(w->ln1_g, H), H * e, "ln1_g")) != FLOVER_OK) return rc;
+  if ((rc = copy_in(c, lw.ln2_g, at(w->ln2_g, H), H * e, "ln2_g")) != FLOVER_OK) return rc;
+  if (f.dtype != FLOVER_F32) {   // padding tiles of the re-tiled matrices must read as zero
+    HIPCHK(c, flk::zero_fill(lw.wqkv, flk::gemm_tiled_bytes(f.dtype, 3 * f.hidden, f.hidden), st));
+    HIPCHK(c, flk::zero_fill(lw.wo, flk::gemm_tiled_bytes(f.dtype, f.hidden, f.hidden), st));
+    HIPCHK(c, flk::zero_fill(lw.w1, flk::gemm_tiled_bytes(f.dtype, gpt ? f.ffn : 2 * f.ffn, f.hidden), st));
+    HIPCHK(c, flk::zero_fill(lw.w2, flk::gemm_tiled_bytes(f.dtype, f.hidden, f.ffn), st));
+  }
+  HIPCHK(c, flk::retile(f.dtype, at(w->wqkv, 3 * H * H), 3 * f.hidden, f.hidden, lw.wqkv, 0, c->p_qkv.NT, st));
+  HIPCHK(c, flk::retile(f.dtype, at(w->wo, H * H), f.hidden, f.hidden, lw.wo, 0, c->p_o.NT, st));
+  HIPCHK(c, flk::retile(f.dtype, at(w->w1, F * H), f.ffn, f.hidden, lw.w1, 0, c->p_1.NT, st));
+  if (!gpt) HIPCHK(c, flk::retile(f.dtype, at(w->wu, F * H), f.ffn, f.hidden, lw.w1, f.ffn, c->p_1.NT, st));
+  HIPCHK(c, flk::retile(f.dtype, at(w->w2, H * F), f.hidden, f.ffn, lw.w2, 0, c->p_2.NT, st));
+  if (gpt) {
+    if ((rc = copy_in(c, lw.ln1_b, at(w->ln1_b, H), H * e, "ln1_b")) != FLOVER_OK) return rc;
+    if ((rc = copy_in(c, lw.ln2_b, at(w->ln2_b, H), H * e, "ln2_b")) != FLOVER_OK) return rc;
+    if ((rc = copy_in(c, lw.bqkv, at(w->bqkv, 3 * H), 3 * H * e, "bqkv")) != FLOVER_OK) return rc;
+    if ((rc = copy_in(c, lw.bo, at(w->bo, H), H * e, "bo")) != FLOVER_OK) return rc;
+    if ((rc = copy_in(c, lw.b1, at(w->b1, F), F * e, "b1")) != FLOVER_OK) return rc;
+    if ((rc = copy_in(c, lw.b2, at(w->b2, H), H * e, "b2")) != FLOVER_OK) return rc;
+  }
+  if (!c->layer_loaded[l]) {
+    c->layer_loaded[l] = true;
+    c->layers_loaded += 1;
+  }
+  return FLOVER_OK;
+}
+
 // Frees what the context owns outside the arena (pinned staging, events, the pre-processing stream).
 void release(flover_ctx* c) {
   for (Lane* ln : {&c->step_lane, &c->prep_lane_own}) {
@@ -595,40 +637,16 @@ int32_t flover_init(const flover_config* cfg, const flover_weights* w, flover_ct
   }
 
   const flover_config& f = c->cfg;
-  const int e = esize(f.dtype), L = f.n_layer, H = f.hidden, F = f.ffn, V = f.vocab, S = f.max_seq;
+  const int e = esize(f.dtype), L = f.n_layer, H = f.hidden, V = f.vocab, S = f.max_seq;
   const bool gpt = f.arch == FLOVER_ARCH_GPT;
   hipStream_t st = c->st;
   // everything the kernels may read before it is written starts at zero (padding tiles, cache, row buffers)
   HIPTRY(flk::zero_fill((char*)cfg->arena + c->act_off, need - c->act_off, st));
-  for (int l = 0; l < L; ++l) {
-    LayerW& lw = c->lw[l];
-    const size_t o1 = (size_t)l * H * e;
-    TRY(copy_in(c, lw.ln1_g, w->ln1_g ? (const char*)w->ln1_g + o1 : nullptr, (size_t)H * e, "ln1_g"));
-    TRY(copy_in(c, lw.ln2_g, w->ln2_g ? (const char*)w->ln2_g + o1 : nullptr, (size_t)H * e, "ln2_g"));
-    if (!w->wqkv || !w->wo || !w->w1 || !w->w2 || (!gpt && !w->wu)) {
-      c->err = "missing weight matrix";
-      return bail(FLOVER_E_INVAL);
-    }
-    if (f.dtype != FLOVER_F32) {
-      HIPTRY(flk::zero_fill(lw.wqkv, flk::gemm_tiled_bytes(f.dtype, 3 * H, H), st));
-      HIPTRY(flk::zero_fill(lw.wo, flk::gemm_tiled_bytes(f.dtype, H, H), st));
-      HIPTRY(flk::zero_fill(lw.w1, flk::gemm_tiled_bytes(f.dtype, gpt ? F : 2 * F, H), st));
-      HIPTRY(flk::zero_fill(lw.w2, flk::gemm_tiled_bytes(f.dtype, H, F), st));
-    }
-    HIPTRY(flk::retile(f.dtype, (const char*)w->wqkv + (size_t)l * 3 * H * H * e, 3 * H, H, lw.wqkv, 0, c->p_qkv.NT, st));
-    HIPTRY(flk::retile(f.dtype, (const char*)w->wo + (size_t)l * H * H * e, H, H, lw.wo, 0, c->p_o.NT, st));
-    HIPTRY(flk::retile(f.dtype, (const char*)w->w1 + (size_t)l * F * H * e, F, H, lw.w1, 0, c->p_1.NT, st));
-    if (!gpt) HIPTRY(flk::retile(f.dtype, (const char*)w->wu + (size_t)l * F * H * e, F, H, lw.w1, F, c->p_1.NT, st));
-    HIPTRY(flk::retile(f.dtype, (const char*)w->w2 + (size_t)l * H * F * e, H, F, lw.w2, 0, c->p_2.NT, st));
-    if (gpt) {
-      TRY(copy_in(c, lw.ln1_b, w->ln1_b ? (const char*)w->ln1_b + o1 : nullptr, (size_t)H * e, "ln1_b"));
-      TRY(copy_in(c, lw.ln2_b, w->ln2_b ? (const char*)w->ln2_b + o1 : nullptr, (size_t)H * e, "ln2_b"));
-      TRY(copy_in(c, lw.bqkv, w->bqkv ? (const char*)w->bqkv + (size_t)l * 3 * H * e : nullptr, (size_t)3 * H * e, "bqkv"));
-      TRY(copy_in(c, lw.bo, w->bo ? (const char*)w->bo + o1 : nullptr, (size_t)H * e, "bo"));
-      TRY(copy_in(c, lw.b1, w->b1 ? (const char*)w->b1 + (size_t)l * F * e : nullptr, (size_t)F * e, "b1"));
-      TRY(copy_in(c, lw.b2, w->b2 ? (const char*)w->b2 + o1 : nullptr, (size_t)H * e, "b2"));
-    }
-  }
+  // every per-layer pointer NULL: the layers are handed over one by one with flover_set_layer_weights
+  const bool deferred = !w->ln1_g && !w->ln2_g && !w->wqkv && !w->wo && !w->w1 && !w->w2 && !w->wu;
+  c->layer_loaded.assign(L, false);
+  if (!deferred)
+    for (int l = 0; l < L; ++l) TRY(load_layer(c, l, w, l));
   TRY(copy_in(c, c->wte, w->wte, (size_t)V * H * e, "wte"));
   TRY(copy_in(c, c->lnf_g, w->lnf_g, (size_t)H * e, "lnf_g"));
   if (gpt) {
@@ -662,6 +680,18 @@ int32_t flover_init(const flover_config* cfg, const flover_weights* w, flover_ct
 #undef HIPTRY
 }
 
+int32_t flover_set_layer_weights(flover_ctx* c, int32_t layer, const flover_weights* w) {
+  if (!c || !w) return fail(c, FLOVER_E_INVAL, "null argument");
+  std::lock_guard<std::mutex> lock(c->mu);
+  if (layer < 0 || layer >= c->cfg.n_layer) return fail(c, FLOVER_E_INVAL, "layer out of range");
+  for (const Slot& s : c->slots)
+    if (s.state != FLOVER_SLOT_EMPTY) return fail(c, FLOVER_E_STATE, "requests are in flight");
+  int rc = load_layer(c, layer, w, 0);
+  if (rc != FLOVER_OK) return rc;
+  HIPCHK(c, hipStreamSynchronize(c->st));   // the caller may free or overwrite its copy on return
+  return FLOVER_OK;
+}
+
 int32_t flover_destroy(flover_ctx* ctx) {
   if (!ctx) return FLOVER_OK;
   (void)hipStreamSynchronize(ctx->st);
@@ -679,6 +709,7 @@ int32_t flover_add_request(flover_ctx* c, uint64_t req_id, const int32_t* prompt
   for (int i = 0; i < P; ++i)
     if (prompt[i] < 0 || prompt[i] >= f.vocab) return fail(c, FLOVER_E_INVAL, "prompt token out of range");
   std::lock_guard<std::mutex> lock(c->mu);
+  if (c->layers_loaded < f.n_layer) return fail(c, FLOVER_E_STATE, "layer weights are missing: flover_set_layer_weights for every layer first");
   if (known(c, req_id)) return fail(c, FLOVER_E_INVAL, "req_id already waiting or live");
   Waiting r{req_id, std::vector<int32_t>(prompt, prompt + P), max_new};
   int slot = -1;
@@ -701,6 +732,7 @@ int32_t flover_add_request_cached(flover_ctx* c, uint64_t req_id, int32_t contex
     return fail(c, FLOVER_E_INVAL, "context_len / max_new_tokens out of range");
   if (next_token < 0 || next_token >= f.vocab) return fail(c, FLOVER_E_INVAL, "token out of range");
   std::lock_guard<std::mutex> lock(c->mu);
+  if (c->layers_loaded < f.n_layer) return fail(c, FLOVER_E_STATE, "layer weights are missing: flover_set_layer_weights for every layer first");
   if (known(c, req_id)) return fail(c, FLOVER_E_INVAL, "req_id already waiting or live");
   if (!c->reque.empty()) return fail(c, FLOVER_E_FULL, "requests are waiting for a slot");
   const int slot = place(c);

@@ -525,3 +525,38 @@ def test_pipelined_abi_errors():
     out = srv.step()                             # and works again afterwards, continuing from the host token
     assert out.n_live == 1
     srv.close()
+
+
+PER_LAYER = ("ln1_g", "ln1_b", "wqkv", "bqkv", "wo", "bo", "ln2_g", "ln2_b", "w1", "b1", "wu", "w2", "b2")
+
+
+@pytest.mark.parametrize("name", ["tiny_gpt", "small_llama16"])
+def test_layer_by_layer_weight_hand_over_equals_the_stacked_init(name):
+    import paper_2305_13484_amd as fl
+    cfg = getattr(synth, name)()
+    w = to_device(synth.make_weights(cfg, 51))
+    reqs = synth.stream_small(52, cfg.V, n=5, arrive_hi=3, p_lo=2, p_hi=20, g_lo=2, g_hi=8)
+    ref = gpu_run_stream(cfg, w, reqs)
+    srv = fl.Flover(cfg, {k: v for k, v in w.items() if k not in PER_LAYER})
+    with pytest.raises(fl.FloverError):
+        srv.add_request(1, [1, 2], 2)                       # layers are missing
+    for l in reversed(range(cfg.L)):                          # any order
+        srv.set_layer_weights(l, {k: w[k][l].contiguous() for k in PER_LAYER if k in w})
+    toks, logits = {}, {}
+    pending = sorted(reqs, key=lambda r: (r.arrival_step, r.req_id))
+    i = done = s = 0
+    while done < len(reqs):
+        while i < len(pending) and pending[i].arrival_step <= s:
+            srv.add_request(pending[i].req_id, pending[i].prompt, pending[i].gen_len)
+            i += 1
+        out = srv.step(True)
+        for j in range(out.n_live):
+            toks.setdefault(int(out.req_id[j]), []).append(int(out.token[j]))
+            logits.setdefault(int(out.req_id[j]), []).append(out.logits[j].clone())
+        done += int(out.finished.sum())
+        srv.reorder_evict()
+        s += 1
+    with pytest.raises(fl.FloverError):
+        srv.set_layer_weights(cfg.L, {k: w[k][0].contiguous() for k in PER_LAYER if k in w})   # out of range
+    srv.close()
+    _same_results(ref, (toks, logits), reqs)
