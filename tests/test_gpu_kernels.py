@@ -55,10 +55,11 @@ def test_gemm_row_result_does_not_depend_on_other_rows(dtype):
     assert torch.equal(alone[0], full[77])
 
 
-@pytest.mark.parametrize("M", [8, 24, 48, 128])
+@pytest.mark.parametrize("M", [8, 24, 48, 128, 600])
 def test_gemm_full_size_sampled_columns(M):
     """The 7B shapes the benchmark runs, at row counts that select each kernel variant (<=16 direct, <=32 / <=64 / <=128
-    LDS-staged with 4 or 8 waves); sampled output columns from the oracle."""
+    LDS-staged with 4 or 8 waves, above that the 256-row blocks of a context pass with a ragged last block); sampled
+    output columns from the oracle."""
     dtype = synth.DT_BF16
     for (N, K) in [(12288, 4096), (4096, 11008), (22016, 4096), (32000, 4096)]:
         print("gemm full", M, N, K, flush=True)

@@ -347,9 +347,11 @@ def test_fused_equals_alone_at_7b_width_many_rows():
 
 
 @pytest.mark.parametrize("make", [lambda: synth.tiny_llama(synth.DT_BF16, C=4, S=700), lambda: synth.tiny_gpt(C=4, S=700),
-                                  lambda: synth.small_gpt16(synth.DT_F16, C=4, S=300)])
+                                  lambda: synth.small_gpt16(synth.DT_F16, C=4, S=300),
+                                  lambda: synth.tiny_llama(synth.DT_F16, C=4, S=1300)])
 def test_long_prompts_through_the_context_pass(make):
-    """Prompts long enough for several 512-row context passes, several 256-position chunks and ragged last query
+    """Prompts long enough for two context passes (more than 1024 rows), several 256-row GEMM blocks with a ragged
+    last one, several 256-position chunks and ragged last query
     blocks; every generated token's logits are compared with the oracle (which fills its cache one token at a time)."""
     cfg = make()
     w = synth.make_weights(cfg, 17)
