@@ -325,13 +325,14 @@ int run_rows(flover_ctx* c, Lane& ln, const Row* rows, int n, bool want_tokens, 
       ++n_items;
     }
   }
-  // context pass: runs of consecutive positions of one slot are served kPrefillQB query rows per wave
+  // context pass: runs of consecutive positions of one slot are served several query rows per wave
+  const int qb = flk::prefill_rows_per_block(f.dtype);
   int n_blocks = 0;
   int* blk = items + 2 * n_items;
   if (context_pass) {
     for (int i = 0; i < n;) {
       int nr = 1;
-      while (nr < flk::kPrefillQB && i + nr < n && rows[i + nr].slot == rows[i].slot && rows[i + nr].pos == rows[i].pos + nr)
+      while (nr < qb && i + nr < n && rows[i + nr].slot == rows[i].slot && rows[i + nr].pos == rows[i].pos + nr)
         ++nr;
       for (int ch = 0; ch < nchunk[i + nr - 1]; ++ch) {
         blk[4 * n_blocks] = i;

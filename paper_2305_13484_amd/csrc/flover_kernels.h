@@ -60,10 +60,11 @@ struct AttnWork {          // all device pointers
   float* po;               // [n_items][nh][d]
   int n_items;
   int chunk;
-  const int4* blocks = nullptr;   // pre-processing passes: (first row, rows <= kPrefillQB, chunk, -)
+  const int4* blocks = nullptr;   // pre-processing passes: (first row, rows <= prefill_rows_per_block, chunk, -)
   int n_blocks = 0;
 };
-constexpr int kPrefillQB = 8;     // query rows one wave serves in a pre-processing pass
+constexpr int kPrefillQB = 8;     // query rows one wave serves in a pre-processing pass (fp32 models)
+int prefill_rows_per_block(int dtype);   // rows per entry of AttnWork::blocks: 8 for fp32, 32 for the 16-bit (MFMA) kernel
 int attn_chunk();   // positions per wave task; fixed for the process, so chunking depends on a request's own length only
 // ev0 / ev1 (optional) are recorded right before / after the streaming kernel (the merge kernel follows ev1).
 hipError_t decode_attention(int dtype, int d, const void* q, const void* kc, const void* vc, const AttnWork& w, int M,

@@ -280,9 +280,181 @@ __global__ __launch_bounds__(256) void attn_prefill_kernel(const void* __restric
   }
 }
 
+// ---------------------------------------------------------------- pre-processing variant on the matrix cores
+// 16-bit models: a wave serves 32 consecutive query rows (two tiles of 16) and walks its chunk 32 keys at a time.
+//   scores   S^T[key][query] = K . Q^T   : A = K rows (a lane's 16 bytes of a cache row are 8 consecutive d of one
+//                                          key), B = Q^T (8 consecutive d of one query) -- both straight from memory;
+//   softmax  per query = per output column: 8 values in the lane, then the 4 lane groups (2 shuffles);
+//   output   O^T[d][query] += V^T . P^T  : B = P^T is what the lane already holds from S^T (keys 4g..4g+3 of both
+//            16-key tiles = its 8 k-slots), A = V^T needs 8 keys of one d per lane: the V rows are staged in LDS
+//            (wave-private, row stride D + 8 elements: 16-byte aligned and conflict-free) and read back transposed.
+// P is rounded to the model dtype for the second product; m, l and the accumulators stay fp32.  Same chunking, partial
+// layout and merge kernel as the other variants.     grid = (n_blocks, n_head / 4), block = 256 (a wave per head).
+constexpr int kPrefillMfmaQB = 32;
+template <int DT> __device__ __forceinline__ uint32_t pack2(float a, float b) {
+  if constexpr (DT == DT_BF16) return (uint32_t)f32_to_bf16(a) | ((uint32_t)f32_to_bf16(b) << 16);
+  else return (uint32_t)f32_to_f16(a) | ((uint32_t)f32_to_f16(b) << 16);
+}
+template <int DT> __device__ __forceinline__ f32x4_t mfma_kq(const u32x4_t& a, const u32x4_t& b, f32x4_t c) {
+  if constexpr (DT == DT_BF16)
+    return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, a), __builtin_bit_cast(bf16x8_t, b), c, 0, 0, 0);
+  else
+    return __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(f16x8_t, a), __builtin_bit_cast(f16x8_t, b), c, 0, 0, 0);
+}
+
+template <int DT, int D>
+__global__ __launch_bounds__(256) void attn_prefill_mfma_kernel(const void* __restrict__ q, const void* __restrict__ kc,
+                                                                const void* __restrict__ vc,
+                                                                const int4* __restrict__ blocks,
+                                                                const int* __restrict__ row_slot,
+                                                                const int* __restrict__ row_len,
+                                                                const int* __restrict__ row_item0,
+                                                                const int* __restrict__ row_nchunk, int nh, int Smax,
+                                                                int chunk, float scale, float* __restrict__ pml,
+                                                                float* __restrict__ po) {
+  static_assert(DT != DT_F32, "16-bit models only");
+  constexpr int QT = kPrefillMfmaQB / 16;   // query tiles per wave
+  constexpr int KS = D / 32;                // MFMA steps over the head dimension
+  constexpr int DTL = D / 16;               // output tiles over the head dimension
+  constexpr int VSTR = D + 8;               // LDS row stride (elements)
+  constexpr int LPRV = D / 8;               // lanes per V row when staging (16 bytes each)
+  constexpr int RPL = 64 / LPRV;            // V rows per wave load
+  __shared__ __attribute__((aligned(16))) uint16_t vlds[4][32 * VSTR];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int g = lane >> 4, n = lane & 15;
+  const int4 bk = blocks[blockIdx.x];
+  const int first = bk.x, nr = bk.y, ch = bk.z;
+  const int hd = blockIdx.y * 4 + wave;
+  const int slot = row_slot[first];
+  const int len0 = row_len[first];                          // rows are consecutive positions: len_i = len0 + i
+  const int j0 = ch * chunk, j1 = min(len0 + nr - 1, j0 + chunk);
+  uint16_t* vl = vlds[wave];
+
+  u32x4_t qf[QT][KS];
+#pragma unroll
+  for (int t = 0; t < QT; ++t) {
+    const int r = first + min(t * 16 + n, nr - 1);
+    const uint16_t* qr = (const uint16_t*)q + (size_t)(r * nh + hd) * D + g * 8;
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) qf[t][ks] = *(const u32x4_t*)(qr + ks * 32);
+  }
+  const size_t head_off = ((size_t)slot * nh + hd) * Smax * D;
+  const uint16_t* kb = (const uint16_t*)kc + head_off;
+  const uint16_t* vb = (const uint16_t*)vc + head_off;
+
+  f32x4_t oacc[DTL][QT];
+  float m[QT], l[QT];
+#pragma unroll
+  for (int t = 0; t < QT; ++t) {
+    m[t] = -INFINITY;
+    l[t] = 0.f;
+#pragma unroll
+    for (int dt = 0; dt < DTL; ++dt) oacc[dt][t] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+  }
+
+  for (int jb = j0; jb < j1; jb += 32) {
+    // K rows as the A operand, V rows to LDS (rows past the chunk repeat its last row; they are masked below)
+    u32x4_t kf[2][KS], vr[32 / RPL];
+#pragma unroll
+    for (int kt = 0; kt < 2; ++kt) {
+      const uint16_t* kr = kb + (size_t)min(jb + kt * 16 + n, j1 - 1) * D + g * 8;
+#pragma unroll
+      for (int ks = 0; ks < KS; ++ks) kf[kt][ks] = *(const u32x4_t*)(kr + ks * 32);
+    }
+#pragma unroll
+    for (int i = 0; i < 32 / RPL; ++i) {
+      const int row = i * RPL + lane / LPRV;
+      vr[i] = *(const u32x4_t*)(vb + (size_t)min(jb + row, j1 - 1) * D + (lane % LPRV) * 8);
+    }
+    __builtin_amdgcn_wave_barrier();          // the previous block's transposed reads come before these writes
+#pragma unroll
+    for (int i = 0; i < 32 / RPL; ++i) {
+      const int row = i * RPL + lane / LPRV;
+      *(u32x4_t*)(vl + row * VSTR + (lane % LPRV) * 8) = vr[i];
+    }
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+
+    // scores: rows = keys kt*16 + 4g + r, column = query n of tile t
+    u32x4_t pb[QT];
+#pragma unroll
+    for (int t = 0; t < QT; ++t) {
+      f32x4_t sacc[2];
+#pragma unroll
+      for (int kt = 0; kt < 2; ++kt) {
+        sacc[kt] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) sacc[kt] = mfma_kq<DT>(kf[kt][ks], qf[t][ks], sacc[kt]);
+      }
+      const int qi = t * 16 + n;
+      const int lim = (qi < nr) ? min(len0 + qi, j1) : 0;        // causal: key < len_i, and inside the chunk
+      float sc[8];
+      float tmax = -INFINITY;
+#pragma unroll
+      for (int kt = 0; kt < 2; ++kt)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+          const int key = jb + kt * 16 + 4 * g + r;
+          const float v = (key < lim) ? sacc[kt][r] * scale : -INFINITY;
+          sc[kt * 4 + r] = v;
+          tmax = fmaxf(tmax, v);
+        }
+      tmax = fmaxf(tmax, __shfl_xor(tmax, 16, 64));
+      tmax = fmaxf(tmax, __shfl_xor(tmax, 32, 64));
+      const float mn = fmaxf(m[t], tmax);
+      const float ms = (mn == -INFINITY) ? 0.f : mn;
+      const float alpha = __expf(m[t] - ms);
+      float p[8], ps = 0.f;
+#pragma unroll
+      for (int j = 0; j < 8; ++j) {
+        p[j] = __expf(sc[j] - ms);
+        ps += p[j];
+      }
+      l[t] = l[t] * alpha + ps;                                   // per-lane share; the lane groups are added at the end
+      m[t] = mn;
+#pragma unroll
+      for (int dt = 0; dt < DTL; ++dt) oacc[dt][t] *= alpha;
+      pb[t] = u32x4_t{pack2<DT>(p[0], p[1]), pack2<DT>(p[2], p[3]), pack2<DT>(p[4], p[5]), pack2<DT>(p[6], p[7])};
+    }
+    // output: A = V^T, k-slot j of lane group g <-> key 4g + j (j < 4) or 16 + 4g + (j - 4), as in pb
+#pragma unroll
+    for (int dt = 0; dt < DTL; ++dt) {
+      const uint16_t* vcol = vl + dt * 16 + n;
+      uint32_t w[4];
+#pragma unroll
+      for (int jj = 0; jj < 4; ++jj) {
+        const int ka = (jj < 2) ? 4 * g + 2 * jj : 16 + 4 * g + 2 * (jj - 2);
+        w[jj] = (uint32_t)vcol[ka * VSTR] | ((uint32_t)vcol[(ka + 1) * VSTR] << 16);
+      }
+      const u32x4_t va = u32x4_t{w[0], w[1], w[2], w[3]};
+#pragma unroll
+      for (int t = 0; t < QT; ++t) oacc[dt][t] = mfma_kq<DT>(va, pb[t], oacc[dt][t]);
+    }
+  }
+  // partial results: lane (n, g) owns O[query n][d = dt*16 + 4g .. +3]
+#pragma unroll
+  for (int t = 0; t < QT; ++t) {
+    float lv = l[t];
+    lv += __shfl_xor(lv, 16, 64);
+    lv += __shfl_xor(lv, 32, 64);
+    const int qi = t * 16 + n;
+    const int r = first + min(qi, nr - 1);
+    if (qi < nr && ch < row_nchunk[r]) {                         // this chunk holds keys this query may see
+      const size_t pi = (size_t)(row_item0[r] + ch) * nh + hd;
+#pragma unroll
+      for (int dt = 0; dt < DTL; ++dt) *(f32x4_t*)(po + pi * D + dt * 16 + 4 * g) = oacc[dt][t];
+      if (g == 0) {
+        pml[pi * 2] = m[t];
+        pml[pi * 2 + 1] = lv;
+      }
+    }
+  }
+}
+
 // ---------------------------------------------------------------- host side
 
 int attn_chunk() { return 256; }
+int prefill_rows_per_block(int dtype) { return dtype == DT_F32 ? kPrefillQB : kPrefillMfmaQB; }
 
 template <int DT, int D>
 static void launch_attn(const void* q, const void* kc, const void* vc, const AttnWork& w, int M, int nh, int Smax,
@@ -314,8 +486,12 @@ template <int DT, int D>
 static void launch_prefill(const void* q, const void* kc, const void* vc, const AttnWork& w, int M, int nh, int Smax,
                            void* out, hipStream_t st) {
   const float scale = 1.0f / sqrtf((float)D);
-  attn_prefill_kernel<DT, D, kPrefillQB><<<dim3(w.n_blocks, nh / 4), 256, 0, st>>>(
-      q, kc, vc, w.blocks, w.row_slot, w.row_len, w.row_item0, w.row_nchunk, nh, Smax, w.chunk, scale, w.pml, w.po);
+  if constexpr (DT == DT_F32)
+    attn_prefill_kernel<DT, D, kPrefillQB><<<dim3(w.n_blocks, nh / 4), 256, 0, st>>>(
+        q, kc, vc, w.blocks, w.row_slot, w.row_len, w.row_item0, w.row_nchunk, nh, Smax, w.chunk, scale, w.pml, w.po);
+  else
+    attn_prefill_mfma_kernel<DT, D><<<dim3(w.n_blocks, nh / 4), 256, 0, st>>>(
+        q, kc, vc, w.blocks, w.row_slot, w.row_len, w.row_item0, w.row_nchunk, nh, Smax, w.chunk, scale, w.pml, w.po);
   attn_merge_kernel<DT, D><<<dim3(M, nh), D, 0, st>>>(w.pml, w.po, w.row_item0, w.row_nchunk, nh, out);
 }
 
