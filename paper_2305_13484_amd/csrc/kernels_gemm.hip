@@ -408,17 +408,30 @@ size_t gemm_tiled_bytes(int dtype, int N, int K) {
   return Npad * K * 2;
 }
 
-// Context passes: fewer K slices, just enough for the (column block, row block, slice) tasks to fill the chip; the
-// partial sums written and re-read per slice are what limits a many-row contraction otherwise.
+// Context passes: the slice count that minimises a simple cost model of the 256 x 256 blocks on 256 compute units:
+// rounds of blocks x k-blocks per slice (about 1 us per k-block step of a block, measured), plus the fp32 partial sums
+// written by this kernel and re-read by the next one (about 5 TB/s) -- at hundreds of rows those outweigh the weights
+// when the iteration's slicing is kept, while a single slice leaves most of the chip idle for the 4096-column matrices.
 GemmPlan context_plan(const GemmPlan& p, int dtype, int M) {
   GemmPlan q = p;
   if (dtype == DT_F32 || M <= 128) return q;
   const int ngroups = p.Npad / (16 * p.NT);
-  const int nx = (ngroups + 3) / 4, nz = (M + 255) / 256;
-  const int want = (256 + (nx * nz) / 2) / (nx * nz);
-  q.S = std::max(1, std::min(p.S, want));
+  const long units = (long)((ngroups + 3) / 4) * ((M + 255) / 256);
+  const int smax = p.S;   // never more slices than the iteration's plan: the partial-sum buffer is sized for those
+  double best = 0.0;
+  int bestS = 1;
+  for (int S = 1; S <= smax; ++S) {
+    const int kbs = (p.KB + S - 1) / S;
+    if ((p.KB + kbs - 1) / kbs != S) continue;                       // slice counts that leave an empty last slice
+    const double rounds = (double)((units * S + 255) / 256);
+    const double cost = rounds * kbs * 1.0 + (double)S * M * p.N * 8.0 / 5.0e6;   // microseconds
+    if (S == 1 || cost < best) {
+      best = cost;
+      bestS = S;
+    }
+  }
+  q.S = bestS;
   q.kbs = (p.KB + q.S - 1) / q.S;
-  q.S = (p.KB + q.kbs - 1) / q.kbs;
   return q;
 }
 
