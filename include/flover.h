@@ -263,6 +263,12 @@ int32_t flover_k_compact(void* cache, int32_t L, int32_t C, int32_t n_head, int3
  * workspace holds the split-K partial sums.  K % 32 == 0.  y == NULL leaves the result as partial sums in the
  * workspace (timing the streaming kernel alone). */
 int32_t flover_k_gemm_tiled_bytes(int32_t dtype, int32_t N, int32_t K, uint64_t* out);
+/* [host only] K slicing of the weight GEMM: *slices partial sums, each over *k_blocks_per_slice blocks of 32 input
+ * features (the last slice may be shorter).  context_rows == 0: the fused iteration's slicing, a function of (dtype, N,
+ * K) alone, so that a row's result cannot depend on how many rows are live; context_rows > 0: the slicing of a
+ * pre-processing pass of that many rows of one request (never more slices than the iteration's). */
+int32_t flover_k_gemm_plan(int32_t dtype, int32_t N, int32_t K, int32_t context_rows, int32_t* slices,
+                           int32_t* k_blocks_per_slice);
 int32_t flover_k_gemm_workspace_bytes(int32_t dtype, int32_t M, int32_t N, int32_t K, uint64_t* out);
 int32_t flover_k_gemm_retile(int32_t dtype, const void* W, int32_t N, int32_t K, void* w_tiled, void* stream);
 int32_t flover_k_gemm(int32_t dtype, const void* x, const void* w_tiled, int32_t M, int32_t N, int32_t K, float* y,

@@ -18,7 +18,7 @@ _LIB_PATH = os.path.join(_HERE, "libflover.so")
 EXPORTED_SYMBOLS = [
     "flover_query_arena_bytes", "flover_init", "flover_destroy", "flover_last_error", "flover_add_request",
     "flover_step", "flover_reorder_evict", "flover_mark_finished", "flover_set_next_token", "flover_get_state",
-    "flover_get_kv_cache", "flover_last_step_launches", "flover_step_submit", "flover_step_collect", "flover_set_layer_weights", "flover_set_profile", "flover_get_profile", "flover_k_find_window", "flover_k_attention_workspace_bytes",
+    "flover_get_kv_cache", "flover_last_step_launches", "flover_step_submit", "flover_step_collect", "flover_set_layer_weights", "flover_k_gemm_plan", "flover_set_profile", "flover_get_profile", "flover_k_find_window", "flover_k_attention_workspace_bytes",
     "flover_k_decode_attention", "flover_k_compact_workspace_bytes", "flover_k_compact", "flover_k_gemm_tiled_bytes",
     "flover_k_gemm_workspace_bytes", "flover_k_gemm_retile", "flover_k_gemm", "flover_add_request_cached",
     "flover_k_copy_probe",
@@ -290,6 +290,13 @@ class Flover:
 
 
 # ------------------------------------------------------------------ operation-level entry points
+
+def k_gemm_plan(dtype: int, N: int, K: int, context_rows: int = 0) -> Tuple[int, int]:
+    """(slices, k-blocks per slice) of the weight GEMM; host only."""
+    s, kbs = C.c_int32(), C.c_int32()
+    _check(load_library().flover_k_gemm_plan(dtype, N, K, context_rows, C.byref(s), C.byref(kbs)))
+    return s.value, kbs.value
+
 
 def arena_bytes(cfg, async_preprocess: bool = False) -> int:
     """flover_query_arena_bytes for a config object (fields as for Flover)."""

@@ -1259,6 +1259,18 @@ __global__ void slice_sum_kernel(const float* __restrict__ part, int S, size_t s
 }
 }  // namespace flk
 
+extern "C" int32_t flover_k_gemm_plan(int32_t dtype, int32_t N, int32_t K, int32_t context_rows, int32_t* slices,
+                                      int32_t* k_blocks_per_slice) {
+  if (dtype < FLOVER_F32 || dtype > FLOVER_BF16 || N < 1 || K < 32 || K % 32 || context_rows < 0 || !slices ||
+      !k_blocks_per_slice)
+    return fail(nullptr, FLOVER_E_INVAL, "bad argument");
+  flk::GemmPlan p = flk::gemm_plan(dtype, N, K);
+  if (context_rows > 0) p = flk::context_plan(p, dtype, context_rows);
+  *slices = p.S;
+  *k_blocks_per_slice = dtype == FLOVER_F32 ? K / 32 : p.kbs;   // the fp32 kernel takes all of K in one slice
+  return FLOVER_OK;
+}
+
 extern "C" int32_t flover_k_gemm(int32_t dtype, const void* x, const void* w_tiled, int32_t M, int32_t N, int32_t K,
                                  float* y, void* workspace, uint64_t workspace_bytes, void* stream) {
   if (dtype < FLOVER_F32 || dtype > FLOVER_BF16 || M < 0 || N < 1 || K < 32 || K % 32)
