@@ -18,7 +18,8 @@
 //     other rows are live (the paper's premise that fused requests undergo identical operations).  A context pass
 //     holds rows of one request and is sliced by that request's row count too (context_plan): fewer slices, because
 //     at hundreds of rows the fp32 partial sums would outweigh the weights.
-//   * MFMA v_mfma_f32_16x16x32_{bf16,f16}: A = 16 rows of x, B = 16 columns of W, 32-deep.
+//   * MFMA v_mfma_f32_16x16x32_{bf16,f16}: A = 16 columns of W, B = 16 rows of x, 32-deep: the accumulator tile is
+//     y^T, so a lane holds 4 consecutive output columns of one row and stores them as one 16-byte write.
 // fp32 models (tiny configurations only) use a plain FMA kernel on the untiled matrix.
 #include <algorithm>
 
@@ -99,7 +100,7 @@ __global__ __launch_bounds__(256) void gemm16_direct_kernel(const uint16_t* __re
 #pragma unroll
         for (int i = 0; i < MT; ++i)
 #pragma unroll
-          for (int t = 0; t < NT; ++t) acc[i][t] = mfma16<DT>(aq[j % PFA][i], bq[j][t], acc[i][t]);
+          for (int t = 0; t < NT; ++t) acc[i][t] = mfma16<DT>(bq[j][t], aq[j % PFA][i], acc[i][t]);
       }
       const int kw = min(kb + j + PFW, kb1 - 1);      // tail re-reads the last block (in bounds, unused)
 #pragma unroll
@@ -114,12 +115,8 @@ __global__ __launch_bounds__(256) void gemm16_direct_kernel(const uint16_t* __re
   for (int i = 0; i < MT; ++i)
 #pragma unroll
     for (int t = 0; t < NT; ++t) {
-      const int n = (g * NT + t) * 16 + (lane & 15);
-#pragma unroll
-      for (int r = 0; r < 4; ++r) {
-        const int m = m0 + i * 16 + (lane >> 4) * 4 + r;
-        if (m < M && n < N) out[(size_t)m * ldc + n] = acc[i][t][r];
-      }
+      const int n = (g * NT + t) * 16 + (lane >> 4) * 4, m = m0 + i * 16 + (lane & 15);
+      if (m < M && n < ldc) *(f32x4_t*)(out + (size_t)m * ldc + n) = acc[i][t];
     }
 }
 
@@ -209,7 +206,7 @@ __global__ __launch_bounds__(64 * 4 * (NT / NTW)) void gemm16_lds_kernel(const u
 #pragma unroll
             for (int i = 0; i < MT; ++i)
 #pragma unroll
-              for (int t = 0; t < NTW; ++t) acc[i][t] = mfma16<DT>(af[i], bq[cc * KC + kc][t], acc[i][t]);
+              for (int t = 0; t < NTW; ++t) acc[i][t] = mfma16<DT>(bq[cc * KC + kc][t], af[i], acc[i][t]);
           }
           const int kk = min(kb + PF, kb1 - 1);
 #pragma unroll
@@ -227,12 +224,8 @@ __global__ __launch_bounds__(64 * 4 * (NT / NTW)) void gemm16_lds_kernel(const u
   for (int i = 0; i < MT; ++i)
 #pragma unroll
     for (int t = 0; t < NTW; ++t) {
-      const int n = (g * NT + sub * NTW + t) * 16 + (lane & 15);
-#pragma unroll
-      for (int r = 0; r < 4; ++r) {
-        const int m = m0 + i * 16 + (lane >> 4) * 4 + r;
-        if (m < M && n < N) out[(size_t)m * ldc + n] = acc[i][t][r];
-      }
+      const int n = (g * NT + sub * NTW + t) * 16 + (lane >> 4) * 4, m = m0 + i * 16 + (lane & 15);
+      if (m < M && n < ldc) *(f32x4_t*)(out + (size_t)m * ldc + n) = acc[i][t];
     }
 }
 
@@ -314,7 +307,7 @@ __global__ __launch_bounds__(512) void gemm16_rows_kernel(const uint16_t* __rest
               if (i < live_tiles) {               // wave-uniform: row tiles past M are skipped
                 const u32x4_t af = la[(kc * MTB + half * MTW + i) * 64 + lane];
 #pragma unroll
-                for (int t = 0; t < NT; ++t) acc[i][t] = mfma16<DT>(af, bq[cc * KC + kc][t], acc[i][t]);
+                for (int t = 0; t < NT; ++t) acc[i][t] = mfma16<DT>(bq[cc * KC + kc][t], af, acc[i][t]);
               }
           }
           const int kk = min(kb + PF, kb1 - 1);
@@ -332,12 +325,8 @@ __global__ __launch_bounds__(512) void gemm16_rows_kernel(const uint16_t* __rest
   for (int i = 0; i < MTW; ++i)
 #pragma unroll
     for (int t = 0; t < NT; ++t) {
-      const int n = (g * NT + t) * 16 + (lane & 15);
-#pragma unroll
-      for (int r = 0; r < 4; ++r) {
-        const int m = m0 + (half * MTW + i) * 16 + (lane >> 4) * 4 + r;
-        if (m < M && n < N) out[(size_t)m * ldc + n] = acc[i][t][r];
-      }
+      const int n = (g * NT + t) * 16 + (lane >> 4) * 4, m = m0 + (half * MTW + i) * 16 + (lane & 15);
+      if (m < M && n < ldc) *(f32x4_t*)(out + (size_t)m * ldc + n) = acc[i][t];
     }
 }
 
