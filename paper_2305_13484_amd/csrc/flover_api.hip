@@ -57,7 +57,7 @@ struct Lane {
   void *h = nullptr, *q = nullptr, *att = nullptr, *act = nullptr;
   float* part = nullptr;
   int* tok_out = nullptr;
-  int* d_stage = nullptr;   // tok | pos | slot | len | item0 | nchunk | items(2x) | context-pass blocks(4x)
+  int* d_stage = nullptr;   // tok | pos | slot | len | item0 | nchunk | items(4x) | context-pass blocks(4x)
   float *pml = nullptr, *po = nullptr;
   // pinned host staging; a ring so that passes can be queued without waiting for the previous copy
   int* h_stage[kStageRing] = {nullptr, nullptr, nullptr, nullptr};
@@ -214,7 +214,7 @@ size_t layout(flover_ctx* c, char* base) {
   c->max_items = R * chunks;
   size_t pw = 0;
   for (const flk::GemmPlan* p : {&c->p_qkv, &c->p_o, &c->p_1, &c->p_2, &c->p_lm}) pw = std::max(pw, (size_t)p->S * p->ldc);
-  c->stage_ints = (size_t)6 * R + (size_t)6 * c->max_items;   // row arrays, (row, chunk) items, context-pass blocks
+  c->stage_ints = (size_t)6 * R + (size_t)8 * c->max_items;   // row arrays, (row, chunk, slot, len) items, context-pass blocks
   c->act_off = align_up(b.off, 256);
   for (Lane* ln : {&c->step_lane, &c->prep_lane_own}) {
     if (ln == &c->prep_lane_own && !f.async_preprocess) break;
@@ -320,15 +320,17 @@ int run_rows(flover_ctx* c, Lane& ln, const Row* rows, int n, bool want_tokens, 
     const int nc = (len[i] + flk::attn_chunk() - 1) / flk::attn_chunk();
     nchunk[i] = nc;
     for (int ch = 0; ch < nc; ++ch) {
-      items[2 * n_items] = i;
-      items[2 * n_items + 1] = ch;
+      items[4 * n_items] = i;
+      items[4 * n_items + 1] = ch;
+      items[4 * n_items + 2] = rows[i].slot;
+      items[4 * n_items + 3] = len[i];
       ++n_items;
     }
   }
   // context pass: runs of consecutive positions of one slot are served several query rows per wave
   const int qb = flk::prefill_rows_per_block(f.dtype);
   int n_blocks = 0;
-  int* blk = items + 2 * n_items;
+  int* blk = items + 4 * n_items;
   if (context_pass) {
     for (int i = 0; i < n;) {
       int nr = 1;
@@ -344,7 +346,7 @@ int run_rows(flover_ctx* c, Lane& ln, const Row* rows, int n, bool want_tokens, 
       i += nr;
     }
   }
-  HIPCHK(c, hipMemcpyAsync(ln.d_stage, hs, ((size_t)6 * R + (size_t)2 * n_items + (size_t)4 * n_blocks) * 4,
+  HIPCHK(c, hipMemcpyAsync(ln.d_stage, hs, ((size_t)6 * R + (size_t)4 * n_items + (size_t)4 * n_blocks) * 4,
                            hipMemcpyHostToDevice, st));
   if (!wait) {
     HIPCHK(c, hipEventRecord(ln.staged[ri], st));
@@ -353,8 +355,8 @@ int run_rows(flover_ctx* c, Lane& ln, const Row* rows, int n, bool want_tokens, 
   int* ds = ln.d_stage;
   const int *d_tok = ds, *d_pos = ds + R, *d_slot = ds + 2 * R, *d_len = ds + 3 * R, *d_item0 = ds + 4 * R,
             *d_nchunk = ds + 5 * R;
-  flk::AttnWork aw{(const int2*)(ds + 6 * R), d_slot, d_len, d_item0, d_nchunk, ln.pml, ln.po, n_items, flk::attn_chunk()};
-  aw.blocks = (const int4*)(ds + 6 * R + 2 * n_items);
+  flk::AttnWork aw{(const int4*)(ds + 6 * R), d_slot, d_len, d_item0, d_nchunk, ln.pml, ln.po, n_items, flk::attn_chunk()};
+  aw.blocks = (const int4*)(ds + 6 * R + 4 * n_items);
   aw.n_blocks = n_blocks;
   const bool prof = &ln == &c->step_lane && (wait || want_tokens);
   if (&ln == &c->step_lane) c->prof_now = prof;
@@ -1105,7 +1107,7 @@ static size_t attn_ws_layout(int M, int nh, int d, int max_len, size_t* o_items,
   const size_t items = (size_t)M * chunks;
   size_t off = align_up((size_t)4 * M * 4, 256);
   *o_items = off;
-  off = align_up(off + items * 8, 256);
+  off = align_up(off + items * 16, 256);
   *o_pml = off;
   off = align_up(off + items * nh * 2 * 4, 256);
   *o_po = off;
@@ -1144,12 +1146,14 @@ int32_t flover_k_decode_attention(int32_t dtype, const void* q, const void* kcac
   for (int i = 0; i < M; ++i) {
     h_slot[i] = slot[i];
     h_len[i] = len[i];
-    h_item0[i] = (int)items.size() / 2;
+    h_item0[i] = (int)items.size() / 4;
     const int nc = (len[i] + flk::attn_chunk() - 1) / flk::attn_chunk();
     h_nchunk[i] = nc;
     for (int ch = 0; ch < nc; ++ch) {
       items.push_back(i);
       items.push_back(ch);
+      items.push_back(slot[i]);
+      items.push_back(len[i]);
     }
   }
   hipStream_t st = (hipStream_t)stream;
@@ -1158,8 +1162,8 @@ int32_t flover_k_decode_attention(int32_t dtype, const void* q, const void* kcac
   HIPCHK(nullptr, hipMemcpyAsync(ws + o_items, items.data(), items.size() * 4, hipMemcpyHostToDevice, st));
   HIPCHK(nullptr, hipStreamSynchronize(st));
   int* ds = (int*)ws;
-  flk::AttnWork aw{(const int2*)(ws + o_items), ds, ds + M, ds + 2 * M, ds + 3 * M, (float*)(ws + o_pml), (float*)(ws + o_po),
-                   (int)items.size() / 2, flk::attn_chunk()};
+  flk::AttnWork aw{(const int4*)(ws + o_items), ds, ds + M, ds + 2 * M, ds + 3 * M, (float*)(ws + o_pml), (float*)(ws + o_po),
+                   (int)items.size() / 4, flk::attn_chunk()};
   HIPCHK(nullptr, flk::decode_attention(dtype, d, q, kcache, vcache, aw, M, nh, S, out, st));
   return FLOVER_OK;
 }

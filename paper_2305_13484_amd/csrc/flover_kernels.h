@@ -51,7 +51,7 @@ hipError_t logits_argmax(const float* part, int S, size_t stride, int ldp, float
 
 // ---- ragged decode attention
 struct AttnWork {          // all device pointers
-  const int2* items;       // [n_items] (row, chunk)
+  const int4* items;       // [n_items] (row, chunk, slot of the row, cache rows of the row)
   const int* row_slot;     // [M]
   const int* row_len;      // [M] rows of cache attended to (>= 1)
   const int* row_item0;    // [M] first item of the row

@@ -17,12 +17,11 @@
 namespace flk {
 
 // grid = (n_items, n_head / 4), block = 256: wave w handles head blockIdx.y * 4 + w of item blockIdx.x.
-// items[i] = (row, chunk).  Writes unnormalised partial (m, l, o[D]) per (item, head).
+// items[i] = (row, chunk, slot, len).  Writes unnormalised partial (m, l, o[D]) per (item, head).
 template <int DT, int D, int U>
 __global__ __launch_bounds__(256) void attn_partial_kernel(const void* __restrict__ q, const void* __restrict__ kc,
-                                                           const void* __restrict__ vc, const int2* __restrict__ items,
-                                                           const int* __restrict__ row_slot,
-                                                           const int* __restrict__ row_len, int nh, int Smax, int chunk,
+                                                           const void* __restrict__ vc, const int4* __restrict__ items, int nh,
+                                                           int Smax, int chunk,
                                                            float scale, float* __restrict__ pml, float* __restrict__ po) {
   constexpr int EB = (DT == DT_F32) ? 4 : 2;
   constexpr int EPL = 16 / EB;          // elements per lane
@@ -31,8 +30,8 @@ __global__ __launch_bounds__(256) void attn_partial_kernel(const void* __restric
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int item = blockIdx.x;
   const int hd = blockIdx.y * 4 + wave;
-  const int row = items[item].x, ch = items[item].y;
-  const int slot = row_slot[row], len = row_len[row];
+  const int4 it = items[item];          // one load: the cache addresses below depend on nothing else
+  const int row = it.x, ch = it.y, slot = it.z, len = it.w;
   const int j0 = ch * chunk, j1 = min(len, j0 + chunk);
   const int grp = lane / LPR, li = lane % LPR;
 
@@ -51,14 +50,17 @@ __global__ __launch_bounds__(256) void attn_partial_kernel(const void* __restric
 #pragma unroll
   for (int e = 0; e < EPL; ++e) o[e] = 0.f;
 
-  for (int jb = j0; jb < j1; jb += RPW * U) {
-    u32x4_t kr[U], vr[U];
+  // Two register buffers: the loads of the next RPW*U rows are in flight while the current ones are consumed.
+  u32x4_t krA[U], vrA[U], krB[U], vrB[U];
+  auto load = [&](u32x4_t* kr, u32x4_t* vr, int jb) {
 #pragma unroll
     for (int u = 0; u < U; ++u) {
       const int r = min(jb + u * RPW + grp, j1 - 1);      // clamp: stays inside the request's valid rows
       kr[u] = __builtin_nontemporal_load((const u32x4_t*)(kb + (size_t)r * D * EB));
       vr[u] = __builtin_nontemporal_load((const u32x4_t*)(vb + (size_t)r * D * EB));
     }
+  };
+  auto consume = [&](const u32x4_t* kr, const u32x4_t* vr, int jb) {
     float s[U];
     float tmax = -INFINITY;
 #pragma unroll
@@ -88,6 +90,16 @@ __global__ __launch_bounds__(256) void attn_partial_kernel(const void* __restric
       for (int e = 0; e < EPL; ++e) o[e] = fmaf(p, vf[e], o[e]);
     }
     m = mn;
+  };
+  constexpr int STEP = RPW * U;
+  load(krA, vrA, j0);
+  for (int jb = j0; jb < j1; jb += 2 * STEP) {
+    if (jb + STEP < j1) load(krB, vrB, jb + STEP);         // wave-uniform
+    consume(krA, vrA, jb);
+    if (jb + STEP < j1) {
+      if (jb + 2 * STEP < j1) load(krA, vrA, jb + 2 * STEP);
+      consume(krB, vrB, jb + STEP);
+    }
   }
   // merge the RPW lane groups (lanes with equal li): butterfly over the group index bits
   if constexpr (RPW > 1) {
@@ -461,8 +473,8 @@ static void launch_attn(const void* q, const void* kc, const void* vc, const Att
                         void* out, hipStream_t st, hipEvent_t ev0, hipEvent_t ev1) {
   const float scale = 1.0f / sqrtf((float)D);
   if (ev0) (void)hipEventRecord(ev0, st);
-  attn_partial_kernel<DT, D, 4><<<dim3(w.n_items, nh / 4), 256, 0, st>>>(q, kc, vc, w.items, w.row_slot, w.row_len, nh, Smax,
-                                                                       w.chunk, scale, w.pml, w.po);
+  attn_partial_kernel<DT, D, 4><<<dim3(w.n_items, nh / 4), 256, 0, st>>>(q, kc, vc, w.items, nh, Smax, w.chunk, scale,
+                                                                       w.pml, w.po);
   if (ev1) (void)hipEventRecord(ev1, st);
   attn_merge_kernel<DT, D><<<dim3(M, nh), D, 0, st>>>(w.pml, w.po, w.row_item0, w.row_nchunk, nh, out);
 }
