@@ -22,6 +22,7 @@
 //     y^T, so a lane holds 4 consecutive output columns of one row and stores them as one 16-byte write.
 // fp32 models (tiny configurations only) use a plain FMA kernel on the untiled matrix.
 #include <algorithm>
+#include <type_traits>
 
 #include "flover_dev.h"
 #include "flover_kernels.h"
@@ -81,35 +82,43 @@ __global__ __launch_bounds__(256) void gemm16_direct_kernel(const uint16_t* __re
   const uint16_t* xp = x + (size_t)(m0 + (lane & 15)) * K + (lane >> 4) * 8;     // + i*16*K + kb*32
 
   u32x4_t bq[PFW][NT], aq[PFA][MT];
+  static_assert(PFW == PFA, "both rings turn together");
 #pragma unroll
-  for (int j = 0; j < PFW; ++j) {
+  for (int j = 0; j < PFW; ++j) {      // same order as the refills in the loop: the wait counts of the first turn match
     const int kk = min(kb0 + j, kb1 - 1);
 #pragma unroll
     for (int t = 0; t < NT; ++t) bq[j][t] = __builtin_nontemporal_load(wp + ((size_t)kk * NT + t) * 64);
-  }
-#pragma unroll
-  for (int j = 0; j < PFA; ++j) {
-    const int kk = min(kb0 + j, kb1 - 1);
 #pragma unroll
     for (int i = 0; i < MT; ++i) aq[j][i] = *(const u32x4_t*)(xp + (size_t)i * 16 * K + kk * 32);
+    __builtin_amdgcn_sched_barrier(0);
   }
-  for (int kb = kb0; kb < kb1; kb += PFW) {
+  // One turn of the ring.  The steady-state turns (TAIL = false: all PFW k-blocks exist) are free of branches, so the
+  // compiler's wait counts for the in-order memory counter stay exact; sched_barrier keeps each refill where it is
+  // written, right after the k-block that freed the slot.
+  auto turn = [&](auto tail_, int kb) {
+    constexpr bool tail = decltype(tail_)::value;
 #pragma unroll
     for (int j = 0; j < PFW; ++j) {
-      if (kb + j < kb1) {
+      if (!tail || kb + j < kb1) {
 #pragma unroll
         for (int i = 0; i < MT; ++i)
 #pragma unroll
           for (int t = 0; t < NT; ++t) acc[i][t] = mfma16<DT>(bq[j][t], aq[j % PFA][i], acc[i][t]);
       }
-      const int kw = min(kb + j + PFW, kb1 - 1);      // tail re-reads the last block (in bounds, unused)
+      if (!tail) {
+        const int kw = min(kb + j + PFW, kb1 - 1);    // the last turns re-read the last block (in bounds, unused)
 #pragma unroll
-      for (int t = 0; t < NT; ++t) bq[j][t] = __builtin_nontemporal_load(wp + ((size_t)kw * NT + t) * 64);
-      const int ka = min(kb + j + PFA, kb1 - 1);
+        for (int t = 0; t < NT; ++t) bq[j][t] = __builtin_nontemporal_load(wp + ((size_t)kw * NT + t) * 64);
+        const int ka = min(kb + j + PFA, kb1 - 1);
 #pragma unroll
-      for (int i = 0; i < MT; ++i) aq[j % PFA][i] = *(const u32x4_t*)(xp + (size_t)i * 16 * K + ka * 32);
+        for (int i = 0; i < MT; ++i) aq[j % PFA][i] = *(const u32x4_t*)(xp + (size_t)i * 16 * K + ka * 32);
+        __builtin_amdgcn_sched_barrier(0);
+      }
     }
-  }
+  };
+  int kb = kb0;
+  for (; kb + PFW <= kb1; kb += PFW) turn(std::false_type{}, kb);
+  if (kb < kb1) turn(std::true_type{}, kb);
   float* out = part + (size_t)s * slice_stride;
 #pragma unroll
   for (int i = 0; i < MT; ++i)
@@ -180,43 +189,56 @@ __global__ __launch_bounds__(64 * 4 * (NT / NTW)) void gemm16_lds_kernel(const u
       areg[j] = *(const u32x4_t*)(xp + (size_t)i * 16 * K + kk * 32);
     }
   };
-  auto store_a = [&](int buf) {
+  auto store_a = [&](int buf) {      // surplus waves store the last fragment once more (same data, no branch)
 #pragma unroll
-    for (int j = 0; j < FPW; ++j)
-      if (wave + NW * j < KC * MT) lds[buf][(wave + NW * j) * 64 + lane] = areg[j];
+    for (int j = 0; j < FPW; ++j) lds[buf][min(wave + NW * j, KC * MT - 1) * 64 + lane] = areg[j];
   };
   load_a(0);
   store_a(0);
   __syncthreads();
-  for (int c0 = 0; c0 < nchunks; c0 += CPR) {
+  // One chunk: stage the next x tile, multiply this one, refill the W ring.  CC (position in the ring turn) is a
+  // compile-time value; TAIL = the chunk may be the last one or short.  The steady-state loop below only runs
+  // chunks that are full and have a successor, so its body is free of branches: the compiler's wait counts for the
+  // in-order memory counter stay exact there (any branch in the body makes them collapse to "wait for all").
+  auto chunk = [&](auto cc_, auto tail_, int c) {
+    constexpr int cc = decltype(cc_)::value;
+    constexpr bool tail = decltype(tail_)::value;
+    const bool more = !tail || c + 1 < nchunks;
+    if (more) load_a(c + 1);
+    __builtin_amdgcn_sched_barrier(0);        // keep these loads ahead of the chunk's MFMAs (the scheduler sinks them to their use)
+    const u32x4_t* la = lds[c & 1];
 #pragma unroll
-    for (int cc = 0; cc < CPR; ++cc) {
-      const int c = c0 + cc;
-      if (c < nchunks) {                          // uniform over the block
-        const bool more = c + 1 < nchunks;
-        if (more) load_a(c + 1);
-        const u32x4_t* la = lds[c & 1];
+    for (int kc = 0; kc < KC; ++kc) {
+      const int kb = kb0 + c * KC + kc;
+      if (!tail || kb < kb1) {
+        u32x4_t af[MT];
 #pragma unroll
-        for (int kc = 0; kc < KC; ++kc) {
-          const int kb = kb0 + c * KC + kc;
-          if (kb < kb1) {
-            u32x4_t af[MT];
+        for (int i = 0; i < MT; ++i) af[i] = la[(kc * MT + i) * 64 + lane];
 #pragma unroll
-            for (int i = 0; i < MT; ++i) af[i] = la[(kc * MT + i) * 64 + lane];
+        for (int i = 0; i < MT; ++i)
 #pragma unroll
-            for (int i = 0; i < MT; ++i)
-#pragma unroll
-              for (int t = 0; t < NTW; ++t) acc[i][t] = mfma16<DT>(bq[cc * KC + kc][t], af[i], acc[i][t]);
-          }
-          const int kk = min(kb + PF, kb1 - 1);
-#pragma unroll
-          for (int t = 0; t < NTW; ++t)
-            bq[cc * KC + kc][t] = __builtin_nontemporal_load(wp + ((size_t)kk * NT + t) * 64);
-        }
-        if (more) store_a((c + 1) & 1);
-        __syncthreads();
+          for (int t = 0; t < NTW; ++t) acc[i][t] = mfma16<DT>(bq[cc * KC + kc][t], af[i], acc[i][t]);
       }
+      const int kk = min(kb + PF, kb1 - 1);
+#pragma unroll
+      for (int t = 0; t < NTW; ++t) bq[cc * KC + kc][t] = __builtin_nontemporal_load(wp + ((size_t)kk * NT + t) * 64);
+      __builtin_amdgcn_sched_barrier(0);      // refill right after the k-block that freed the slot
     }
+    if (more) store_a((c + 1) & 1);
+    __syncthreads();
+  };
+  int c = 0;
+  for (; c + CPR < nchunks; c += CPR) {
+    if constexpr (CPR >= 1) chunk(std::integral_constant<int, 0>{}, std::false_type{}, c);
+    if constexpr (CPR >= 2) chunk(std::integral_constant<int, 1>{}, std::false_type{}, c + 1);
+    if constexpr (CPR >= 3) chunk(std::integral_constant<int, 2>{}, std::false_type{}, c + 2);
+    if constexpr (CPR >= 4) chunk(std::integral_constant<int, 3>{}, std::false_type{}, c + 3);
+  }
+  for (; c < nchunks; c += CPR) {               // the last turn of the ring
+    if constexpr (CPR >= 1) if (c < nchunks) chunk(std::integral_constant<int, 0>{}, std::true_type{}, c);
+    if constexpr (CPR >= 2) if (c + 1 < nchunks) chunk(std::integral_constant<int, 1>{}, std::true_type{}, c + 1);
+    if constexpr (CPR >= 3) if (c + 2 < nchunks) chunk(std::integral_constant<int, 2>{}, std::true_type{}, c + 2);
+    if constexpr (CPR >= 4) if (c + 3 < nchunks) chunk(std::integral_constant<int, 3>{}, std::true_type{}, c + 3);
   }
   if (g >= ngroups) return;
   float* out = part + (size_t)s * slice_stride;
@@ -284,40 +306,48 @@ __global__ __launch_bounds__(512) void gemm16_rows_kernel(const uint16_t* __rest
   };
   auto store_a = [&](int buf) {
 #pragma unroll
-    for (int j = 0; j < FPW; ++j)
-      if (wave + NW * j < KC * MTB) lds[buf][(wave + NW * j) * 64 + lane] = areg[j];
+    for (int j = 0; j < FPW; ++j) lds[buf][min(wave + NW * j, KC * MTB - 1) * 64 + lane] = areg[j];
   };
   load_a(0);
   store_a(0);
   __syncthreads();
-  for (int c0 = 0; c0 < nchunks; c0 += CPR) {
+  // Chunks as in the kernel above: branch-free steady state, refills pinned where they are written.
+  auto chunk = [&](auto cc_, auto tail_, int c) {
+    constexpr int cc = decltype(cc_)::value;
+    constexpr bool tail = decltype(tail_)::value;
+    const bool more = !tail || c + 1 < nchunks;
+    if (more) load_a(c + 1);
+    __builtin_amdgcn_sched_barrier(0);
+    const u32x4_t* la = lds[c & 1];
 #pragma unroll
-    for (int cc = 0; cc < CPR; ++cc) {
-      const int c = c0 + cc;
-      if (c < nchunks) {
-        const bool more = c + 1 < nchunks;
-        if (more) load_a(c + 1);
-        const u32x4_t* la = lds[c & 1];
+    for (int kc = 0; kc < KC; ++kc) {
+      const int kb = kb0 + c * KC + kc;
+      if (!tail || kb < kb1) {
 #pragma unroll
-        for (int kc = 0; kc < KC; ++kc) {
-          const int kb = kb0 + c * KC + kc;
-          if (kb < kb1) {
+        for (int i = 0; i < MTW; ++i)
+          if (i < live_tiles) {               // wave-uniform: row tiles past M are skipped
+            const u32x4_t af = la[(kc * MTB + half * MTW + i) * 64 + lane];
 #pragma unroll
-            for (int i = 0; i < MTW; ++i)
-              if (i < live_tiles) {               // wave-uniform: row tiles past M are skipped
-                const u32x4_t af = la[(kc * MTB + half * MTW + i) * 64 + lane];
-#pragma unroll
-                for (int t = 0; t < NT; ++t) acc[i][t] = mfma16<DT>(bq[cc * KC + kc][t], af, acc[i][t]);
-              }
+            for (int t = 0; t < NT; ++t) acc[i][t] = mfma16<DT>(bq[cc * KC + kc][t], af, acc[i][t]);
           }
-          const int kk = min(kb + PF, kb1 - 1);
-#pragma unroll
-          for (int t = 0; t < NT; ++t) bq[cc * KC + kc][t] = wp[((size_t)kk * NT + t) * 64];
-        }
-        if (more) store_a((c + 1) & 1);
-        __syncthreads();
       }
+      const int kk = min(kb + PF, kb1 - 1);
+#pragma unroll
+      for (int t = 0; t < NT; ++t) bq[cc * KC + kc][t] = wp[((size_t)kk * NT + t) * 64];
+      __builtin_amdgcn_sched_barrier(0);
     }
+    if (more) store_a((c + 1) & 1);
+    __syncthreads();
+  };
+  static_assert(CPR <= 2, "ring turns of one or two chunks");
+  int c = 0;
+  for (; c + CPR < nchunks; c += CPR) {
+    chunk(std::integral_constant<int, 0>{}, std::false_type{}, c);
+    if constexpr (CPR >= 2) chunk(std::integral_constant<int, 1>{}, std::false_type{}, c + 1);
+  }
+  for (; c < nchunks; c += CPR) {
+    chunk(std::integral_constant<int, 0>{}, std::true_type{}, c);
+    if constexpr (CPR >= 2) if (c + 1 < nchunks) chunk(std::integral_constant<int, 1>{}, std::true_type{}, c + 1);
   }
   if (g >= ngroups) return;
   float* out = part + (size_t)s * slice_stride;
