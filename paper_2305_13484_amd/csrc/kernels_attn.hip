@@ -93,13 +93,23 @@ __global__ __launch_bounds__(256) void attn_partial_kernel(const void* __restric
   };
   constexpr int STEP = RPW * U;
   load(krA, vrA, j0);
-  for (int jb = j0; jb < j1; jb += 2 * STEP) {
-    if (jb + STEP < j1) load(krB, vrB, jb + STEP);         // wave-uniform
+  int jb = j0;
+  // Steady state without branches (the compiler's wait counts for the in-order memory counter collapse to "wait for
+  // everything" around a branch, which would make consuming one buffer wait for the other's loads too); the loads
+  // past the chunk re-read its last row.
+  for (; jb + 2 * STEP <= j1; jb += 2 * STEP) {
+    load(krB, vrB, jb + STEP);
+    __builtin_amdgcn_sched_barrier(0);
     consume(krA, vrA, jb);
-    if (jb + STEP < j1) {
-      if (jb + 2 * STEP < j1) load(krA, vrA, jb + 2 * STEP);
-      consume(krB, vrB, jb + STEP);
-    }
+    load(krA, vrA, jb + 2 * STEP);
+    __builtin_amdgcn_sched_barrier(0);
+    consume(krB, vrB, jb + STEP);
+  }
+  if (jb < j1) {                                           // one or two steps left (wave-uniform)
+    const bool two = jb + STEP < j1;
+    if (two) load(krB, vrB, jb + STEP);
+    consume(krA, vrA, jb);
+    if (two) consume(krB, vrB, jb + STEP);
   }
   // merge the RPW lane groups (lanes with equal li): butterfly over the group index bits
   if constexpr (RPW > 1) {
