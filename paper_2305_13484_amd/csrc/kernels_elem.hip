@@ -9,19 +9,21 @@
 
 namespace flk {
 
-// Sum of S split-K slices at 4 consecutive elements, added in slice order.  Loads of 4 slices are issued together so a
-// thread keeps several 16-byte requests in flight; the additions stay sequential (s = 0, 1, 2, ...).
+// Sum of S split-K slices at 4 consecutive elements, added in slice order (s = 0, 1, 2, ...).  The loads of up to 16
+// slices (no plan has more) are all issued before the first addition, so a thread pays the memory latency once; S is
+// uniform over the grid, so the predicates are scalar branches.
 __device__ __forceinline__ f32x4_t ld4(const float* p) { return *(const f32x4_t*)p; }
 __device__ __forceinline__ f32x4_t psum4(const float* __restrict__ part, int S, size_t stride, size_t idx) {
   const float* p = part + idx;
-  f32x4_t v = ld4(p);
-  int s = 1;
-  for (; s + 3 < S; s += 4) {
-    const f32x4_t a = ld4(p + (size_t)s * stride), b = ld4(p + (size_t)(s + 1) * stride),
-                  c = ld4(p + (size_t)(s + 2) * stride), d = ld4(p + (size_t)(s + 3) * stride);
-    v += a; v += b; v += c; v += d;
-  }
-  for (; s < S; ++s) v += ld4(p + (size_t)s * stride);
+  f32x4_t pv[16];
+#pragma unroll
+  for (int j = 0; j < 16; ++j)
+    if (j < S) pv[j] = ld4(p + (size_t)j * stride);
+  f32x4_t v = pv[0];
+#pragma unroll
+  for (int j = 1; j < 16; ++j)
+    if (j < S) v += pv[j];
+  for (int s = 16; s < S; ++s) v += ld4(p + (size_t)s * stride);
   return v;
 }
 template <int DT> __device__ __forceinline__ f32x4_t ldv4(const void* p, size_t i) {   // 4 consecutive dtype elements
@@ -74,7 +76,7 @@ __global__ __launch_bounds__(256) void embed_kernel(const void* __restrict__ wte
 // x[m] += sum_s part[s][m] + bias   (skipped when part == nullptr), then
 // h[m] = LayerNorm(x[m]) * g + b   (RMS == 0)   or   x[m] / rms(x[m]) * g   (RMS == 1), rounded to dtype.
 // grid = M, block = 1024, 4 consecutive elements per thread and pass (2 passes cover H <= 8192); H % 4 == 0.
-// part rows have length ldp.  All slice loads of a pass are issued before the first addition (S <= 8 at a time).
+// part rows have length ldp.  All slice loads of a pass are issued before the first addition.
 template <int DT, int RMS>
 __global__ __launch_bounds__(1024) void add_norm_kernel(float* __restrict__ x, const float* __restrict__ part, int S,
                                                         size_t stride, int ldp, const void* __restrict__ bias,
@@ -96,16 +98,7 @@ __global__ __launch_bounds__(1024) void add_norm_kernel(float* __restrict__ x, c
       if (!RMS) bv[c] = ldv4<DT>(b, i);
       f32x4_t t = *(const f32x4_t*)(x + (size_t)m * H + i);
       if (part) {
-        const float* p = part + (size_t)m * ldp + i;
-        f32x4_t a = ld4(p);
-        for (int s0 = 1; s0 < S; s0 += 8) {
-          f32x4_t pv[8];
-#pragma unroll
-          for (int j = 0; j < 8; ++j) pv[j] = ld4(p + (size_t)min(s0 + j, S - 1) * stride);
-#pragma unroll
-          for (int j = 0; j < 8; ++j)
-            if (s0 + j < S) a += pv[j];
-        }
+        f32x4_t a = psum4(part, S, stride, (size_t)m * ldp + i);
         if (bias) a += ldv4<DT>(bias, i);
         t += a;
         *(f32x4_t*)(x + (size_t)m * H + i) = t;
