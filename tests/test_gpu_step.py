@@ -562,3 +562,21 @@ def test_layer_by_layer_weight_hand_over_equals_the_stacked_init(name):
         srv.set_layer_weights(cfg.L, {k: w[k][0].contiguous() for k in PER_LAYER if k in w})   # out of range
     srv.close()
     _same_results(ref, (toks, logits), reqs)
+
+
+@pytest.mark.parametrize("async_pre", [False, True])
+def test_pipelined_stress_with_a_waiting_queue(async_pre):
+    """Many requests through few slots with three iterations outstanding: requests wait for slots, are admitted by later
+    submissions, evictions and shuffles happen while iterations are in flight; every request's tokens equal the
+    synchronous run's."""
+    cfg = dataclasses.replace(synth.tiny_llama(synth.DT_BF16), C=4, S=96)
+    w = to_device(synth.make_weights(cfg, 61))
+    reqs = synth.stream_small(62, cfg.V, n=40, arrive_hi=50, p_lo=1, p_hi=40, g_lo=1, g_hi=24)
+    ref = gpu_run_stream(cfg, w, reqs, want_logits=False)
+    st = {}
+    got = gpu_run_stream_pipelined(cfg, w, reqs, depth=3, async_preprocess=async_pre, want_logits=False, stats=st)
+    print("pipelined stress", st)
+    for r in reqs:
+        assert ref[0][r.req_id] == got[0][r.req_id], r.req_id
+        assert len(got[0][r.req_id]) == r.gen_len
+    assert st["moves"] > 0 and st["max_outstanding"] == 3
