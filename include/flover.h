@@ -108,8 +108,8 @@ int32_t flover_set_layer_weights(flover_ctx* ctx, int32_t layer, const flover_we
 
 int32_t flover_destroy(flover_ctx* ctx);
 
-/* Text of the last error on ctx (ctx == NULL: of the last failed flover_init / query / kernel-level call).
- * Owned by the library, valid until the next failing call. */
+/* Text of the last error on ctx (ctx == NULL: of the calling thread's last failed flover_init / query /
+ * kernel-level call).  Owned by the library, valid until the next failing call. */
 const char* flover_last_error(const flover_ctx* ctx);
 
 /* Body of Algorithm 1 for one request (Section V-B): assign the slot adjacent to the live region

@@ -21,7 +21,7 @@
 
 namespace {
 
-std::string g_err;   // last error of calls that have no context
+thread_local std::string g_err;   // last error of calls that have no context, per calling thread
 
 struct Slot {
   int state = FLOVER_SLOT_EMPTY;
@@ -442,7 +442,10 @@ int preprocess(flover_ctx* c, int slot, const Waiting& r) {
     rows.resize(n);
     for (int i = 0; i < n; ++i) rows[i] = Row{slot, r.prompt[p0 + i], p0 + i};
     int rc = run_rows(c, ln, rows.data(), n, false, nullptr, true, !async);
-    if (rc != FLOVER_OK) return rc;
+    if (rc != FLOVER_OK) {
+      s.state = FLOVER_SLOT_DEAD;   // never joins an iteration; the next flover_reorder_evict frees the slot
+      return rc;
+    }
   }
   if (async && P > 1) {
     HIPCHK(c, hipEventRecord(c->prep_ev[slot], ln.st));
@@ -748,6 +751,7 @@ int32_t flover_add_request_cached(flover_ctx* c, uint64_t req_id, int32_t contex
   s.len = context_len;
   s.next_token = next_token;
   s.pending = false;
+  s.ev = -1;
   s.dev_row = -1;
   if (out_slot) *out_slot = slot;
   return FLOVER_OK;
@@ -993,8 +997,11 @@ int32_t flover_reorder_evict(flover_ctx* c, flover_reorder_out* out) {
         if (out->move_src) out->move_src[i] = a;
         if (out->move_dst) out->move_dst[i] = b;
         const int len = c->slots[a].len;
-        if (c->slots[a].pending)   // its context cache is still being written: the copy waits for it
-          HIPCHK(c, hipStreamWaitEvent(c->st, c->prep_ev[c->slots[a].ev], 0));
+        if (c->slots[a].pending) {   // its context cache is still being written: the copy, and with it every
+          HIPCHK(c, hipStreamWaitEvent(c->st, c->prep_ev[c->slots[a].ev], 0));   // later iteration, waits for it
+          c->slots[a].pending = false;
+          c->slots[a].ev = -1;
+        }
         bytes += 2LL * len * 2 * f.n_layer * f.hidden * esize(f.dtype);
         if (len > 0) {
           const int seg_bytes = len * row_bytes;
@@ -1016,7 +1023,6 @@ int32_t flover_reorder_evict(flover_ctx* c, flover_reorder_out* out) {
         if (pi >= 0) (void)hipEventRecord(c->ev[2 * pi + 1], c->st);
         if (!piped) {
           HIPCHK(c, hipStreamSynchronize(c->st));   // following iterations wait until memory is in order (Section V-D)
-          for (int i = 0; i < n_moves; ++i) c->slots[holes[i]].pending = false;   // the copy waited for their caches
           prof_collect(c);
         }
       }
