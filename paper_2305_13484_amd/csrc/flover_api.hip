@@ -279,11 +279,11 @@ void prof_collect(flover_ctx* c, size_t upto = (size_t)-1) {
   }
 }
 hipError_t timed_gemm(flover_ctx* c, Lane& ln, int kind, const void* x, const void* w, int n, const flk::GemmPlan& p,
-                      size_t ss) {
+                      size_t ss, int mtt) {
   const int64_t bytes = (int64_t)flk::gemm_tiled_bytes(c->cfg.dtype, p.N, p.K);
   const int pi = (&ln == &c->step_lane && c->prof_now) ? prof_begin(c, kind, bytes) : -1;
   if (pi >= 0) (void)hipEventRecord(c->ev[2 * pi], ln.st);
-  hipError_t e = flk::gemm(c->cfg.dtype, x, w, n, p, ln.part, ss, ln.st);
+  hipError_t e = flk::gemm(c->cfg.dtype, x, w, n, p, ln.part, ss, mtt, ln.st);
   if (pi >= 0) (void)hipEventRecord(c->ev[2 * pi + 1], ln.st);
   return e;
 }
@@ -358,6 +358,10 @@ int run_rows(flover_ctx* c, Lane& ln, const Row* rows, int n, bool want_tokens, 
   flk::AttnWork aw{(const int4*)(ds + 6 * R), d_slot, d_len, d_item0, d_nchunk, ln.pml, ln.po, n_items, flk::attn_chunk()};
   aw.blocks = (const int4*)(ds + 6 * R + 4 * n_items);
   aw.n_blocks = n_blocks;
+  // what feeds a GEMM (norm output, attention output, MLP activation) is written in the order the GEMM's MFMA reads
+  // it: 16-bit models only, tiles of 16 rows, mtt of them per k-block
+  const int mtt = f.dtype == FLOVER_F32 ? 0 : (n + 15) / 16;
+  aw.out_mtt = mtt;
   const bool prof = &ln == &c->step_lane && (wait || want_tokens);
   if (&ln == &c->step_lane) c->prof_now = prof;
 
@@ -377,8 +381,8 @@ int run_rows(flover_ctx* c, Lane& ln, const Row* rows, int n, bool want_tokens, 
     const bool first = l == 0;
     HIPCHK(c, flk::add_norm(f.dtype, !gpt, ln.x, first ? nullptr : ln.part, p_2.S, ss_h, p_2.ldc,
                             first ? nullptr : c->lw[l - 1].b2,
-                            w.ln1_g, w.ln1_b, ln.h, n, H, f.norm_eps, st));
-    HIPCHK(c, timed_gemm(c, ln, FLOVER_PROF_GEMM_QKV, ln.h, w.wqkv, n, p_qkv, ss_qkv));
+                            w.ln1_g, w.ln1_b, ln.h, n, H, f.norm_eps, mtt, st));
+    HIPCHK(c, timed_gemm(c, ln, FLOVER_PROF_GEMM_QKV, ln.h, w.wqkv, n, p_qkv, ss_qkv, mtt));
     char* kl = c->kv + (size_t)(2 * l) * c->plane_bytes;
     char* vl = kl + c->plane_bytes;
     HIPCHK(c, flk::qkv_post(f.dtype, ln.part, p_qkv.S, ss_qkv, p_qkv.ldc, w.bqkv, c->rope_cs, d_slot, d_pos, ln.q, kl, vl, n, H, nh,
@@ -392,17 +396,17 @@ int run_rows(flover_ctx* c, Lane& ln, const Row* rows, int n, bool want_tokens, 
       HIPCHK(c, flk::decode_attention(f.dtype, d, ln.q, kl, vl, aw, n, nh, f.max_seq, ln.att, st,
                                       pi >= 0 ? c->ev[2 * pi] : nullptr, pi >= 0 ? c->ev[2 * pi + 1] : nullptr));
     }
-    HIPCHK(c, timed_gemm(c, ln, FLOVER_PROF_GEMM_OUT, ln.att, w.wo, n, p_o, ss_h));
-    HIPCHK(c, flk::add_norm(f.dtype, !gpt, ln.x, ln.part, p_o.S, ss_h, p_o.ldc, w.bo, w.ln2_g, w.ln2_b, ln.h, n, H, f.norm_eps, st));
-    HIPCHK(c, timed_gemm(c, ln, FLOVER_PROF_GEMM_FF1, ln.h, w.w1, n, p_1, ss_1));
-    HIPCHK(c, flk::activation(f.dtype, !gpt, ln.part, p_1.S, ss_1, p_1.ldc, w.b1, ln.act, n, F, st));
-    HIPCHK(c, timed_gemm(c, ln, FLOVER_PROF_GEMM_FF2, ln.act, w.w2, n, p_2, ss_h));
+    HIPCHK(c, timed_gemm(c, ln, FLOVER_PROF_GEMM_OUT, ln.att, w.wo, n, p_o, ss_h, mtt));
+    HIPCHK(c, flk::add_norm(f.dtype, !gpt, ln.x, ln.part, p_o.S, ss_h, p_o.ldc, w.bo, w.ln2_g, w.ln2_b, ln.h, n, H, f.norm_eps, mtt, st));
+    HIPCHK(c, timed_gemm(c, ln, FLOVER_PROF_GEMM_FF1, ln.h, w.w1, n, p_1, ss_1, mtt));
+    HIPCHK(c, flk::activation(f.dtype, !gpt, ln.part, p_1.S, ss_1, p_1.ldc, w.b1, ln.act, n, F, mtt, st));
+    HIPCHK(c, timed_gemm(c, ln, FLOVER_PROF_GEMM_FF2, ln.act, w.w2, n, p_2, ss_h, mtt));
     launches += 10;
   }
   if (want_tokens) {
     HIPCHK(c, flk::add_norm(f.dtype, !gpt, ln.x, ln.part, c->p_2.S, ss_h, c->p_2.ldc, c->lw[L - 1].b2, c->lnf_g, c->lnf_b, ln.h, n, H,
-                            f.norm_eps, st));
-    HIPCHK(c, timed_gemm(c, ln, FLOVER_PROF_GEMM_LM, ln.h, c->wlm, n, c->p_lm, ss_v));
+                            f.norm_eps, mtt, st));
+    HIPCHK(c, timed_gemm(c, ln, FLOVER_PROF_GEMM_LM, ln.h, c->wlm, n, c->p_lm, ss_v, mtt));
     HIPCHK(c, flk::logits_argmax(ln.part, c->p_lm.S, ss_v, c->p_lm.ldc, logits_out, ln.tok_out, n, V, st));
     const int ti = ln.tok_next;       // at most kStageRing - 1 iterations are outstanding, so this entry is free
     ln.tok_next = (ln.tok_next + 1) % kStageRing;
@@ -1291,7 +1295,7 @@ extern "C" int32_t flover_k_gemm(int32_t dtype, const void* x, const void* w_til
   const size_t stride = (size_t)M * p.ldc;
   if ((size_t)p.S * stride * 4 > workspace_bytes) return fail(nullptr, FLOVER_E_NOMEM, "gemm workspace too small");
   hipStream_t st = (hipStream_t)stream;
-  HIPCHK(nullptr, flk::gemm(dtype, x, w_tiled, M, p, (float*)workspace, stride, st));
+  HIPCHK(nullptr, flk::gemm(dtype, x, w_tiled, M, p, (float*)workspace, stride, 0, st));
   if (y) {
     const size_t total = (size_t)M * N;
     flk::slice_sum_kernel<<<(unsigned)((total + 255) / 256), 256, 0, st>>>((const float*)workspace, p.S, stride, p.ldc, y, M, N);

@@ -64,6 +64,17 @@ template <int DT> __device__ __forceinline__ void unpack16(const u32x4_t& r, flo
   }
 }
 
+// ---- layout of the 16-bit GEMM inputs (norm output, attention output, MLP activation) inside a pass
+// "Fragment order": x[M][K] is kept as tiles of 16 rows x 32 k in the order the MFMA reads its row operand -- lane l
+// of a tile holds x[16*mt + l%16][32*kb + 8*(l/16) .. +7] (16 bytes) -- tiles ordered [k-block][row tile], so one
+// fragment load of a wave is 1 KiB contiguous and the row tiles of a k-block follow each other.  mtt = row tiles of the
+// pass (ceil(M/16)); mtt == 0 means plain row-major with leading dimension ld.  k % 4 == 0 keeps 4 consecutive
+// elements contiguous in both layouts.
+__device__ __forceinline__ size_t xrow_index(int m, int k, int ld, int mtt) {
+  if (mtt == 0) return (size_t)m * ld + k;
+  return ((size_t)(k >> 5) * mtt + (m >> 4)) * 512 + ((((k & 31) >> 3) << 4) + (m & 15)) * 8 + (k & 7);
+}
+
 // ---- cross-lane: DPP within a row of 16 lanes, LDS-permute beyond.  Every step is a fixed butterfly,
 // so a reduction's result does not depend on anything but the values reduced.
 template <int CTRL> __device__ __forceinline__ float dpp_f(float v) {

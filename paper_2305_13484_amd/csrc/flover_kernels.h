@@ -27,8 +27,10 @@ GemmPlan context_plan(const GemmPlan& p, int dtype, int M);
 hipError_t retile(int dtype, const void* W, int N, int K, void* tiled, int n_off, int NT, hipStream_t st);
 hipError_t zero_fill(void* p, size_t bytes, hipStream_t st);
 // part[s][m][p.ldc] (slice stride in floats) = x[M][K] . W^T over slice s of K.
+// xmtt == 0: x is row-major [gemm_rows_read(M)][K]; xmtt = ceil(M/16) (16-bit dtypes only): x is in fragment order
+// (tiles of 16 rows x 32 k, [k-block][row tile], see xrow_index) and the buffer holds K/32 * gemm_rows_read(M)/16 tiles.
 hipError_t gemm(int dtype, const void* x, const void* w_tiled, int M, const GemmPlan& p, float* part,
-                size_t slice_stride, hipStream_t st);
+                size_t slice_stride, int xmtt, hipStream_t st);
 // rows of x that gemm() may read for M live rows
 inline int gemm_rows_read(int M) {
   return M <= 16 ? 16 : M <= 32 ? 32 : M <= 64 ? 64 : M <= 128 ? 128 : (M + 255) / 256 * 256;
@@ -39,13 +41,15 @@ inline int gemm_rows_read(int M) {
 hipError_t embed(int dtype, const void* wte, const void* wpe, const int* tok, const int* pos, const int* tok_prev,
                  float* x, int M, int H, hipStream_t st);
 // `part` is the preceding GEMM's split-K output: S slices, `stride` floats apart, rows of `ldp` floats (ldp % 4 == 0).
+// h (and the outputs of activation and of the attention calls below) feed a GEMM: with mtt = ceil(M/16) they are
+// written in fragment order (16-bit dtypes; see gemm), with mtt == 0 row-major.
 hipError_t add_norm(int dtype, bool rms, float* x, const float* part, int S, size_t stride, int ldp, const void* bias,
-                    const void* g, const void* b, void* h, int M, int H, float eps, hipStream_t st);
+                    const void* g, const void* b, void* h, int M, int H, float eps, int mtt, hipStream_t st);
 hipError_t qkv_post(int dtype, const float* part, int S, size_t stride, int ldp, const void* bias, const float* rope_cs,
                     const int* slot, const int* pos, void* q, void* kcache, void* vcache, int M, int H, int nh, int d,
                     int Smax, hipStream_t st);
 hipError_t activation(int dtype, bool swiglu, const float* part, int S, size_t stride, int ldp, const void* bias, void* a,
-                      int M, int F, hipStream_t st);
+                      int M, int F, int mtt, hipStream_t st);
 hipError_t logits_argmax(const float* part, int S, size_t stride, int ldp, float* logits, int* tok, int M, int V,
                          hipStream_t st);
 
@@ -62,6 +66,7 @@ struct AttnWork {          // all device pointers
   int chunk;
   const int4* blocks = nullptr;   // pre-processing passes: (first row, rows <= prefill_rows_per_block, chunk, -)
   int n_blocks = 0;
+  int out_mtt = 0;                // layout of the attention output: 0 row-major, else fragment order (see add_norm)
 };
 constexpr int kPrefillQB = 8;     // query rows one wave serves in a pre-processing pass (fp32 models)
 int prefill_rows_per_block(int dtype);   // rows per entry of AttnWork::blocks: 8 for fp32, 32 for the 16-bit (MFMA) kernel

@@ -141,10 +141,11 @@ __global__ __launch_bounds__(256) void attn_partial_kernel(const void* __restric
 }
 
 // grid = (M, n_head), block = D: merges a row's chunks in chunk order, normalises, rounds to dtype.
+// out is [M][nh * D] row-major (mtt == 0) or in the GEMM's fragment order with mtt row tiles.
 template <int DT, int D>
 __global__ void attn_merge_kernel(const float* __restrict__ pml, const float* __restrict__ po,
                                   const int* __restrict__ row_item0, const int* __restrict__ row_nchunk, int nh,
-                                  void* __restrict__ out) {
+                                  void* __restrict__ out, int mtt) {
   float red_m = 0.f;
   const int row = blockIdx.x, hd = blockIdx.y, i = threadIdx.x;
   const int it0 = row_item0[row], nc = row_nchunk[row];
@@ -174,7 +175,7 @@ __global__ void attn_merge_kernel(const float* __restrict__ pml, const float* __
         o += w * oc[j];
       }
   }
-  st<DT>(out, ((size_t)row * nh + hd) * D + i, o / l);
+  st<DT>(out, xrow_index(row, hd * D + i, nh * D, mtt), o / l);
 }
 
 // ---------------------------------------------------------------- pre-processing variant (context decoder)
@@ -486,7 +487,7 @@ static void launch_attn(const void* q, const void* kc, const void* vc, const Att
   attn_partial_kernel<DT, D, 4><<<dim3(w.n_items, nh / 4), 256, 0, st>>>(q, kc, vc, w.items, nh, Smax, w.chunk, scale,
                                                                        w.pml, w.po);
   if (ev1) (void)hipEventRecord(ev1, st);
-  attn_merge_kernel<DT, D><<<dim3(M, nh), D, 0, st>>>(w.pml, w.po, w.row_item0, w.row_nchunk, nh, out);
+  attn_merge_kernel<DT, D><<<dim3(M, nh), D, 0, st>>>(w.pml, w.po, w.row_item0, w.row_nchunk, nh, out, w.out_mtt);
 }
 
 hipError_t decode_attention(int dtype, int d, const void* q, const void* kc, const void* vc, const AttnWork& w, int M,
@@ -514,7 +515,7 @@ static void launch_prefill(const void* q, const void* kc, const void* vc, const 
   else
     attn_prefill_mfma_kernel<DT, D><<<dim3(w.n_blocks, nh / 4), 256, 0, st>>>(
         q, kc, vc, w.blocks, w.row_slot, w.row_len, w.row_item0, w.row_nchunk, nh, Smax, w.chunk, scale, w.pml, w.po);
-  attn_merge_kernel<DT, D><<<dim3(M, nh), D, 0, st>>>(w.pml, w.po, w.row_item0, w.row_nchunk, nh, out);
+  attn_merge_kernel<DT, D><<<dim3(M, nh), D, 0, st>>>(w.pml, w.po, w.row_item0, w.row_nchunk, nh, out, w.out_mtt);
 }
 
 hipError_t prefill_attention(int dtype, int d, const void* q, const void* kc, const void* vc, const AttnWork& w, int M,

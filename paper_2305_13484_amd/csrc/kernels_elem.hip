@@ -81,7 +81,7 @@ template <int DT, int RMS>
 __global__ __launch_bounds__(1024) void add_norm_kernel(float* __restrict__ x, const float* __restrict__ part, int S,
                                                         size_t stride, int ldp, const void* __restrict__ bias,
                                                         const void* __restrict__ g, const void* __restrict__ b,
-                                                        void* __restrict__ h, int H, float eps) {
+                                                        void* __restrict__ h, int H, float eps, int mtt) {
   __shared__ float red[16];
   const int m = blockIdx.x;
   constexpr int PER = 2;
@@ -129,7 +129,7 @@ __global__ __launch_bounds__(1024) void add_norm_kernel(float* __restrict__ x, c
     if (i < H) {
       f32x4_t o = (v[c] - mean) * inv * gv[c];
       if (!RMS) o += bv[c];
-      stv4<DT>(h, (size_t)m * H + i, o);
+      stv4<DT>(h, xrow_index(m, i, H, mtt), o);
     }
   }
 }
@@ -193,7 +193,8 @@ __global__ void qkv_post_kernel(const float* __restrict__ part, int S, size_t st
 // 4 consecutive j per thread; F % 4 == 0.
 template <int DT, int SWIGLU>
 __global__ __launch_bounds__(256) void act_kernel(const float* __restrict__ part, int S, size_t stride, int ldp,
-                                                  const void* __restrict__ bias, void* __restrict__ a, int F, long total4) {
+                                                  const void* __restrict__ bias, void* __restrict__ a, int F, long total4,
+                                                  int mtt) {
   const long idx = (long)blockIdx.x * 256 + threadIdx.x;
   if (idx >= total4) return;
   const int F4 = F >> 2;
@@ -211,7 +212,7 @@ __global__ __launch_bounds__(256) void act_kernel(const float* __restrict__ part
     for (int e = 0; e < 4; ++e)
       o[e] = 0.5f * t[e] * (1.0f + tanhf(0.7978845608028654f * (t[e] + 0.044715f * t[e] * t[e] * t[e])));
   }
-  stv4<DT>(a, (size_t)m * F + j, o);
+  stv4<DT>(a, xrow_index((int)m, j, F, mtt), o);
 }
 
 // ---------------------------------------------------------------- logits + greedy token
@@ -265,12 +266,12 @@ hipError_t embed(int dtype, const void* wte, const void* wpe, const int* tok, co
 }
 
 hipError_t add_norm(int dtype, bool rms, float* x, const float* part, int S, size_t stride, int ldp, const void* bias,
-                    const void* g, const void* b, void* h, int M, int H, float eps, hipStream_t st) {
+                    const void* g, const void* b, void* h, int M, int H, float eps, int mtt, hipStream_t st) {
   if (M <= 0) return hipSuccess;
   if (rms) {
-    FLK_DT_SWITCH(dtype, (add_norm_kernel<DT, 1><<<M, 1024, 0, st>>>(x, part, S, stride, ldp, bias, g, b, h, H, eps)));
+    FLK_DT_SWITCH(dtype, (add_norm_kernel<DT, 1><<<M, 1024, 0, st>>>(x, part, S, stride, ldp, bias, g, b, h, H, eps, mtt)));
   } else {
-    FLK_DT_SWITCH(dtype, (add_norm_kernel<DT, 0><<<M, 1024, 0, st>>>(x, part, S, stride, ldp, bias, g, b, h, H, eps)));
+    FLK_DT_SWITCH(dtype, (add_norm_kernel<DT, 0><<<M, 1024, 0, st>>>(x, part, S, stride, ldp, bias, g, b, h, H, eps, mtt)));
   }
   return hipGetLastError();
 }
@@ -285,14 +286,14 @@ hipError_t qkv_post(int dtype, const float* part, int S, size_t stride, int ldp,
 }
 
 hipError_t activation(int dtype, bool swiglu, const float* part, int S, size_t stride, int ldp, const void* bias, void* a,
-                      int M, int F, hipStream_t st) {
+                      int M, int F, int mtt, hipStream_t st) {
   if (M <= 0) return hipSuccess;
   const long total = (long)M * (F / 4);
   const unsigned grid = (unsigned)((total + 255) / 256);
   if (swiglu) {
-    FLK_DT_SWITCH(dtype, (act_kernel<DT, 1><<<grid, 256, 0, st>>>(part, S, stride, ldp, bias, a, F, total)));
+    FLK_DT_SWITCH(dtype, (act_kernel<DT, 1><<<grid, 256, 0, st>>>(part, S, stride, ldp, bias, a, F, total, mtt)));
   } else {
-    FLK_DT_SWITCH(dtype, (act_kernel<DT, 0><<<grid, 256, 0, st>>>(part, S, stride, ldp, bias, a, F, total)));
+    FLK_DT_SWITCH(dtype, (act_kernel<DT, 0><<<grid, 256, 0, st>>>(part, S, stride, ldp, bias, a, F, total, mtt)));
   }
   return hipGetLastError();
 }

@@ -62,7 +62,8 @@ template <int DT> __device__ __forceinline__ f32x4_t mfma16(const u32x4_t& a, co
 template <int DT, int MT, int NT, int PFW, int PFA>
 __global__ __launch_bounds__(256) void gemm16_direct_kernel(const uint16_t* __restrict__ x, const u32x4_t* __restrict__ wt,
                                                             float* __restrict__ part, int M, int N, int K, int ngroups,
-                                                            int KB, int kbs, size_t slice_stride, int ldc) {
+                                                            int KB, int kbs, size_t slice_stride, int ldc,
+                                                            int xmtt) {
   static_assert(PFW % PFA == 0, "ring shapes");
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int g = blockIdx.x * 4 + wave;
@@ -79,7 +80,10 @@ __global__ __launch_bounds__(256) void gemm16_direct_kernel(const uint16_t* __re
     for (int t = 0; t < NT; ++t) acc[i][t] = f32x4_t{0.f, 0.f, 0.f, 0.f};
 
   const u32x4_t* wp = wt + ((size_t)g * KB) * NT * 64 + lane;                    // + (kb*NT + t)*64
-  const uint16_t* xp = x + (size_t)(m0 + (lane & 15)) * K + (lane >> 4) * 8;     // + i*16*K + kb*32
+  // rows' operand: row-major [M][K] (xmtt == 0) or fragment order with xmtt row tiles per k-block
+  const size_t tstride = xmtt ? 512 : (size_t)16 * K, kstride = xmtt ? (size_t)xmtt * 512 : 32;
+  const uint16_t* xp = xmtt ? x + (size_t)(m0 >> 4) * 512 + lane * 8
+                            : x + (size_t)(m0 + (lane & 15)) * K + (lane >> 4) * 8;     // + i*tstride + kb*kstride
 
   u32x4_t bq[PFW][NT], aq[PFA][MT];
   static_assert(PFW == PFA, "both rings turn together");
@@ -89,7 +93,7 @@ __global__ __launch_bounds__(256) void gemm16_direct_kernel(const uint16_t* __re
 #pragma unroll
     for (int t = 0; t < NT; ++t) bq[j][t] = __builtin_nontemporal_load(wp + ((size_t)kk * NT + t) * 64);
 #pragma unroll
-    for (int i = 0; i < MT; ++i) aq[j][i] = *(const u32x4_t*)(xp + (size_t)i * 16 * K + kk * 32);
+    for (int i = 0; i < MT; ++i) aq[j][i] = *(const u32x4_t*)(xp + i * tstride + kk * kstride);
     __builtin_amdgcn_sched_barrier(0);
   }
   // One turn of the ring.  The steady-state turns (TAIL = false: all PFW k-blocks exist) are free of branches, so the
@@ -111,7 +115,7 @@ __global__ __launch_bounds__(256) void gemm16_direct_kernel(const uint16_t* __re
         for (int t = 0; t < NT; ++t) bq[j][t] = __builtin_nontemporal_load(wp + ((size_t)kw * NT + t) * 64);
         const int ka = min(kb + j + PFA, kb1 - 1);
 #pragma unroll
-        for (int i = 0; i < MT; ++i) aq[j % PFA][i] = *(const u32x4_t*)(xp + (size_t)i * 16 * K + ka * 32);
+        for (int i = 0; i < MT; ++i) aq[j % PFA][i] = *(const u32x4_t*)(xp + i * tstride + ka * kstride);
         __builtin_amdgcn_sched_barrier(0);
       }
     }
@@ -143,7 +147,7 @@ __global__ __launch_bounds__(64 * 4 * (NT / NTW)) void gemm16_lds_kernel(const u
                                                                          float* __restrict__ part, int M, int N, int K,
                                                                          int ngroups, int KB, int kbs,
                                                                          size_t slice_stride, int ldc, int nx,
-                                                                         int nslices, int nz) {
+                                                                         int nslices, int nz, int xmtt) {
   static_assert(PF % KC == 0 && NT % NTW == 0, "ring and tile shapes");
   constexpr int WPG = NT / NTW;                  // waves that share one column group, each taking NTW of its n-tiles
   constexpr int NW = 4 * WPG;                    // waves per block: 4 column groups
@@ -172,7 +176,10 @@ __global__ __launch_bounds__(64 * 4 * (NT / NTW)) void gemm16_lds_kernel(const u
     for (int t = 0; t < NTW; ++t) acc[i][t] = f32x4_t{0.f, 0.f, 0.f, 0.f};
 
   const u32x4_t* wp = wt + (((size_t)gl * KB) * NT + sub * NTW) * 64 + lane;     // + (kb*NT + t)*64
-  const uint16_t* xp = x + (size_t)(m0 + (lane & 15)) * K + (lane >> 4) * 8;
+  // rows' operand: row-major [M][K] (xmtt == 0) or fragment order with xmtt row tiles per k-block
+  const size_t tstride = xmtt ? 512 : (size_t)16 * K, kstride = xmtt ? (size_t)xmtt * 512 : 32;
+  const uint16_t* xp = xmtt ? x + (size_t)(m0 >> 4) * 512 + lane * 8
+                            : x + (size_t)(m0 + (lane & 15)) * K + (lane >> 4) * 8;     // + i*tstride + kb*kstride
 
   u32x4_t bq[PF][NTW], areg[FPW];
 #pragma unroll
@@ -186,7 +193,7 @@ __global__ __launch_bounds__(64 * 4 * (NT / NTW)) void gemm16_lds_kernel(const u
     for (int j = 0; j < FPW; ++j) {
       const int f = min(wave + NW * j, KC * MT - 1), kc = f / MT, i = f - kc * MT;
       const int kk = min(kb0 + chunk * KC + kc, kb1 - 1);
-      areg[j] = *(const u32x4_t*)(xp + (size_t)i * 16 * K + kk * 32);
+      areg[j] = *(const u32x4_t*)(xp + i * tstride + kk * kstride);
     }
   };
   auto store_a = [&](int buf) {      // surplus waves store the last fragment once more (same data, no branch)
@@ -260,7 +267,7 @@ template <int DT, int MTW, int NT, int KC, int PF>
 __global__ __launch_bounds__(512) void gemm16_rows_kernel(const uint16_t* __restrict__ x, const u32x4_t* __restrict__ wt,
                                                           float* __restrict__ part, int M, int N, int K, int ngroups,
                                                           int KB, int kbs, size_t slice_stride, int ldc, int nx,
-                                                          int nslices, int nz) {
+                                                          int nslices, int nz, int xmtt) {
   static_assert(PF % KC == 0, "ring shape");
   constexpr int MTB = 2 * MTW;                   // row tiles per block
   constexpr int NW = 8;
@@ -287,7 +294,10 @@ __global__ __launch_bounds__(512) void gemm16_rows_kernel(const uint16_t* __rest
     for (int t = 0; t < NT; ++t) acc[i][t] = f32x4_t{0.f, 0.f, 0.f, 0.f};
 
   const u32x4_t* wp = wt + ((size_t)gl * KB) * NT * 64 + lane;     // + (kb*NT + t)*64
-  const uint16_t* xp = x + (size_t)(m0 + (lane & 15)) * K + (lane >> 4) * 8;
+  // rows' operand: row-major [M][K] (xmtt == 0) or fragment order with xmtt row tiles per k-block
+  const size_t tstride = xmtt ? 512 : (size_t)16 * K, kstride = xmtt ? (size_t)xmtt * 512 : 32;
+  const uint16_t* xp = xmtt ? x + (size_t)(m0 >> 4) * 512 + lane * 8
+                            : x + (size_t)(m0 + (lane & 15)) * K + (lane >> 4) * 8;     // + i*tstride + kb*kstride
 
   u32x4_t bq[PF][NT], areg[FPW];
 #pragma unroll
@@ -301,7 +311,7 @@ __global__ __launch_bounds__(512) void gemm16_rows_kernel(const uint16_t* __rest
     for (int j = 0; j < FPW; ++j) {
       const int f = min(wave + NW * j, KC * MTB - 1), kc = f / MTB, i = f - kc * MTB;
       const int kk = min(kb0 + chunk * KC + kc, kb1 - 1);
-      areg[j] = *(const u32x4_t*)(xp + (size_t)i * 16 * K + kk * 32);
+      areg[j] = *(const u32x4_t*)(xp + i * tstride + kk * kstride);
     }
   };
   auto store_a = [&](int buf) {
@@ -468,51 +478,56 @@ hipError_t retile(int dtype, const void* W, int N, int K, void* tiled, int n_off
 hipError_t zero_fill(void* p, size_t bytes, hipStream_t st) { return hipMemsetAsync(p, 0, bytes, st); }
 
 template <int DT, int MT, int NT, int PFW, int PFA>
-static void launch_direct(const void* x, const void* wt, float* part, int M, const GemmPlan& p, size_t ss, hipStream_t st) {
+static void launch_direct(const void* x, const void* wt, float* part, int M, const GemmPlan& p, size_t ss, int xmtt,
+                          hipStream_t st) {
   const int ngroups = p.Npad / (16 * NT);
   dim3 grid((ngroups + 3) / 4, p.S, (M + 16 * MT - 1) / (16 * MT));
   gemm16_direct_kernel<DT, MT, NT, PFW, PFA><<<grid, 256, 0, st>>>((const uint16_t*)x, (const u32x4_t*)wt, part, M, p.N, p.K,
-                                                             ngroups, p.KB, p.kbs, ss, p.ldc);
+                                                             ngroups, p.KB, p.kbs, ss, p.ldc, xmtt);
 }
 template <int DT, int MT, int NT, int NTW, int PF>
-static void launch_lds(const void* x, const void* wt, float* part, int M, const GemmPlan& p, size_t ss, hipStream_t st) {
+static void launch_lds(const void* x, const void* wt, float* part, int M, const GemmPlan& p, size_t ss, int xmtt,
+                       hipStream_t st) {
   const int ngroups = p.Npad / (16 * NT);
   const int nx = (ngroups + 3) / 4, nz = (M + 16 * MT - 1) / (16 * MT);
   const int tasks8 = (nx * p.S + 7) / 8 * 8;
   gemm16_lds_kernel<DT, MT, NT, NTW, 2, PF><<<dim3(tasks8 * nz), 64 * 4 * (NT / NTW), 0, st>>>(
-      (const uint16_t*)x, (const u32x4_t*)wt, part, M, p.N, p.K, ngroups, p.KB, p.kbs, ss, p.ldc, nx, p.S, nz);
+      (const uint16_t*)x, (const u32x4_t*)wt, part, M, p.N, p.K, ngroups, p.KB, p.kbs, ss, p.ldc, nx, p.S, nz, xmtt);
 }
 
 template <int DT, int NT>
-static void launch_rows(const void* x, const void* wt, float* part, int M, const GemmPlan& p, size_t ss, hipStream_t st) {
+static void launch_rows(const void* x, const void* wt, float* part, int M, const GemmPlan& p, size_t ss, int xmtt,
+                        hipStream_t st) {
   const int ngroups = p.Npad / (16 * NT);
   const int nx = (ngroups + 3) / 4, nz = (M + 255) / 256;
   const int tasks8 = (nx * p.S + 7) / 8 * 8;
   gemm16_rows_kernel<DT, 8, NT, 2, 2><<<dim3(tasks8 * nz), 512, 0, st>>>(
-      (const uint16_t*)x, (const u32x4_t*)wt, part, M, p.N, p.K, ngroups, p.KB, p.kbs, ss, p.ldc, nx, p.S, nz);
+      (const uint16_t*)x, (const u32x4_t*)wt, part, M, p.N, p.K, ngroups, p.KB, p.kbs, ss, p.ldc, nx, p.S, nz, xmtt);
 }
 
 template <int DT, int NT>
-static void dispatch16(const void* x, const void* wt, float* part, int M, const GemmPlan& p, size_t ss, hipStream_t st) {
-  if (M <= 16) launch_direct<DT, 1, NT, 8, 8>(x, wt, part, M, p, ss, st);
-  else if (M <= 32) launch_lds<DT, 2, NT, NT, 4>(x, wt, part, M, p, ss, st);     // 4 waves, one per column group
-  else if (M <= 64) launch_lds<DT, 4, NT, 2, 4>(x, wt, part, M, p, ss, st);      // 8 waves, two per column group
-  else if (M <= 128) launch_lds<DT, 8, NT, 2, 4>(x, wt, part, M, p, ss, st);
-  else launch_rows<DT, NT>(x, wt, part, M, p, ss, st);             // row blocks of 256
+static void dispatch16(const void* x, const void* wt, float* part, int M, const GemmPlan& p, size_t ss, int xmtt,
+                       hipStream_t st) {
+  if (M <= 16) launch_direct<DT, 1, NT, 8, 8>(x, wt, part, M, p, ss, xmtt, st);
+  else if (M <= 32) launch_lds<DT, 2, NT, NT, 4>(x, wt, part, M, p, ss, xmtt, st);     // 4 waves, one per column group
+  else if (M <= 64) launch_lds<DT, 4, NT, 2, 4>(x, wt, part, M, p, ss, xmtt, st);      // 8 waves, two per column group
+  else if (M <= 128) launch_lds<DT, 8, NT, 2, 4>(x, wt, part, M, p, ss, xmtt, st);
+  else launch_rows<DT, NT>(x, wt, part, M, p, ss, xmtt, st);             // row blocks of 256
 }
 
 hipError_t gemm(int dtype, const void* x, const void* wt, int M, const GemmPlan& p, float* part, size_t slice_stride,
-                hipStream_t st) {
+                int xmtt, hipStream_t st) {
   if (M <= 0) return hipSuccess;
   if (dtype == DT_F32) {
+    if (xmtt) return hipErrorInvalidValue;   // fp32 rows are always row-major
     dim3 grid((p.N + 3) / 4, (M + 7) / 8);
     gemm32_kernel<<<grid, 256, 0, st>>>((const float*)x, (const float*)wt, part, M, p.N, p.K, p.ldc);
   } else if (dtype == DT_BF16) {
-    if (p.NT == 4) dispatch16<DT_BF16, 4>(x, wt, part, M, p, slice_stride, st);
-    else dispatch16<DT_BF16, 2>(x, wt, part, M, p, slice_stride, st);
+    if (p.NT == 4) dispatch16<DT_BF16, 4>(x, wt, part, M, p, slice_stride, xmtt, st);
+    else dispatch16<DT_BF16, 2>(x, wt, part, M, p, slice_stride, xmtt, st);
   } else {
-    if (p.NT == 4) dispatch16<DT_F16, 4>(x, wt, part, M, p, slice_stride, st);
-    else dispatch16<DT_F16, 2>(x, wt, part, M, p, slice_stride, st);
+    if (p.NT == 4) dispatch16<DT_F16, 4>(x, wt, part, M, p, slice_stride, xmtt, st);
+    else dispatch16<DT_F16, 2>(x, wt, part, M, p, slice_stride, xmtt, st);
   }
   return hipGetLastError();
 }
