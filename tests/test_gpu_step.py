@@ -333,14 +333,17 @@ def test_llama30b_shape_one_layer():
     ls.close()
 
 
-def test_fused_equals_alone_at_7b_width_many_rows():
-    """HIP path only: 40 live requests at the 7B layer width (one layer) exercise the 8-wave LDS GEMM and multi-chunk
-    attention inside the step; every request's logits equal, bit for bit, those of decoding it alone."""
-    cfg = dataclasses.replace(synth.llama_7b(L=1, C=48, S=400), V=4096)
+@pytest.mark.parametrize("C,n", [(48, 40), (128, 110), (176, 160)])
+def test_fused_equals_alone_at_7b_width_many_rows(C, n):
+    """HIP path only: 40 / 110 / 160 live requests at the 7B layer width (one layer) take the step through the 8-wave
+    LDS GEMMs (33-64 and 65-128 rows) and the 256-row-block GEMM, each reading its rows in fragment order, and through
+    multi-chunk attention; every request's logits equal, bit for bit, those of decoding it alone (one row, the
+    no-LDS GEMM)."""
+    cfg = dataclasses.replace(synth.llama_7b(L=1, C=C, S=400), V=4096)
     w = to_device(synth.make_weights(cfg, 31))
-    reqs = synth.stream_small(9, cfg.V, n=40, arrive_hi=2, p_lo=1, p_hi=300, g_lo=4, g_hi=8)
+    reqs = synth.stream_small(9, cfg.V, n=n, arrive_hi=2, p_lo=1, p_hi=300, g_lo=4, g_hi=8)
     toks, logits = gpu_run_stream(cfg, w, reqs)
-    for r in reqs[::5]:
+    for r in reqs[::max(1, n // 8)]:
         t1, l1 = gpu_run_stream(cfg, w, [synth.Request(r.req_id, 0, r.prompt, r.gen_len)])
         assert t1[r.req_id] == toks[r.req_id]
         assert torch.equal(torch.stack(l1[r.req_id]), torch.stack(logits[r.req_id]))
