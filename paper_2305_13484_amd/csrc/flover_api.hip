@@ -382,9 +382,9 @@ int run_rows(flover_ctx* c, Lane& ln, const Row* rows, int n, bool want_tokens, 
     HIPCHK(c, flk::add_norm(f.dtype, !gpt, ln.x, first ? nullptr : ln.part, p_2.S, ss_h, p_2.ldc,
                             first ? nullptr : c->lw[l - 1].b2,
                             w.ln1_g, w.ln1_b, ln.h, n, H, f.norm_eps, mtt, st));
-    HIPCHK(c, timed_gemm(c, ln, FLOVER_PROF_GEMM_QKV, ln.h, w.wqkv, n, p_qkv, ss_qkv, mtt));
     char* kl = c->kv + (size_t)(2 * l) * c->plane_bytes;
     char* vl = kl + c->plane_bytes;
+    HIPCHK(c, timed_gemm(c, ln, FLOVER_PROF_GEMM_QKV, ln.h, w.wqkv, n, p_qkv, ss_qkv, mtt));
     HIPCHK(c, flk::qkv_post(f.dtype, ln.part, p_qkv.S, ss_qkv, p_qkv.ldc, w.bqkv, c->rope_cs, d_slot, d_pos, ln.q, kl, vl, n, H, nh,
                             d, f.max_seq, st));
     if (context_pass) {

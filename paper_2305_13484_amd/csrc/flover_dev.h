@@ -75,6 +75,61 @@ __device__ __forceinline__ size_t xrow_index(int m, int k, int ld, int mtt) {
   return ((size_t)(k >> 5) * mtt + (m >> 4)) * 512 + ((((k & 31) >> 3) << 4) + (m & 15)) * 8 + (k & 7);
 }
 
+// ---- 4 consecutive elements at a time
+__device__ __forceinline__ f32x4_t ld4(const float* p) { return *(const f32x4_t*)p; }
+template <int DT> __device__ __forceinline__ f32x4_t ldv4(const void* p, size_t i) {   // 4 consecutive dtype elements
+  if constexpr (DT == DT_F32) return *(const f32x4_t*)((const float*)p + i);
+  else {
+    const uint2 r = *(const uint2*)((const uint16_t*)p + i);
+    if constexpr (DT == DT_BF16)
+      return f32x4_t{__uint_as_float(r.x << 16), __uint_as_float(r.x & 0xffff0000u), __uint_as_float(r.y << 16),
+                     __uint_as_float(r.y & 0xffff0000u)};
+    else
+      return f32x4_t{f16_to_f32((uint16_t)(r.x & 0xffffu)), f16_to_f32((uint16_t)(r.x >> 16)),
+                     f16_to_f32((uint16_t)(r.y & 0xffffu)), f16_to_f32((uint16_t)(r.y >> 16))};
+  }
+}
+template <int DT> __device__ __forceinline__ void stv4(void* p, size_t i, f32x4_t v) {
+  if constexpr (DT == DT_F32) *(f32x4_t*)((float*)p + i) = v;
+  else {
+    uint2 r;
+    if constexpr (DT == DT_BF16) {
+      r.x = (uint32_t)f32_to_bf16(v[0]) | ((uint32_t)f32_to_bf16(v[1]) << 16);
+      r.y = (uint32_t)f32_to_bf16(v[2]) | ((uint32_t)f32_to_bf16(v[3]) << 16);
+    } else {
+      r.x = (uint32_t)f32_to_f16(v[0]) | ((uint32_t)f32_to_f16(v[1]) << 16);
+      r.y = (uint32_t)f32_to_f16(v[2]) | ((uint32_t)f32_to_f16(v[3]) << 16);
+    }
+    *(uint2*)((uint16_t*)p + i) = r;
+  }
+}
+
+// ---- row-wise epilogue arithmetic shared by the stand-alone kernels and the GEMM kernels that fuse them
+// Floating-point contraction is switched off inside, so that the same inputs give the same bits wherever the function
+// is inlined (a request's result must not depend on which variant served it).
+// Rotary pair (a0, a1) = elements (i, i + d/2) of a head, (cs, sn) = cos/sin of pos * theta^(-2i/d).
+__device__ __forceinline__ void rope_rotate(f32x4_t& a0, f32x4_t& a1, const f32x4_t& cs, const f32x4_t& sn) {
+#pragma clang fp contract(off)
+  const f32x4_t r0 = a0 * cs - a1 * sn, r1 = a1 * cs + a0 * sn;
+  a0 = r0;
+  a1 = r1;
+}
+__device__ __forceinline__ f32x4_t act_swiglu(const f32x4_t& g, const f32x4_t& u) {   // silu(g) * u
+#pragma clang fp contract(off)
+  f32x4_t o;
+#pragma unroll
+  for (int e = 0; e < 4; ++e) o[e] = g[e] / (1.0f + expf(-g[e])) * u[e];
+  return o;
+}
+__device__ __forceinline__ f32x4_t act_gelu(const f32x4_t& t) {                        // tanh form
+#pragma clang fp contract(off)
+  f32x4_t o;
+#pragma unroll
+  for (int e = 0; e < 4; ++e)
+    o[e] = 0.5f * t[e] * (1.0f + tanhf(0.7978845608028654f * (t[e] + 0.044715f * t[e] * t[e] * t[e])));
+  return o;
+}
+
 // ---- cross-lane: DPP within a row of 16 lanes, LDS-permute beyond.  Every step is a fixed butterfly,
 // so a reduction's result does not depend on anything but the values reduced.
 template <int CTRL> __device__ __forceinline__ float dpp_f(float v) {

@@ -12,7 +12,6 @@ namespace flk {
 // Sum of S split-K slices at 4 consecutive elements, added in slice order (s = 0, 1, 2, ...).  The loads of up to 16
 // slices (no plan has more) are all issued before the first addition, so a thread pays the memory latency once; S is
 // uniform over the grid, so the predicates are scalar branches.
-__device__ __forceinline__ f32x4_t ld4(const float* p) { return *(const f32x4_t*)p; }
 __device__ __forceinline__ f32x4_t psum4(const float* __restrict__ part, int S, size_t stride, size_t idx) {
   const float* p = part + idx;
   f32x4_t pv[16];
@@ -26,33 +25,6 @@ __device__ __forceinline__ f32x4_t psum4(const float* __restrict__ part, int S, 
   for (int s = 16; s < S; ++s) v += ld4(p + (size_t)s * stride);
   return v;
 }
-template <int DT> __device__ __forceinline__ f32x4_t ldv4(const void* p, size_t i) {   // 4 consecutive dtype elements
-  if constexpr (DT == DT_F32) return *(const f32x4_t*)((const float*)p + i);
-  else {
-    const uint2 r = *(const uint2*)((const uint16_t*)p + i);
-    if constexpr (DT == DT_BF16)
-      return f32x4_t{__uint_as_float(r.x << 16), __uint_as_float(r.x & 0xffff0000u), __uint_as_float(r.y << 16),
-                     __uint_as_float(r.y & 0xffff0000u)};
-    else
-      return f32x4_t{f16_to_f32((uint16_t)(r.x & 0xffffu)), f16_to_f32((uint16_t)(r.x >> 16)),
-                     f16_to_f32((uint16_t)(r.y & 0xffffu)), f16_to_f32((uint16_t)(r.y >> 16))};
-  }
-}
-template <int DT> __device__ __forceinline__ void stv4(void* p, size_t i, f32x4_t v) {
-  if constexpr (DT == DT_F32) *(f32x4_t*)((float*)p + i) = v;
-  else {
-    uint2 r;
-    if constexpr (DT == DT_BF16) {
-      r.x = (uint32_t)f32_to_bf16(v[0]) | ((uint32_t)f32_to_bf16(v[1]) << 16);
-      r.y = (uint32_t)f32_to_bf16(v[2]) | ((uint32_t)f32_to_bf16(v[3]) << 16);
-    } else {
-      r.x = (uint32_t)f32_to_f16(v[0]) | ((uint32_t)f32_to_f16(v[1]) << 16);
-      r.y = (uint32_t)f32_to_f16(v[2]) | ((uint32_t)f32_to_f16(v[3]) << 16);
-    }
-    *(uint2*)((uint16_t*)p + i) = r;
-  }
-}
-
 // ---------------------------------------------------------------- embedding
 // x[m][i] = wte[tok[m]][i] (+ wpe[pos[m]][i])            grid = M, block = 256
 // tok[m] < 0 feeds the token the previous iteration chose for its row -1 - tok[m] (still on the device).
@@ -173,8 +145,7 @@ __global__ void qkv_post_kernel(const float* __restrict__ part, int S, size_t st
   if (bias) { a0 += ldv4<DT>(bias, c0); a1 += ldv4<DT>(bias, c1); }
   if (rot) {
     const f32x4_t cs = {t0[0], t0[2], t1[0], t1[2]}, sn = {t0[1], t0[3], t1[1], t1[3]};
-    const f32x4_t r0 = a0 * cs - a1 * sn, r1 = a1 * cs + a0 * sn;
-    a0 = r0; a1 = r1;
+    rope_rotate(a0, a1, cs, sn);
   }
   if (which == 0) {
     stv4<DT>(qout, (size_t)m * H + hd * d + i, a0);
@@ -204,13 +175,10 @@ __global__ __launch_bounds__(256) void act_kernel(const float* __restrict__ part
   if (SWIGLU) {
     const f32x4_t g = psum4(part, S, stride, (size_t)m * ldp + j);
     const f32x4_t u = psum4(part, S, stride, (size_t)m * ldp + F + j);
-#pragma unroll
-    for (int e = 0; e < 4; ++e) o[e] = g[e] / (1.0f + expf(-g[e])) * u[e];
+    o = act_swiglu(g, u);
   } else {
     const f32x4_t t = psum4(part, S, stride, (size_t)m * ldp + j) + ldv4<DT>(bias, j);
-#pragma unroll
-    for (int e = 0; e < 4; ++e)
-      o[e] = 0.5f * t[e] * (1.0f + tanhf(0.7978845608028654f * (t[e] + 0.044715f * t[e] * t[e] * t[e])));
+    o = act_gelu(t);
   }
   stv4<DT>(a, xrow_index((int)m, j, F, mtt), o);
 }
