@@ -266,7 +266,8 @@ int32_t flover_k_gemm_tiled_bytes(int32_t dtype, int32_t N, int32_t K, uint64_t*
 /* [host only] K slicing of the weight GEMM: *slices partial sums, each over *k_blocks_per_slice blocks of 32 input
  * features (the last slice may be shorter).  context_rows == 0: the fused iteration's slicing, a function of (dtype, N,
  * K) alone, so that a row's result cannot depend on how many rows are live; context_rows > 0: the slicing of a
- * pre-processing pass of that many rows of one request (never more slices than the iteration's). */
+ * pre-processing pass of that many rows of one request (at most 16 slices; a context may use fewer when its
+ * partial-sum buffer, sized for the iteration, holds fewer at that row count). */
 int32_t flover_k_gemm_plan(int32_t dtype, int32_t N, int32_t K, int32_t context_rows, int32_t* slices,
                            int32_t* k_blocks_per_slice);
 int32_t flover_k_gemm_workspace_bytes(int32_t dtype, int32_t M, int32_t N, int32_t K, uint64_t* out);

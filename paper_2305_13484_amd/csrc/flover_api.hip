@@ -106,6 +106,7 @@ struct flover_ctx {
   Lane* prep_lane = nullptr;   // == &step_lane unless pre-processing is asynchronous
   int4* d_moves;
   size_t stage_ints;
+  size_t part_floats = 0;      // capacity of a lane's split-K partial-sum buffer
   size_t act_off = 0;          // arena offset where the row buffers start
   struct InFlight {                  // an iteration submitted with flover_step_submit and not collected yet
     int64_t id;
@@ -224,6 +225,7 @@ size_t layout(flover_ctx* c, char* base) {
     ln->att = b.take((size_t)R * H * e);
     ln->act = b.take((size_t)R * F * e);
     ln->part = (float*)b.take(pw * R * 4);
+    c->part_floats = pw * R;
     ln->tok_out = (int*)b.take((size_t)R * 4);
     ln->d_stage = (int*)b.take(c->stage_ints * 4);
     ln->pml = (float*)b.take((size_t)c->max_items * f.n_head * 2 * 4);
@@ -368,10 +370,13 @@ int run_rows(flover_ctx* c, Lane& ln, const Row* rows, int n, bool want_tokens, 
   int launches = 0;
   // K slicing: the iteration's is fixed by the matrix shape; a context pass holds rows of one request only and may
   // slice by that request's row count as well (still independent of what else is in flight)
-  const flk::GemmPlan p_qkv = context_pass ? flk::context_plan(c->p_qkv, f.dtype, n) : c->p_qkv;
-  const flk::GemmPlan p_o = context_pass ? flk::context_plan(c->p_o, f.dtype, n) : c->p_o;
-  const flk::GemmPlan p_1 = context_pass ? flk::context_plan(c->p_1, f.dtype, n) : c->p_1;
-  const flk::GemmPlan p_2 = context_pass ? flk::context_plan(c->p_2, f.dtype, n) : c->p_2;
+  auto ctx_plan = [&](const flk::GemmPlan& p) {
+    return flk::context_plan(p, f.dtype, n, (int)std::min<size_t>(16, c->part_floats / ((size_t)n * p.ldc)));
+  };
+  const flk::GemmPlan p_qkv = context_pass ? ctx_plan(c->p_qkv) : c->p_qkv;
+  const flk::GemmPlan p_o = context_pass ? ctx_plan(c->p_o) : c->p_o;
+  const flk::GemmPlan p_1 = context_pass ? ctx_plan(c->p_1) : c->p_1;
+  const flk::GemmPlan p_2 = context_pass ? ctx_plan(c->p_2) : c->p_2;
   const size_t ss_qkv = (size_t)n * p_qkv.ldc, ss_h = (size_t)n * p_o.ldc, ss_1 = (size_t)n * p_1.ldc,
                ss_v = (size_t)n * c->p_lm.ldc;
   HIPCHK(c, flk::embed(f.dtype, c->wte, c->wpe, d_tok, d_pos, ln.tok_out, ln.x, n, H, st));
@@ -1279,7 +1284,7 @@ extern "C" int32_t flover_k_gemm_plan(int32_t dtype, int32_t N, int32_t K, int32
       !k_blocks_per_slice)
     return fail(nullptr, FLOVER_E_INVAL, "bad argument");
   flk::GemmPlan p = flk::gemm_plan(dtype, N, K);
-  if (context_rows > 0) p = flk::context_plan(p, dtype, context_rows);
+  if (context_rows > 0) p = flk::context_plan(p, dtype, context_rows, 16);
   *slices = p.S;
   *k_blocks_per_slice = dtype == FLOVER_F32 ? K / 32 : p.kbs;   // the fp32 kernel takes all of K in one slice
   return FLOVER_OK;

@@ -20,8 +20,8 @@ inline int part_ld(int N) { return (N + 3) / 4 * 4; }
 GemmPlan gemm_plan(int dtype, int N, int K);
 size_t gemm_tiled_bytes(int dtype, int N, int K);
 // Slicing for a context pass of M rows of one request (a function of the matrix shape and of that request's own row
-// count only): same tiling, fewer K slices.
-GemmPlan context_plan(const GemmPlan& p, int dtype, int M);
+// count only): same tiling, its own number of K slices, at most max_slices (what the partial-sum buffer holds) and 16.
+GemmPlan context_plan(const GemmPlan& p, int dtype, int M, int max_slices);
 // Re-tile W [N][K] into `tiled` starting at output column n_off (multiple of 16) of a possibly larger matrix whose
 // plan uses NT n-tiles per column group.
 hipError_t retile(int dtype, const void* W, int N, int K, void* tiled, int n_off, int NT, hipStream_t st);

@@ -261,14 +261,15 @@ __global__ __launch_bounds__(64 * 4 * (NT / NTW)) void gemm16_lds_kernel(const u
 // ---- context passes (hundreds of rows): the contraction is MFMA-bound there, so each wave keeps a 128 x 64 output
 // tile (MTW = 8 row tiles x NT = 4 n-tiles, 128 accumulator registers): per k-block 32 MFMAs for 8 KiB of LDS reads and
 // 4 KiB of W loads, which halves the operand traffic per flop of the 128-row kernel above (whose waves own 128 x 32).
-// A block is 4 column groups x 2 row halves = 8 waves over 256 rows x 256 columns; x tile and W ring as above.
+// A block is 4 column units x 2 row halves = 8 waves over 256 rows x 256 columns; a unit is 64 columns = one group of
+// the matrix layout or (NTL = 2) two consecutive ones; x tile and W ring as above.
 // The per-(m, n) arithmetic is again the same MFMA sequence over k.
-template <int DT, int MTW, int NT, int KC, int PF>
+template <int DT, int MTW, int NT, int NTL, int KC, int PF>
 __global__ __launch_bounds__(512) void gemm16_rows_kernel(const uint16_t* __restrict__ x, const u32x4_t* __restrict__ wt,
                                                           float* __restrict__ part, int M, int N, int K, int ngroups,
                                                           int KB, int kbs, size_t slice_stride, int ldc, int nx,
                                                           int nslices, int nz, int xmtt) {
-  static_assert(PF % KC == 0, "ring shape");
+  static_assert(PF % KC == 0 && NT % NTL == 0, "ring and tile shapes");
   constexpr int MTB = 2 * MTW;                   // row tiles per block
   constexpr int NW = 8;
   __shared__ u32x4_t lds[2][KC * MTB * 64];
@@ -293,7 +294,9 @@ __global__ __launch_bounds__(512) void gemm16_rows_kernel(const uint16_t* __rest
 #pragma unroll
     for (int t = 0; t < NT; ++t) acc[i][t] = f32x4_t{0.f, 0.f, 0.f, 0.f};
 
-  const u32x4_t* wp = wt + ((size_t)gl * KB) * NT * 64 + lane;     // + (kb*NT + t)*64
+  // the wave's NT n-tiles are NT / NTL consecutive column groups of the matrix layout (NTL tiles per group)
+  const u32x4_t* wp = wt + ((size_t)gl * (NT / NTL) * KB) * NTL * 64 + lane;     // + woff(kb, t)
+  auto woff = [&](int kb, int t) { return (((size_t)(t / NTL) * KB + kb) * NTL + (t % NTL)) * 64; };
   // rows' operand: row-major [M][K] (xmtt == 0) or fragment order with xmtt row tiles per k-block
   const size_t tstride = xmtt ? 512 : (size_t)16 * K, kstride = xmtt ? (size_t)xmtt * 512 : 32;
   const uint16_t* xp = xmtt ? x + (size_t)(m0 >> 4) * 512 + lane * 8
@@ -304,7 +307,7 @@ __global__ __launch_bounds__(512) void gemm16_rows_kernel(const uint16_t* __rest
   for (int j = 0; j < PF; ++j) {
     const int kk = min(kb0 + j, kb1 - 1);
 #pragma unroll
-    for (int t = 0; t < NT; ++t) bq[j][t] = wp[((size_t)kk * NT + t) * 64];
+    for (int t = 0; t < NT; ++t) bq[j][t] = wp[woff(kk, t)];
   }
   auto load_a = [&](int chunk) {
 #pragma unroll
@@ -343,7 +346,7 @@ __global__ __launch_bounds__(512) void gemm16_rows_kernel(const uint16_t* __rest
       }
       const int kk = min(kb + PF, kb1 - 1);
 #pragma unroll
-      for (int t = 0; t < NT; ++t) bq[cc * KC + kc][t] = wp[((size_t)kk * NT + t) * 64];
+      for (int t = 0; t < NT; ++t) bq[cc * KC + kc][t] = wp[woff(kk, t)];
       __builtin_amdgcn_sched_barrier(0);
     }
     if (more) store_a((c + 1) & 1);
@@ -415,10 +418,12 @@ GemmPlan gemm_plan(int dtype, int N, int K) {
   }
   p.Npad = (N + 63) / 64 * 64;
   p.KB = K / 32;
-  // Everything below is a function of (N, K) only, never of the number of live rows.  A wave owns 64 columns; K is
-  // split just enough for about 800 waves (3 per CU, each streaming a contiguous run of W with a deep prefetch ring):
-  // more slices would only add partial-sum traffic.
-  p.NT = 4;
+  // Everything below is a function of (N, K) only, never of the number of live rows.  A wave owns 64 columns -- 32 for
+  // matrices of at most 4096 columns, which would otherwise need 13 K slices to fill the chip -- and K is split just
+  // enough for about 800 waves (3 per CU, each streaming a contiguous run of W with a deep prefetch ring): more slices
+  // only add partial-sum traffic, for this kernel's stores and for the row-wise kernel that adds the slices up
+  // (measured on the 7B stream: 32-column waves for out-proj and FFN-down + 2 % tokens/s, for the wider matrices - 2 %).
+  p.NT = p.Npad / 64 <= 64 ? 2 : 4;
   const int ngroups = p.Npad / (16 * p.NT);
   const int target = 800;
   int S = (target + ngroups / 2) / ngroups;
@@ -441,12 +446,12 @@ size_t gemm_tiled_bytes(int dtype, int N, int K) {
 // rounds of blocks x k-blocks per slice (about 1 us per k-block step of a block, measured), plus the fp32 partial sums
 // written by this kernel and re-read by the next one (about 5 TB/s) -- at hundreds of rows those outweigh the weights
 // when the iteration's slicing is kept, while a single slice leaves most of the chip idle for the 4096-column matrices.
-GemmPlan context_plan(const GemmPlan& p, int dtype, int M) {
+GemmPlan context_plan(const GemmPlan& p, int dtype, int M, int max_slices) {
   GemmPlan q = p;
   if (dtype == DT_F32 || M <= 128) return q;
-  const int ngroups = p.Npad / (16 * p.NT);
-  const long units = (long)((ngroups + 3) / 4) * ((M + 255) / 256);
-  const int smax = p.S;   // never more slices than the iteration's plan: the partial-sum buffer is sized for those
+  const long units = (long)((p.Npad / 64 + 3) / 4) * ((M + 255) / 256);
+  const int smax = std::max(1, std::min(max_slices, 16));   // what the caller's partial-sum buffer holds; the row-wise
+                                                             // kernels load up to 16 slices at once
   double best = 0.0;
   int bestS = 1;
   for (int S = 1; S <= smax; ++S) {
@@ -495,13 +500,13 @@ static void launch_lds(const void* x, const void* wt, float* part, int M, const 
       (const uint16_t*)x, (const u32x4_t*)wt, part, M, p.N, p.K, ngroups, p.KB, p.kbs, ss, p.ldc, nx, p.S, nz, xmtt);
 }
 
-template <int DT, int NT>
+template <int DT, int NTL>
 static void launch_rows(const void* x, const void* wt, float* part, int M, const GemmPlan& p, size_t ss, int xmtt,
                         hipStream_t st) {
-  const int ngroups = p.Npad / (16 * NT);
+  const int ngroups = p.Npad / 64;            // units of 64 columns, whatever the layout's group width
   const int nx = (ngroups + 3) / 4, nz = (M + 255) / 256;
   const int tasks8 = (nx * p.S + 7) / 8 * 8;
-  gemm16_rows_kernel<DT, 8, NT, 2, 2><<<dim3(tasks8 * nz), 512, 0, st>>>(
+  gemm16_rows_kernel<DT, 8, 4, NTL, 2, 2><<<dim3(tasks8 * nz), 512, 0, st>>>(
       (const uint16_t*)x, (const u32x4_t*)wt, part, M, p.N, p.K, ngroups, p.KB, p.kbs, ss, p.ldc, nx, p.S, nz, xmtt);
 }
 
