@@ -134,15 +134,15 @@ __global__ __launch_bounds__(256) void gemm16_direct_kernel(const uint16_t* __re
 }
 
 // ---- larger M (17..128 rows per block): the rows' operand is staged through LDS once per block and shared by its
-// waves; a block covers 4 column groups (256 columns), each group by NT/NTW waves that own NTW of its n-tiles and stream
-// their W tiles from HBM into registers, PF k-blocks ahead.  From 33 rows up two waves share a group (8 waves per
-// block): a single wave issues MFMAs at about 60% of the unit's rate, two waves per SIMD interleave and also hide each
-// other's LDS and memory waits.
+// waves; a block covers GPB = 4 column groups (256 columns; 128 for matrices laid out in 32-column groups), each group
+// by NT/NTW waves that own NTW of its n-tiles and stream their W tiles from HBM into registers, PF k-blocks ahead.
+// From 33 rows up a wave owns 32 columns (8 waves per 256-column block): a single wave issues MFMAs at about 60% of
+// the unit's rate, two waves per SIMD interleave and also hide each other's LDS and memory waits.
 // LDS holds the x tile in MFMA fragment order ([k-block][m-tile][lane] x 16 B), so every ds_read_b128 of a fragment
 // is 1 KiB contiguous and bank-conflict free.  Double-buffered chunks of KC k-blocks, one barrier per chunk.
 // The per-(m, n) arithmetic (MFMA sequence over k) is identical to the direct kernel's.
-template <int DT, int MT, int NT, int NTW, int KC, int PF>
-__global__ __launch_bounds__(64 * 4 * (NT / NTW)) void gemm16_lds_kernel(const uint16_t* __restrict__ x,
+template <int DT, int MT, int NT, int NTW, int KC, int PF, int GPB>
+__global__ __launch_bounds__(64 * GPB * (NT / NTW)) void gemm16_lds_kernel(const uint16_t* __restrict__ x,
                                                                          const u32x4_t* __restrict__ wt,
                                                                          float* __restrict__ part, int M, int N, int K,
                                                                          int ngroups, int KB, int kbs,
@@ -150,7 +150,7 @@ __global__ __launch_bounds__(64 * 4 * (NT / NTW)) void gemm16_lds_kernel(const u
                                                                          int nslices, int nz, int xmtt) {
   static_assert(PF % KC == 0 && NT % NTW == 0, "ring and tile shapes");
   constexpr int WPG = NT / NTW;                  // waves that share one column group, each taking NTW of its n-tiles
-  constexpr int NW = 4 * WPG;                    // waves per block: 4 column groups
+  constexpr int NW = GPB * WPG;                  // waves per block: GPB column groups (256 columns)
   __shared__ u32x4_t lds[2][KC * MT * 64];
   constexpr int FPW = (KC * MT + NW - 1) / NW;   // fragments each wave stages per chunk (surplus ones are skipped)
   constexpr int CPR = PF / KC;                   // chunks per turn of the W ring
@@ -162,7 +162,7 @@ __global__ __launch_bounds__(64 * 4 * (NT / NTW)) void gemm16_lds_kernel(const u
   const int zb = qq % nz, task = (qq / nz) * 8 + xcd;
   if (task >= nx * nslices) return;              // padding of the grid (whole block)
   const int bx = task % nx, s = task / nx;
-  const int g = bx * 4 + wave / WPG, sub = wave % WPG;
+  const int g = bx * GPB + wave / WPG, sub = wave % WPG;
   const int gl = min(g, ngroups - 1);            // surplus waves repeat the last group (they still serve the barriers)
   const int m0 = zb * (16 * MT);
   const int kb0 = s * kbs;
@@ -493,10 +493,12 @@ static void launch_direct(const void* x, const void* wt, float* part, int M, con
 template <int DT, int MT, int NT, int NTW, int PF>
 static void launch_lds(const void* x, const void* wt, float* part, int M, const GemmPlan& p, size_t ss, int xmtt,
                        hipStream_t st) {
+  constexpr int GPB = 4;                        // column groups per block: 256 columns, or 128 for the 32-column groups
+                                                // (8 groups per block measured 3 % slower on the 7B stream)
   const int ngroups = p.Npad / (16 * NT);
-  const int nx = (ngroups + 3) / 4, nz = (M + 16 * MT - 1) / (16 * MT);
+  const int nx = (ngroups + GPB - 1) / GPB, nz = (M + 16 * MT - 1) / (16 * MT);
   const int tasks8 = (nx * p.S + 7) / 8 * 8;
-  gemm16_lds_kernel<DT, MT, NT, NTW, 2, PF><<<dim3(tasks8 * nz), 64 * 4 * (NT / NTW), 0, st>>>(
+  gemm16_lds_kernel<DT, MT, NT, NTW, 2, PF, GPB><<<dim3(tasks8 * nz), 64 * GPB * (NT / NTW), 0, st>>>(
       (const uint16_t*)x, (const u32x4_t*)wt, part, M, p.N, p.K, ngroups, p.KB, p.kbs, ss, p.ldc, nx, p.S, nz, xmtt);
 }
 
