@@ -7,9 +7,10 @@
 //     lane l holds W[n0 + l%16][k0 + 8*(l/16) .. +8], so every wave load is one contiguous, fully used 1 KiB;
 //     tiles are ordered [column group of NT n-tiles][k-block][n-tile in group], so the K slice a wave streams is
 //     one contiguous run of memory (NT KiB per k-block).
-//   * a column group (64 columns = 4 n-tiles) x one K slice x all rows of a row block is the unit of work; up to 16
-//     rows one wave takes it and reads the rows' operand straight from L2/L1 (no LDS, no barriers); above that the
-//     rows' operand is staged through LDS once per block of 4 column groups and shared by the block's 4 or 8 waves.
+//   * a column group (NT n-tiles: 64 columns, or 32 for matrices of at most 4096 columns) x one K slice x all rows of
+//     a row block is the unit of work; up to 16 rows one wave takes it and reads the rows' operand straight from L2/L1
+//     (no LDS, no barriers); above that the rows' operand is staged through LDS once per block of 4 column groups and
+//     shared by the block's 4 or 8 waves.
 //   * more than 128 rows (context passes, very wide windows): the contraction turns MFMA-bound, so a wave keeps a
 //     128 x 64 output tile and a block covers 256 rows x 256 columns; row blocks of one (column block, K slice) get
 //     workgroup ids that land on the same XCD, so the weight tiles cross HBM once and are L2 hits for the others.
