@@ -17,8 +17,8 @@
 //   * split-K: for the fused iteration slice count and boundaries depend on (N, K) only -- never on M -- and partial
 //     sums are written per slice and added by the consumer in slice order, so a row's result does not depend on which
 //     other rows are live (the paper's premise that fused requests undergo identical operations).  A context pass
-//     holds rows of one request and is sliced by that request's row count too (context_plan): fewer slices, because
-//     at hundreds of rows the fp32 partial sums would outweigh the weights.
+//     holds rows of one request and is sliced by that request's row count too (context_plan): few slices at hundreds
+//     of rows, where the fp32 partial sums would outweigh the weights, more for short prompts.
 //   * MFMA v_mfma_f32_16x16x32_{bf16,f16}: A = 16 columns of W, B = 16 rows of x, 32-deep: the accumulator tile is
 //     y^T, so a lane holds 4 consecutive output columns of one row and stores them as one 16-byte write.
 // fp32 models (tiny configurations only) use a plain FMA kernel on the untiled matrix.
