@@ -453,6 +453,14 @@ def main():
             buckets["live_%d_%s" % (lo, hi if hi < 10 ** 9 else "up")] = {
                 "steps": len(sel), "ms_per_step": round(1e3 * tt / len(sel), 3),
                 "hbm_GBs": round(sum(b for _, _, b in sel) / tt / 1e9, 1)}
+    # per-step achieved bandwidth as a distribution (synchronous step only: pipelined iterations overlap)
+    dist = None
+    if not piped:
+        g = sorted((b / t / 1e9, n) for n, t, b in per if n and t > 0)
+        if g:
+            pick = lambda q: round(g[min(len(g) - 1, int(q * len(g)))][0], 1)
+            dist = {"p10": pick(0.10), "p50": pick(0.50), "p90": pick(0.90),
+                    "token_weighted_mean": round(sum(v * n for v, n in g) / sum(n for _, n in g), 1)}
     gemms = {}
     for k in ("gemm_qkv", "gemm_out", "gemm_ff1", "gemm_ff2", "gemm_lm", "compact"):
         p = prof[k]
@@ -469,6 +477,7 @@ def main():
                    "async_preprocess": a.async_preprocess, "pipeline": piped},
         "tokens": res["tokens"], "mean_live": round(res["tokens"] / K, 2),
         "step_hbm_GBs": round(step_gbs, 1), "step_hbm_frac": round(step_gbs / HBM_PEAK_GBS, 4), "by_live_rows": buckets,
+        "step_hbm_GBs_distribution": dist,
         "preprocess_s": round(res["t_pre"], 3), "tokens_per_s_incl_preprocess": round(res["tokens"] / (total + res["t_pre"]), 2),
         "shuffle_moves": res["moves"], "shuffle_bytes": res["bytes_moved"],
         "total_iterations_from_first_token": K - min(r.arrival_step for r in reqs),
