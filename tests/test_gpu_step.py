@@ -164,9 +164,11 @@ def test_llama7b_shape_reduced_depth():
     ls.close()
 
 
-def test_llama7b_full_configuration_full_depth_sampled_requests():
-    """The benchmark's own configuration -- LLaMA-7B shape, all 32 layers, the 128-slot arena with 2048-row slots
-    (its strides, its launch shapes) -- on a sample the oracle can follow: three short requests, every generated
+@pytest.mark.parametrize("make", [synth.llama_7b, synth.gpt_1p3b])
+def test_full_configuration_full_depth_sampled_requests(make):
+    """The benchmark's own configurations -- LLaMA-7B shape, all 32 layers, the 128-slot arena with 2048-row slots
+    (its strides, its launch shapes), and the GPT-1.3B shape at its 24 layers and 64 slots (fp16, biases, LayerNorm,
+    learned positions, tied output projection over 50257 columns) -- on a sample the oracle can follow: three short requests, every generated
     token's logits against the oracle at full depth.  The oracle runs the same weights with a small cache of its own
     (slots and positions used are the same on both sides).
     Tolerance: 2e-2 * sqrt(L / 16).  With 16-bit rounding points in every layer, an fp32 and an fp64 evaluation of
@@ -177,8 +179,8 @@ def test_llama7b_full_configuration_full_depth_sampled_requests():
     import dataclasses
     import paper_2305_13484_amd as fl
     from oracle import oracle as orc
-    cfg = synth.llama_7b()
-    assert (cfg.L, cfg.C, cfg.S) == (32, 128, 2048)
+    cfg = make()
+    assert (cfg.L, cfg.C, cfg.S) in ((32, 128, 2048), (24, 64, 2048))
     print(cfg.name, flush=True)
     w = synth.make_weights(cfg, 21, device="cuda")
     gpu = fl.Flover(cfg, w)
@@ -210,7 +212,7 @@ def test_llama7b_full_configuration_full_depth_sampled_requests():
         assert np.array_equal(g.finished, c.finished)
         rg, rc = gpu.reorder_evict(), cpu.reorder_evict()
         assert np.array_equal(rg.evicted, rc.evicted) and rg.moves == rc.moves
-    print("7b full depth: max rel err", max_err, "ties", ties, flush=True)
+    print(cfg.name, "full depth: max rel err", max_err, "ties", ties, flush=True)
     gpu.close()
     cpu.close()
 
