@@ -70,3 +70,11 @@ def test_gemm_slicing_is_a_function_of_the_matrix_shape_only():
                 if rows <= 128:
                     assert (Sc, kc) == (S, kbs)
     assert k_gemm_plan(0, 1000, 256) == (1, 8)          # fp32 models: one slice
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """The benchmark measures one GPU's throughput; asking for more is refused with a message, before anything touches a GPU."""
+    import subprocess
+    import sys
+    r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True, timeout=120)
+    assert r.returncode != 0 and "ONE GPU" in (r.stderr + r.stdout)
