@@ -392,6 +392,10 @@ int run_rows(flover_ctx* c, Lane& ln, const Row* rows, int n, bool want_tokens, 
     HIPCHK(c, timed_gemm(c, ln, FLOVER_PROF_GEMM_QKV, ln.h, w.wqkv, n, p_qkv, ss_qkv, mtt));
     HIPCHK(c, flk::qkv_post(f.dtype, ln.part, p_qkv.S, ss_qkv, p_qkv.ldc, w.bqkv, c->rope_cs, d_slot, d_pos, ln.q, kl, vl, n, H, nh,
                             d, f.max_seq, st));
+    if (context_pass && l == L - 1) {
+      launches += 3;
+      break;   // the pass exists to fill the cache: the last layer's K and V rows are written, nothing reads the rest
+    }
     if (context_pass) {
       HIPCHK(c, flk::prefill_attention(f.dtype, d, ln.q, kl, vl, aw, n, nh, f.max_seq, ln.att, st));
     } else {
