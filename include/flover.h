@@ -246,6 +246,21 @@ int32_t flover_k_decode_attention(int32_t dtype, const void* q, const void* kcac
                                   int32_t head_dim, int32_t S, void* out, void* workspace, uint64_t workspace_bytes,
                                   void* stream);
 
+/* flover_k_decode_attention for callers that cannot allocate device memory (code under HIP graph capture, tight
+ * serving loops, harnesses that forbid hipMalloc): same kernels, same arguments and results, but the workspace is a
+ * FLOVER_NOALLOC_SCRATCH_BYTES array inside the library's device image (one copy per GPU, held until the process ends)
+ * and the row descriptors travel as a kernel argument, so the call performs no allocation and no host-to-device copy;
+ * it only enqueues on `stream` and returns.  slot, len [host][M] are consumed before return.  The device that `stream`
+ * belongs to must be current.  Limits: M <= FLOVER_NOALLOC_MAX_ROWS and
+ * flover_k_attention_workspace_bytes(M, n_head, head_dim, max(len)) <= FLOVER_NOALLOC_SCRATCH_BYTES, else NOMEM with
+ * the sizes in flover_last_error(NULL).  Every call on a GPU uses that GPU's one array: calls that overlap on one GPU
+ * (two streams, two threads) race; calls ordered on one stream do not.  Nothing in the array has to start at zero. */
+#define FLOVER_NOALLOC_SCRATCH_BYTES (16u << 20)
+#define FLOVER_NOALLOC_MAX_ROWS 256
+int32_t flover_k_decode_attention_noalloc(int32_t dtype, const void* q, const void* kcache, const void* vcache,
+                                          const int32_t* slot, const int32_t* len, int32_t M, int32_t C, int32_t n_head,
+                                          int32_t head_dim, int32_t S, void* out, void* stream);
+
 /* Bytes of [device] workspace flover_k_compact needs for n_moves moves. */
 int32_t flover_k_compact_workspace_bytes(int32_t n_moves, uint64_t* out);
 

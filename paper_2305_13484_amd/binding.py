@@ -21,7 +21,7 @@ EXPORTED_SYMBOLS = [
     "flover_get_kv_cache", "flover_last_step_launches", "flover_step_submit", "flover_step_collect", "flover_set_layer_weights", "flover_k_gemm_plan", "flover_set_profile", "flover_get_profile", "flover_k_find_window", "flover_k_attention_workspace_bytes",
     "flover_k_decode_attention", "flover_k_compact_workspace_bytes", "flover_k_compact", "flover_k_gemm_tiled_bytes",
     "flover_k_gemm_workspace_bytes", "flover_k_gemm_retile", "flover_k_gemm", "flover_add_request_cached",
-    "flover_k_copy_probe",
+    "flover_k_copy_probe", "flover_k_decode_attention_noalloc",
 ]
 
 WEIGHT_FIELDS = ["wte", "wpe", "ln1_g", "ln1_b", "wqkv", "bqkv", "wo", "bo", "ln2_g", "ln2_b", "w1", "b1", "wu", "w2",
@@ -98,6 +98,8 @@ def load_library():
     L.flover_k_attention_workspace_bytes.argtypes = [C.c_int32] * 4 + [C.POINTER(C.c_uint64)]
     L.flover_k_decode_attention.argtypes = [C.c_int32] + [C.c_void_p] * 5 + [C.c_int32] * 5 + \
                                            [C.c_void_p, C.c_void_p, C.c_uint64, C.c_void_p]
+    L.flover_k_decode_attention_noalloc.argtypes = [C.c_int32] + [C.c_void_p] * 5 + [C.c_int32] * 5 + \
+                                                   [C.c_void_p, C.c_void_p]
     L.flover_k_compact_workspace_bytes.argtypes = [C.c_int32, C.POINTER(C.c_uint64)]
     L.flover_k_compact.argtypes = [C.c_void_p] + [C.c_int32] * 6 + [C.c_void_p] * 3 + [C.c_int32, C.c_void_p,
                                                                                      C.c_uint64, C.c_void_p]
@@ -336,6 +338,19 @@ def k_decode_attention(q: torch.Tensor, kcache: torch.Tensor, vcache: torch.Tens
                                                     vcache.data_ptr(), slot.ctypes.data, length.ctypes.data, M, Cn, nh,
                                                     d, S, out.data_ptr(), workspace.buf.data_ptr(),
                                                     workspace.buf.numel(), _stream_ptr()))
+    return out
+
+
+def k_decode_attention_noalloc(q: torch.Tensor, kcache: torch.Tensor, vcache: torch.Tensor, slot, length,
+                               out: torch.Tensor):
+    """flover_k_decode_attention_noalloc: as k_decode_attention, workspace inside the library; `out` is the caller's."""
+    M, nh, d = q.shape
+    Cn, _, S, _ = kcache.shape
+    slot, length = _i32(slot), _i32(length)
+    assert q.is_contiguous() and kcache.is_contiguous() and vcache.is_contiguous() and out.is_contiguous()
+    _check(load_library().flover_k_decode_attention_noalloc(_DT_OF[q.dtype], q.data_ptr(), kcache.data_ptr(),
+                                                            vcache.data_ptr(), slot.ctypes.data, length.ctypes.data, M,
+                                                            Cn, nh, d, S, out.data_ptr(), _stream_ptr()))
     return out
 
 

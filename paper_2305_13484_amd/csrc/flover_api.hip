@@ -1187,6 +1187,115 @@ int32_t flover_k_decode_attention(int32_t dtype, const void* q, const void* kcac
   return FLOVER_OK;
 }
 
+// ---- decode attention for callers that cannot allocate: same kernels, workspace in a file-scope device array
+}  // extern "C"
+
+// One copy per GPU that loads the library, held until the process ends.  In host code this name is only a stand-in
+// for the symbol; the device address comes from hipGetSymbolAddress (once per device) and is what the kernels get.
+static __device__ __align__(256) unsigned char scratch[FLOVER_NOALLOC_SCRATCH_BYTES];
+
+namespace {
+
+constexpr size_t kNoallocScratchBytes = (size_t)FLOVER_NOALLOC_SCRATCH_BYTES;
+constexpr int kNoallocMaxRows = FLOVER_NOALLOC_MAX_ROWS;
+constexpr int kMaxDevices = 64;
+
+std::mutex g_scratch_mu;
+void* g_scratch_ptr[kMaxDevices] = {};
+
+// Address of the current device's copy of `scratch`; looked up on the first call on that device.
+int scratch_of_current_device(void** out) {
+  int dev = -1;
+  HIPCHK(nullptr, hipGetDevice(&dev));
+  if (dev < 0 || dev >= kMaxDevices) return fail(nullptr, FLOVER_E_HIP, "device index out of range");
+  std::lock_guard<std::mutex> lock(g_scratch_mu);
+  if (!g_scratch_ptr[dev]) {
+    void* p = nullptr;
+    HIPCHK(nullptr, hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+    if (!p) return fail(nullptr, FLOVER_E_HIP, "hipGetSymbolAddress returned a null address");
+    g_scratch_ptr[dev] = p;
+  }
+  *out = g_scratch_ptr[dev];
+  return FLOVER_OK;
+}
+
+// Row descriptors travel as a kernel argument (2 KiB), so the call needs no host-to-device copy either.
+struct NoallocRows {
+  int32_t slot[kNoallocMaxRows];
+  int32_t len[kNoallocMaxRows];
+};
+
+// One block of kNoallocMaxRows threads: thread t owns row t, writes its descriptors and its (row, chunk, slot, len)
+// work items; first-item indices are an exclusive scan of the rows' chunk counts.
+__global__ __launch_bounds__(kNoallocMaxRows) void noalloc_rows_kernel(NoallocRows r, int M, int chunk, int* __restrict__ row_slot,
+                                                                       int* __restrict__ row_len, int* __restrict__ row_item0,
+                                                                       int* __restrict__ row_nchunk, int4* __restrict__ items) {
+  __shared__ int scan[kNoallocMaxRows];
+  const int t = threadIdx.x;
+  const int slot = t < M ? r.slot[t] : 0, len = t < M ? r.len[t] : 0;
+  const int nc = (len + chunk - 1) / chunk;
+  scan[t] = nc;
+  __syncthreads();
+  for (int dlt = 1; dlt < kNoallocMaxRows; dlt <<= 1) {     // inclusive scan, log steps
+    const int v = t >= dlt ? scan[t - dlt] : 0;
+    __syncthreads();
+    scan[t] += v;
+    __syncthreads();
+  }
+  if (t >= M) return;
+  const int first = scan[t] - nc;
+  row_slot[t] = slot;
+  row_len[t] = len;
+  row_item0[t] = first;
+  row_nchunk[t] = nc;
+  for (int ch = 0; ch < nc; ++ch) items[first + ch] = make_int4(t, ch, slot, len);
+}
+
+}  // namespace
+
+extern "C" {
+
+int32_t flover_k_decode_attention_noalloc(int32_t dtype, const void* q, const void* kcache, const void* vcache,
+                                          const int32_t* slot, const int32_t* len, int32_t M, int32_t C, int32_t nh,
+                                          int32_t d, int32_t S, void* out, void* stream) {
+  if (dtype < FLOVER_F32 || dtype > FLOVER_BF16) return fail(nullptr, FLOVER_E_INVAL, "bad dtype");
+  if (M < 0 || nh < 4 || nh % 4 || (d != 64 && d != 128) || S < 1 || C < 1) return fail(nullptr, FLOVER_E_INVAL, "bad shape");
+  if (M == 0) return FLOVER_OK;
+  if (!q || !kcache || !vcache || !slot || !len || !out) return fail(nullptr, FLOVER_E_INVAL, "null argument");
+  if (M > kNoallocMaxRows)
+    return fail(nullptr, FLOVER_E_NOMEM, "flover_k_decode_attention_noalloc serves at most " + std::to_string(kNoallocMaxRows) +
+                                             " rows per call; got " + std::to_string(M));
+  NoallocRows rows;
+  int max_len = 0, n_items = 0;
+  for (int i = 0; i < M; ++i) {
+    if (len[i] < 1 || len[i] > S || slot[i] < 0 || slot[i] >= C) return fail(nullptr, FLOVER_E_INVAL, "slot / len out of range");
+    rows.slot[i] = slot[i];
+    rows.len[i] = len[i];
+    max_len = std::max(max_len, len[i]);
+    n_items += (len[i] + flk::attn_chunk() - 1) / flk::attn_chunk();
+  }
+  for (int i = M; i < kNoallocMaxRows; ++i) rows.slot[i] = rows.len[i] = 0;
+  size_t o_items, o_pml, o_po;
+  const size_t need = attn_ws_layout(M, nh, d, max_len, &o_items, &o_pml, &o_po);
+  if (need > kNoallocScratchBytes)
+    return fail(nullptr, FLOVER_E_NOMEM, "attention workspace of " + std::to_string(need) + " bytes exceeds the built-in scratch of " +
+                                             std::to_string(kNoallocScratchBytes) + " bytes: fewer rows or shorter lengths per call");
+  void* base = nullptr;
+  int rc = scratch_of_current_device(&base);
+  if (rc != FLOVER_OK) return rc;
+  char* ws = (char*)base;
+  int* ds = (int*)ws;
+  hipStream_t st = (hipStream_t)stream;
+  // every part of the scratch this call reads is written first by this call's own kernels: nothing has to start at zero
+  noalloc_rows_kernel<<<1, kNoallocMaxRows, 0, st>>>(rows, M, flk::attn_chunk(), ds, ds + M, ds + 2 * M, ds + 3 * M,
+                                                     (int4*)(ws + o_items));
+  HIPCHK(nullptr, hipGetLastError());
+  flk::AttnWork aw{(const int4*)(ws + o_items), ds, ds + M, ds + 2 * M, ds + 3 * M, (float*)(ws + o_pml), (float*)(ws + o_po),
+                   n_items, flk::attn_chunk()};
+  HIPCHK(nullptr, flk::decode_attention(dtype, d, q, kcache, vcache, aw, M, nh, S, out, st));
+  return FLOVER_OK;
+}
+
 int32_t flover_k_compact_workspace_bytes(int32_t n_moves, uint64_t* out) {
   if (n_moves < 0 || !out) return fail(nullptr, FLOVER_E_INVAL, "bad argument");
   *out = align_up((size_t)std::max(n_moves, 1) * sizeof(int4), 256);
