@@ -90,6 +90,7 @@ struct flover_ctx {
   flover_config cfg;
   hipStream_t st;
   std::string err;
+  std::mutex err_mu;                 // the two lanes may fail at the same time (see fail())
   // weights in the arena
   std::vector<LayerW> lw;
   std::vector<bool> layer_loaded;
@@ -122,6 +123,8 @@ struct flover_ctx {
   hipEvent_t moves_ev[kStageRing] = {nullptr, nullptr, nullptr, nullptr};
   bool moves_busy[kStageRing] = {false, false, false, false};
   int moves_next = 0;
+  hipEvent_t compact_ev = nullptr;   // end of the most recent shuffle copy on the iteration's stream
+  bool compact_pending = false;      // ... recorded and not yet known to be complete
   std::vector<hipEvent_t> prep_ev;   // one per slot: the slot's context cache is complete
   mutable std::mutex mu;             // scheduler state; see flover.h for which calls may run concurrently
   // scheduler
@@ -145,9 +148,15 @@ struct flover_ctx {
 
 namespace {
 
+// Records the message of a failing call.  A context's message has its own lock: with asynchronous pre-processing the
+// thread in flover_add_request and the thread in flover_step can both fail while the scheduler lock is released.
 int fail(flover_ctx* c, int code, const std::string& msg) {
-  if (c) c->err = msg;
-  else g_err = msg;
+  if (c) {
+    std::lock_guard<std::mutex> lock(c->err_mu);
+    c->err = msg;
+  } else {
+    g_err = msg;
+  }
   return code;
 }
 #define HIPCHK(ctx, expr)                                                                        \
@@ -449,6 +458,9 @@ int preprocess(flover_ctx* c, int slot, const Waiting& r) {
   const int P = (int)r.prompt.size();
   if (async && !c->inflight.empty())   // a submitted iteration may still read the slot's previous tenant
     HIPCHK(c, hipStreamWaitEvent(ln.st, c->step_lane.done[c->inflight.back().ring], 0));
+  // ... and so may a shuffle copy enqueued after that iteration: the slot handed out here is often the one a move has
+  // just vacated, and with iterations outstanding flover_reorder_evict does not wait for its copy
+  if (async && c->compact_pending) HIPCHK(c, hipStreamWaitEvent(ln.st, c->compact_ev, 0));
   std::vector<Row> rows;
   for (int p0 = 0; p0 + 1 < P; p0 += c->rows_cap) {
     const int n = std::min(c->rows_cap, P - 1 - p0);
@@ -564,6 +576,7 @@ void release(flover_ctx* c) {
     if (c->h_moves_ring[i]) (void)hipHostFree(c->h_moves_ring[i]);
     if (c->moves_ev[i]) (void)hipEventDestroy(c->moves_ev[i]);
   }
+  if (c->compact_ev) (void)hipEventDestroy(c->compact_ev);
   for (hipEvent_t e : c->prep_ev)
     if (e) (void)hipEventDestroy(e);
   for (hipEvent_t e : c->ev) (void)hipEventDestroy(e);
@@ -651,6 +664,7 @@ int32_t flover_init(const flover_config* cfg, const flover_weights* w, flover_ct
       HIPTRY(hipHostMalloc((void**)&pl.h_stage[i], c->stage_ints * 4, hipHostMallocDefault));
       HIPTRY(hipEventCreateWithFlags(&pl.staged[i], hipEventDisableTiming));
     }
+    HIPTRY(hipEventCreateWithFlags(&c->compact_ev, hipEventDisableTiming));
     c->prep_ev.assign(cfg->max_concurrency, nullptr);
     for (int i = 0; i < cfg->max_concurrency; ++i) HIPTRY(hipEventCreateWithFlags(&c->prep_ev[i], hipEventDisableTiming));
   }
@@ -1036,7 +1050,11 @@ int32_t flover_reorder_evict(flover_ctx* c, flover_reorder_out* out) {
         if (pi >= 0) (void)hipEventRecord(c->ev[2 * pi + 1], c->st);
         if (!piped) {
           HIPCHK(c, hipStreamSynchronize(c->st));   // following iterations wait until memory is in order (Section V-D)
+          c->compact_pending = false;
           prof_collect(c);
+        } else if (c->compact_ev) {                 // the pre-processing stream orders itself behind the copy
+          HIPCHK(c, hipEventRecord(c->compact_ev, c->st));
+          c->compact_pending = true;
         }
       }
       c->lo = old_lo + off;
@@ -1087,6 +1105,7 @@ int32_t flover_get_kv_cache(const flover_ctx* c, void** base, uint64_t* bytes) {
 
 int32_t flover_set_profile(flover_ctx* c, int32_t level) {
   if (!c || level < 0 || level > 2) return fail(c, FLOVER_E_INVAL, "profile level must be 0, 1 or 2");
+  std::lock_guard<std::mutex> lock(c->mu);
   c->profile = level;
   for (int k = 0; k < FLOVER_PROF_KINDS; ++k) {
     c->prof_ms[k] = 0;
@@ -1098,6 +1117,7 @@ int32_t flover_set_profile(flover_ctx* c, int32_t level) {
 
 int32_t flover_get_profile(const flover_ctx* c, int32_t kind, double* ms, int64_t* launches, int64_t* bytes) {
   if (!c || kind < 0 || kind >= FLOVER_PROF_KINDS) return FLOVER_E_INVAL;
+  std::lock_guard<std::mutex> lock(c->mu);
   if (ms) *ms = c->prof_ms[kind];
   if (launches) *launches = c->prof_launches[kind];
   if (bytes) *bytes = c->prof_bytes[kind];

@@ -636,3 +636,52 @@ def test_pipelined_stress_with_a_waiting_queue(async_pre):
         assert ref[0][r.req_id] == got[0][r.req_id], r.req_id
         assert len(got[0][r.req_id]) == r.gen_len
     assert st["moves"] > 0 and st["max_outstanding"] == 3
+
+
+def test_context_pass_waits_for_the_shuffle_copy_that_vacated_its_slot():
+    """Asynchronous pre-processing + pipelined iterations: a request that takes the slot a move has just vacated must
+    not have its context written before the shuffle copy has read that slot.  The copy is held back on the
+    iteration's stream by a long-running operation enqueued just before flover_reorder_evict, so a context pass that
+    did not order itself behind the copy would overwrite the moved request's rows first; the moved request's logits
+    are compared bit for bit with a plain synchronous run."""
+    import paper_2305_13484_amd as fl
+    cfg = dataclasses.replace(synth.small_llama16(synth.DT_BF16), C=4)
+    w = to_device(synth.make_weights(cfg, 71))
+    rng = np.random.default_rng(72)
+    mk = lambda rid, at, P, G: synth.Request(rid, at, rng.integers(0, cfg.V, size=P).astype(np.int32), G)
+    reqs = [mk(0, 0, 10, 12), mk(1, 0, 10, 2), mk(2, 0, 10, 12), mk(3, 0, 120, 12), mk(4, 2, 40, 5)]
+    ref = gpu_run_stream(cfg, w, reqs)
+    srv = fl.Flover(cfg, w, async_preprocess=True)
+    bufs = [torch.empty((cfg.C, cfg.V), dtype=torch.float32, device="cuda") for _ in range(3)]
+    big = torch.randn((6144, 6144), device="cuda")
+    toks, logits = {}, {}
+
+    def collect(buf):
+        out = srv.step_collect()
+        for j in range(out.n_live):
+            rid = int(out.req_id[j])
+            toks.setdefault(rid, []).append(int(out.token[j]))
+            logits.setdefault(rid, []).append(buf[j].clone())
+        return int(out.finished.sum())
+
+    for r in reqs[:4]:
+        srv.add_request(r.req_id, r.prompt, r.gen_len)
+    torch.cuda.synchronize()                          # all four context caches complete: they join together
+    assert srv.step_submit(bufs[0]) == 4
+    assert srv.reorder_evict().moves == []
+    assert srv.step_submit(bufs[1]) == 4             # request 1 ends with this iteration
+    for _ in range(6):                                # tens of milliseconds of work ahead of the shuffle copy
+        big = (big @ big) * 1e-4
+    rr = srv.reorder_evict()
+    assert rr.moves == [(3, 1)]                       # the long request moves into the hole; slot 3 is vacated ...
+    assert srv.add_request(4, reqs[4].prompt, reqs[4].gen_len) == 3       # ... and handed out again at once
+    done = collect(bufs[0]) + collect(bufs[1])
+    k = 2
+    while done < len(reqs):
+        n = srv.step_submit(bufs[k % 3])
+        srv.reorder_evict()
+        if n:
+            done += collect(bufs[k % 3])
+            k += 1
+    srv.close()
+    _same_results(ref, (toks, logits), reqs)
