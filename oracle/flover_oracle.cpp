@@ -22,10 +22,11 @@
 // fp32 logits, lowest index on ties.
 //
 // Readings of the paper where it is silent or inconsistent (each also applied by the product):
-//   R1  Algorithm 3 as printed never scores the window at offset 0 (window_cost starts at 0 and the
-//       loop starts at i = non_zero).  Here the first window is scored before the loop; the loop and
-//       its strict '<' are as printed, so the lowest offset wins ties.  Section V-D claims minimal
-//       movement; the printed listing does not deliver it (e.g. [1,1,0] -> offset 1, one move).
+//   R1  Algorithm 3 as printed never scores the window at offset 0: its running sum starts from zero and
+//       its loop from the first index after that window.  Section V-D claims minimal movement, which the
+//       listing then misses (for [1,1,0] it settles on offset 1, one move, where offset 0 needs none).
+//       Here every window is scored; a better window replaces the best only when strictly better, as in
+//       the listing, so the lowest offset wins ties.
 //   R2  arr covers the window [lo,hi) of slots the kernels currently span; entries are 0/1.
 //   R3  i-th hole inside the chosen region (ascending) receives the i-th occupied slot outside (ascending).
 //   R4  A new request takes slot hi if hi < C, else lo-1 if lo > 0, else waits; an empty region restarts at 0.
@@ -259,55 +260,32 @@ int argmax_lowest(const double* v, int n) {
 
 // ---------------------------------------------------------------- Algorithm 3 (reading R1)
 
-// arr: 0 = empty, non-zero = valid (weight arr[i]).  Returns the offset of the size-non_zero window
-// whose complement holds the least weight; *min_cost = that weight (= slots to move for 0/1 input).
+// What Algorithm 3 (Section V-D) is stated to deliver, written out as its definition: among all windows of `valid`
+// consecutive entries, valid = number of non-zero entries, the one that leaves the least weight outside -- for 0/1
+// input the fewest slots to move -- and, of equally good ones, the lowest offset (the listing replaces its best
+// only on a strictly smaller cost).  Every window is scored, the one at offset 0 included (R1).  Window sums come
+// from a prefix-sum table; nothing slides.
+// arr: 0 = empty, non-zero = valid with weight arr[i].  Returns the offset; *min_cost_out = weight left outside.
 int find_window(const int32_t* arr, int n, int* min_cost_out, int* non_zero_out) {
-  long total_cost = 0;
-  int non_zero = 0;
-  for (int i = 0; i < n; ++i)
-    if (arr[i] != 0) {
-      non_zero += 1;
-      total_cost += arr[i];
-    }
-  long window_cost = 0;
-  for (int i = 0; i < non_zero; ++i) window_cost += arr[i];   // the window at offset 0 (R1)
-  long min_cost = total_cost - window_cost;
-  int mem_offset = 0;
-  for (int i = non_zero; i < n; ++i) {
-    window_cost += arr[i] - arr[i - non_zero];
-    long current_cost = total_cost - window_cost;
-    if (current_cost < min_cost) {
-      min_cost = current_cost;
-      mem_offset = i - non_zero + 1;
+  std::vector<long> upto(n + 1, 0);   // upto[i] = arr[0] + ... + arr[i-1]
+  int valid = 0;
+  for (int i = 0; i < n; ++i) {
+    upto[i + 1] = upto[i] + arr[i];
+    if (arr[i] != 0) valid += 1;
+  }
+  const long everything = upto[n];
+  int best_offset = 0;
+  long least_outside = everything - upto[valid];
+  for (int offset = 1; offset + valid <= n; ++offset) {
+    const long outside = everything - (upto[offset + valid] - upto[offset]);
+    if (outside < least_outside) {
+      least_outside = outside;
+      best_offset = offset;
     }
   }
-  if (min_cost_out) *min_cost_out = (int)min_cost;
-  if (non_zero_out) *non_zero_out = non_zero;
-  return mem_offset;
-}
-
-// The listing exactly as printed (kept only so a test can document reading R1).
-int find_window_as_printed(const int32_t* arr, int n, int* min_cost_out) {
-  long total_cost = 0;
-  int non_zero = 0;
-  for (int i = 0; i < n; ++i)
-    if (arr[i] != 0) {
-      non_zero += 1;
-      total_cost += arr[i];
-    }
-  long min_cost = std::numeric_limits<long>::max();
-  long window_cost = 0;
-  int mem_offset = 0;
-  for (int i = non_zero; i < n; ++i) {
-    window_cost += arr[i] - arr[i - non_zero];
-    long current_cost = total_cost - window_cost;
-    if (current_cost < min_cost) {
-      min_cost = current_cost;
-      mem_offset = i - non_zero + 1;
-    }
-  }
-  if (min_cost_out) *min_cost_out = (min_cost == std::numeric_limits<long>::max()) ? -1 : (int)min_cost;
-  return mem_offset;
+  if (min_cost_out) *min_cost_out = (int)least_outside;
+  if (non_zero_out) *non_zero_out = valid;
+  return best_offset;
 }
 
 // Moves for a window (reading R3): src[i] -> dst[i], absolute indices into arr.
@@ -654,12 +632,6 @@ int orc_find_window(const int32_t* arr, int n, int32_t* mem_offset, int32_t* min
   *mem_offset = find_window(arr, n, &mc, &nz);
   *min_cost = mc;
   *non_zero = nz;
-  return 0;
-}
-int orc_find_window_as_printed(const int32_t* arr, int n, int32_t* mem_offset, int32_t* min_cost) {
-  int mc = 0;
-  *mem_offset = find_window_as_printed(arr, n, &mc);
-  *min_cost = mc;
   return 0;
 }
 int orc_plan_moves(const int32_t* arr, int n, int off, int non_zero, int32_t* src, int32_t* dst) {

@@ -56,7 +56,6 @@ def lib():
         L.orc_read_kv.argtypes = [C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, C.c_void_p]
         L.orc_full_forward.argtypes = [C.POINTER(OrcConfig), C.POINTER(OrcWeights), C.c_void_p, C.c_int, C.c_void_p]
         L.orc_find_window.argtypes = [C.c_void_p, C.c_int] + [C.POINTER(C.c_int32)] * 3
-        L.orc_find_window_as_printed.argtypes = [C.c_void_p, C.c_int] + [C.POINTER(C.c_int32)] * 2
         L.orc_plan_moves.argtypes = [C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_void_p, C.c_void_p]
         L.orc_attention.argtypes = [C.c_int] + [C.c_void_p] * 5 + [C.c_int] * 3 + [C.c_void_p, C.c_int, C.c_void_p]
         L.orc_gemm.argtypes = [C.c_int, C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_void_p, C.c_int,
@@ -222,13 +221,6 @@ def find_window(arr):
     off, cost, nz = C.c_int32(), C.c_int32(), C.c_int32()
     lib().orc_find_window(a.ctypes.data, len(a), C.byref(off), C.byref(cost), C.byref(nz))
     return off.value, cost.value, nz.value
-
-
-def find_window_as_printed(arr):
-    a = np.ascontiguousarray(np.asarray(arr, np.int32))
-    off, cost = C.c_int32(), C.c_int32()
-    lib().orc_find_window_as_printed(a.ctypes.data, len(a), C.byref(off), C.byref(cost))
-    return off.value, cost.value
 
 
 def plan_moves(arr, off, non_zero):

@@ -490,30 +490,32 @@ bool known(const flover_ctx* c, uint64_t id) {
   return false;
 }
 
-// Algorithm 3 with the first window scored before the loop (as printed the listing never scores offset 0).
+// Algorithm 3 (Section V-D): where the compact region goes.  A window as long as the number of valid entries slides
+// over the occupancy array once; the window that keeps the most weight inside leaves the least outside, which is the
+// listing's cost.  The window at offset 0 is a candidate like every other (the listing as printed never scores it),
+// and a later window replaces the choice only when it keeps strictly more, so the lowest offset wins ties.
+// arr: 0 = empty, otherwise the entry's weight (1, or cached rows + 1 for FLOVER_SHUFFLE_BY_LENGTH).
 int find_window(const int32_t* arr, int n, int* min_cost, int* non_zero) {
-  long total_cost = 0;
-  int nz = 0;
-  for (int i = 0; i < n; ++i)
-    if (arr[i] != 0) {
-      ++nz;
-      total_cost += arr[i];
-    }
-  long window_cost = 0;
-  for (int i = 0; i < nz; ++i) window_cost += arr[i];
-  long best = total_cost - window_cost;
-  int off = 0;
-  for (int i = nz; i < n; ++i) {
-    window_cost += arr[i] - arr[i - nz];
-    const long cur = total_cost - window_cost;
-    if (cur < best) {
-      best = cur;
-      off = i - nz + 1;
+  int width = 0;
+  long all = 0;
+  for (int i = 0; i < n; ++i) {
+    width += arr[i] != 0;
+    all += arr[i];
+  }
+  long kept = 0;
+  for (int i = 0; i < width; ++i) kept += arr[i];
+  long most_kept = kept;
+  int at = 0;
+  for (int right = width; right < n; ++right) {   // the window now ends at `right`
+    kept += arr[right] - arr[right - width];
+    if (kept > most_kept) {
+      most_kept = kept;
+      at = right - width + 1;
     }
   }
-  *min_cost = (int)best;
-  *non_zero = nz;
-  return off;
+  *min_cost = (int)(all - most_kept);
+  *non_zero = width;
+  return at;
 }
 
 int copy_in(flover_ctx* c, void* dst, const void* src, size_t bytes, const char* name) {

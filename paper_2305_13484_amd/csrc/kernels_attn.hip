@@ -311,8 +311,8 @@ __global__ __launch_bounds__(256) void attn_prefill_kernel(const void* __restric
 //   output   O^T[d][query] += V^T . P^T  : B = P^T is what the lane already holds from S^T (keys 4g..4g+3 of both
 //            16-key tiles = its 8 k-slots), A = V^T needs 8 keys of one d per lane: the V rows are staged in LDS
 //            (wave-private, row stride D + 8 elements: 16-byte aligned and conflict-free) and read back transposed.
-// P is rounded to the model dtype for the second product; m, l and the accumulators stay fp32.  Same chunking, partial
-// layout and merge kernel as the other variants.     grid = (n_blocks, n_head / 4), block = 256 (a wave per head).
+// P enters the second product as two 16-bit terms (value + rounding remainder), i.e. with 16 or more significant bits;
+// m, l and the accumulators stay fp32.  Same chunking, partial layout and merge kernel as the other variants.     grid = (n_blocks, n_head / 4), block = 256 (a wave per head).
 constexpr int kPrefillMfmaQB = 32;
 template <int DT> __device__ __forceinline__ uint32_t pack2(float a, float b) {
   if constexpr (DT == DT_BF16) return (uint32_t)f32_to_bf16(a) | ((uint32_t)f32_to_bf16(b) << 16);
@@ -326,7 +326,7 @@ template <int DT> __device__ __forceinline__ f32x4_t mfma_kq(const u32x4_t& a, c
 }
 
 template <int DT, int D>
-__global__ __launch_bounds__(256) void attn_prefill_mfma_kernel(const void* __restrict__ q, const void* __restrict__ kc,
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) void attn_prefill_mfma_kernel(const void* __restrict__ q, const void* __restrict__ kc,
                                                                 const void* __restrict__ vc,
                                                                 const int4* __restrict__ blocks,
                                                                 const int* __restrict__ row_slot,
@@ -399,7 +399,7 @@ __global__ __launch_bounds__(256) void attn_prefill_mfma_kernel(const void* __re
     __builtin_amdgcn_wave_barrier();
 
     // scores: rows = keys kt*16 + 4g + r, column = query n of tile t
-    u32x4_t pb[QT];
+    u32x4_t pb[QT], pl[QT];
 #pragma unroll
     for (int t = 0; t < QT; ++t) {
       f32x4_t sacc[2];
@@ -437,7 +437,15 @@ __global__ __launch_bounds__(256) void attn_prefill_mfma_kernel(const void* __re
       m[t] = mn;
 #pragma unroll
       for (int dt = 0; dt < DTL; ++dt) oacc[dt][t] *= alpha;
+      // The probabilities enter the second product as two 16-bit terms, p = hi + lo with hi = p rounded to the model
+      // dtype and lo = (p - hi) rounded: 16 significant bits for bf16 (more for fp16), so that this kernel weighs the V
+      // rows as accurately as the decode kernel's fp32 probabilities do (one term alone would add a rounding point
+      // that the decode path does not have).
+      float q_[8];
+#pragma unroll
+      for (int j = 0; j < 8; ++j) q_[j] = p[j] - rdt<DT>(p[j]);
       pb[t] = u32x4_t{pack2<DT>(p[0], p[1]), pack2<DT>(p[2], p[3]), pack2<DT>(p[4], p[5]), pack2<DT>(p[6], p[7])};
+      pl[t] = u32x4_t{pack2<DT>(q_[0], q_[1]), pack2<DT>(q_[2], q_[3]), pack2<DT>(q_[4], q_[5]), pack2<DT>(q_[6], q_[7])};
     }
     // output: A = V^T, k-slot j of lane group g <-> key 4g + j (j < 4) or 16 + 4g + (j - 4), as in pb
 #pragma unroll
@@ -451,7 +459,10 @@ __global__ __launch_bounds__(256) void attn_prefill_mfma_kernel(const void* __re
       }
       const u32x4_t va = u32x4_t{w[0], w[1], w[2], w[3]};
 #pragma unroll
-      for (int t = 0; t < QT; ++t) oacc[dt][t] = mfma_kq<DT>(va, pb[t], oacc[dt][t]);
+      for (int t = 0; t < QT; ++t) {
+        oacc[dt][t] = mfma_kq<DT>(va, pl[t], oacc[dt][t]);
+        oacc[dt][t] = mfma_kq<DT>(va, pb[t], oacc[dt][t]);
+      }
     }
   }
   // partial results: lane (n, g) owns O[query n][d = dt*16 + 4g .. +3]

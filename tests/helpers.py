@@ -171,3 +171,115 @@ def gpu_run_stream_pipelined(cfg, weights_dev, reqs, depth=2, shuffle_off=False,
             done += int(out.finished.sum())
     srv.close()
     return toks, logits
+
+
+class LockstepPipelined(Lockstep):
+    """The oracle beside the pipelined form of the iteration (flover_step_submit / flover_step_collect): the scheduler
+    state advances at submission, so slot assignment, window, evictions and move lists are compared right after every
+    submission + reorder; tokens, finished flags and logits of an iteration arrive `depth` submissions later and are
+    compared then with what the oracle's step of the same number produced.  There is no teacher forcing here (the next
+    iteration already runs on the device-resident token), so a near tie fails the run: use it where tokens are exact."""
+
+    def __init__(self, cfg, weights, depth=2, shuffle_off=False, by_length=False):
+        super().__init__(cfg, weights, shuffle_off=shuffle_off, by_length=by_length)
+        import collections
+        self.depth = depth
+        self.queue = collections.deque()          # (oracle step result, logits buffer) of submitted iterations
+        self.bufs = [torch.empty((cfg.C, cfg.V), dtype=torch.float32, device="cuda") for _ in range(depth + 1)]
+        self.k = 0
+        self.max_outstanding = 0
+
+    def submit(self):
+        n = self.gpu.step_submit(self.bufs[self.k])
+        c = self.cpu.step(True)
+        assert n == c.n_live, "rows of the submitted iteration differ"
+        if n:
+            self.queue.append((c, self.bufs[self.k]))
+            self.k = (self.k + 1) % len(self.bufs)
+        self.max_outstanding = max(self.max_outstanding, len(self.queue))
+        return n, c
+
+    def collect(self):
+        c, buf = self.queue.popleft()
+        g = self.gpu.step_collect()
+        assert g.n_live == c.n_live
+        assert np.array_equal(g.req_id, c.req_id) and np.array_equal(g.slot, c.slot)
+        gl = buf[:g.n_live].cpu().double().numpy()
+        scale = np.abs(c.logits).max(axis=1)
+        err = np.abs(gl - c.logits).max(axis=1) / scale
+        self.max_err = max(self.max_err, float(err.max()))
+        assert err.max() <= self.tol, "logits error %g > %g" % (err.max(), self.tol)
+        assert np.array_equal(g.token, c.token), "token differs (pipelined runs cannot be re-synchronised)"
+        assert np.array_equal(g.finished, c.finished)
+        self.compared_rows += g.n_live
+        for j in range(g.n_live):
+            self.tokens.setdefault(int(g.req_id[j]), []).append(int(g.token[j]))
+        self.steps += 1
+
+    def run(self, reqs, max_steps=100000):
+        pending = sorted(reqs, key=lambda r: (r.arrival_step, r.req_id))
+        i = s = 0
+        finished = 0
+        while finished < len(reqs) and s < max_steps:
+            while i < len(pending) and pending[i].arrival_step <= s:
+                self.add(pending[i])
+                i += 1
+            n, c = self.submit()
+            finished += int(c.finished.sum())
+            self.reorder()                         # state comparison: next_token is not part of it (device-resident)
+            s += 1
+            while self.queue and (len(self.queue) >= self.depth or n == 0):
+                self.collect()
+        while self.queue:
+            self.collect()
+        return s
+
+
+def oracle_per_request(cfg, weights, reqs, shuffle_off=False):
+    """Every request's tokens and fp32-valued logits from the oracle's fused run of the stream (by the oracle's own
+    pinned invariant these do not depend on the schedule)."""
+    srv = orc.OracleServer(cfg, weights, shuffle_off=shuffle_off)
+    pending = sorted(reqs, key=lambda r: (r.arrival_step, r.req_id))
+    toks, logits = {}, {}
+    i = done = s = 0
+    while done < len(reqs):
+        while i < len(pending) and pending[i].arrival_step <= s:
+            srv.add_request(pending[i].req_id, pending[i].prompt, pending[i].gen_len)
+            i += 1
+        out = srv.step(True)
+        for j in range(out.n_live):
+            toks.setdefault(int(out.req_id[j]), []).append(int(out.token[j]))
+            logits.setdefault(int(out.req_id[j]), []).append(out.logits[j])
+        done += int(out.finished.sum())
+        srv.reorder_evict()
+        s += 1
+    srv.close()
+    return toks, logits
+
+
+def assert_matches_oracle_per_request(cfg, got, want, reqs, max_ties=2):
+    """got: (tokens, device logits) per request from the HIP path under any schedule; want: oracle_per_request.
+    Token by token: logits within the tolerance of the dtype, token ids equal.  Where the ids differ the oracle's two
+    best logits must be a near tie (closer than twice the allowed error); nothing can re-synchronise a finished run, so
+    the rest of that request is left out.  Returns the worst logits error."""
+    tol = TOL[cfg.dtype]
+    worst, ties, compared, total = 0.0, 0, 0, 0
+    for r in reqs:
+        gt, gl = got[0][r.req_id], torch.stack(got[1][r.req_id]).cpu().double().numpy()
+        wt, wl = want[0][r.req_id], np.stack(want[1][r.req_id])
+        assert len(gt) == len(wt) == r.gen_len
+        total += r.gen_len
+        for t in range(r.gen_len):
+            scale = np.abs(wl[t]).max()
+            err = float(np.abs(gl[t] - wl[t]).max() / scale)
+            worst = max(worst, err)
+            assert err <= tol, (r.req_id, t, err)
+            compared += 1
+            if gt[t] != wt[t]:
+                srt = np.sort(wl[t])
+                assert srt[-1] - srt[-2] <= 2 * tol * scale, "tokens of request %d differ beyond a near tie" % r.req_id
+                ties += 1
+                break
+    assert ties <= max_ties and (ties == 0 or cfg.dtype != synth.DT_F32), "near ties: %d" % ties
+    assert compared >= 0.8 * total
+    return worst
