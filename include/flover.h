@@ -96,7 +96,6 @@ int32_t flover_query_arena_bytes(const flover_config* cfg, uint64_t* out_bytes);
  * Errors: INVAL (bad shape / NULL required weight / misaligned arena), NOMEM (arena too small), HIP. */
 int32_t flover_init(const flover_config* cfg, const flover_weights* w, flover_ctx** out_ctx);
 
-/* Waits for the stream, releases host resources.  The arena is the caller's. */
 /* Layer-by-layer hand-over, for models whose natural-layout copy would not fit in device memory beside the arena
  * (the Buffer Manager sizes everything from the model configuration, Section V-A; the 30B shape holds 65 GB of weights).
  * flover_init with EVERY per-layer pointer of `weights` NULL (ln1_g .. b2; the global tensors wte, wpe, lnf_*, wlm are
@@ -106,6 +105,8 @@ int32_t flover_init(const flover_config* cfg, const flover_weights* w, flover_ct
  * may be set again while no request is in flight.  Errors: INVAL (layer out of range, missing tensor), STATE, HIP. */
 int32_t flover_set_layer_weights(flover_ctx* ctx, int32_t layer, const flover_weights* w);
 
+/* Waits for the library's streams, releases what the context owns on the host (staging, events, the pre-processing
+ * stream).  The arena is the caller's and is not touched.  ctx == NULL is a no-op. */
 int32_t flover_destroy(flover_ctx* ctx);
 
 /* Text of the last error on ctx (ctx == NULL: of the calling thread's last failed flover_init / query /
@@ -184,17 +185,11 @@ int32_t flover_step_collect(flover_ctx* ctx, flover_step_out* out);
  * With FLOVER_SHUFFLE_OFF only the empty ends of the window are dropped.  Safe to call after every step. */
 int32_t flover_reorder_evict(flover_ctx* ctx, flover_reorder_out* out);
 
-/* Measurement hook (not in the paper): like flover_add_request, but the slot's context cache (KV rows
- * [0, context_len)) is taken to be whatever the slot already holds -- no pre-processing kernels run.  The request
- * feeds next_token at position context_len in the next flover_step.  Meant for profiler runs in which every launch
- * must be a fused-iteration launch; results are meaningless numerically unless the caller filled the cache.
- * Errors: INVAL (context_len < 0, context_len + 1 + max_new_tokens > max_seq, bad token, duplicate id),
- * FULL (no adjacent slot free or requests already waiting; this call never queues). */
-int32_t flover_add_request_cached(flover_ctx* ctx, uint64_t req_id, int32_t context_len, int32_t next_token,
-                                  int32_t max_new_tokens, int32_t* out_slot);
+/* ------------------------------------------------------------------ inspection and test hooks (not in the paper)
+ * Read-only views of the scheduler and the cache, and two hooks that let a test steer a stream. */
 
-/* Test / benchmark hooks (not in the paper): end a request as if it had produced EOS; overwrite the token a
- * live request feeds in the next iteration (teacher forcing, to re-synchronise a comparison after a near tie). */
+/* End a request as if it had produced EOS; overwrite the token a live request feeds in the next iteration
+ * (teacher forcing, to re-synchronise a comparison after a near tie). */
 int32_t flover_mark_finished(flover_ctx* ctx, uint64_t req_id);
 int32_t flover_set_next_token(flover_ctx* ctx, uint64_t req_id, int32_t token);
 
@@ -212,18 +207,35 @@ int32_t flover_get_kv_cache(const flover_ctx* ctx, void** base, uint64_t* bytes)
  * requests are live). */
 int32_t flover_last_step_launches(const flover_ctx* ctx, int32_t* n);
 
+/* ------------------------------------------------------------------ measurement hooks (not in the paper)
+ * Used by the benchmark and by profiler runs only; nothing in the method depends on them. */
+
+/* Like flover_add_request, but the slot's context cache (KV rows
+ * [0, context_len)) is taken to be whatever the slot already holds -- no pre-processing kernels run.  The request
+ * feeds next_token at position context_len in the next flover_step.  Meant for profiler runs in which every launch
+ * must be a fused-iteration launch; results are meaningless numerically unless the caller filled the cache.
+ * Errors: INVAL (context_len < 0, context_len + 1 + max_new_tokens > max_seq, bad token, duplicate id),
+ * FULL (no adjacent slot free or requests already waiting; this call never queues). */
+int32_t flover_add_request_cached(flover_ctx* ctx, uint64_t req_id, int32_t context_len, int32_t next_token,
+                                  int32_t max_new_tokens, int32_t* out_slot);
+
 /* Kernel timing with HIP events on the context's stream (measurement aid, not in the paper).
- * level 0 = off, 1 = the attention streaming kernel of one layer in four (layers 0, 4, 8, ...: two event records per
- * launch cost about as much as a small kernel, and the layers' launches are alike), 2 = the attention kernel of every
- * layer and every weight GEMM; the shuffle copy is timed at levels 1 and 2.  Iterations submitted with
- * flover_step_submit are timed too (added up when they are collected).  Setting the level clears the totals.
- * flover_get_profile returns, for one kind, the summed duration (ms), the number of TIMED launches and the summed
- * algorithmic bytes of those launches: for attention the K and V
- * rows [0,len) of every row; for a GEMM the weight matrix; for the shuffle copy bytes read + written. */
+ * level 0 = off; 1 = sampled: the attention streaming kernel of one layer in four (layers 0, 4, 8, ...) in every
+ * iteration, and in every second iteration the four weight GEMMs of the middle layer (n_layer / 2) and the output
+ * projection -- two event records per launch cost about as much as a small kernel, and the layers' launches are alike;
+ * 2 = the attention kernel of every layer and every weight GEMM.  The shuffle copy is timed at levels 1 and 2.
+ * Iterations submitted with flover_step_submit are timed too (added up when they are collected).  Setting the level
+ * clears the totals.  flover_get_profile returns, for one kind, the summed duration (ms), the number of TIMED launches
+ * and the summed algorithmic bytes of those launches: for attention the K and V rows [0,len) of every row; for a GEMM
+ * the weight matrix; for the shuffle copy bytes read + written. */
 enum { FLOVER_PROF_ATTENTION = 0, FLOVER_PROF_GEMM_QKV = 1, FLOVER_PROF_GEMM_OUT = 2, FLOVER_PROF_GEMM_FF1 = 3,
        FLOVER_PROF_GEMM_FF2 = 4, FLOVER_PROF_GEMM_LM = 5, FLOVER_PROF_COMPACT = 6, FLOVER_PROF_KINDS = 7 };
 int32_t flover_set_profile(flover_ctx* ctx, int32_t level);
 int32_t flover_get_profile(const flover_ctx* ctx, int32_t kind, double* ms, int64_t* launches, int64_t* bytes);
+
+/* Plain device-to-device copy kernel of a known size (bytes % 16 == 0): the reference against which profiler byte
+ * counters (FETCH_SIZE / WRITE_SIZE) are scaled.  Measurement aid only. */
+int32_t flover_k_copy_probe(void* dst, const void* src, uint64_t bytes, void* stream);
 
 /* ------------------------------------------------------------------ operation-level entry points
  * The same kernels the step uses, callable on caller-owned buffers (micro-benchmarks, unit parity).
@@ -289,10 +301,6 @@ int32_t flover_k_gemm_workspace_bytes(int32_t dtype, int32_t M, int32_t N, int32
 int32_t flover_k_gemm_retile(int32_t dtype, const void* W, int32_t N, int32_t K, void* w_tiled, void* stream);
 int32_t flover_k_gemm(int32_t dtype, const void* x, const void* w_tiled, int32_t M, int32_t N, int32_t K, float* y,
                       void* workspace, uint64_t workspace_bytes, void* stream);
-
-/* Plain device-to-device copy kernel of a known size (bytes % 16 == 0): the reference against which profiler byte
- * counters (FETCH_SIZE / WRITE_SIZE) are scaled.  Measurement aid only. */
-int32_t flover_k_copy_probe(void* dst, const void* src, uint64_t bytes, void* stream);
 
 #ifdef __cplusplus
 }

@@ -134,7 +134,8 @@ struct flover_ctx {
   int last_launches = 0;
   int launches = 0;
   // optional timing of the kernels with HIP events on the library's stream
-  int profile = 0;                         // 0 off, 1 attention of every 4th layer + shuffle copy, 2 every launch of every kind
+  int profile = 0;                         // 0 off, 1 sampled launches (see flover_set_profile), 2 every launch of every kind
+  int64_t prof_iter = 0;                   // fused iterations enqueued since the level was set (level 1 samples by it)
   bool in_step = false;                    // only the fused iteration is timed, not pre-processing
   bool prof_now = false;                   // the pass being enqueued on the iteration's lane is a timed one
   std::vector<hipEvent_t> ev;              // pool of pairs
@@ -260,7 +261,7 @@ int place(flover_ctx* c) {
 // Pairs are numbered in recording order; pair g lives in pool entry g % kEvPool until it has been added up.
 constexpr size_t kEvPool = 4096;
 int prof_begin(flover_ctx* c, int kind, int64_t bytes) {
-  if (c->profile == 0 || (c->profile == 1 && kind != FLOVER_PROF_ATTENTION && kind != FLOVER_PROF_COMPACT)) return -1;
+  if (c->profile == 0) return -1;
   if (!c->in_step && kind != FLOVER_PROF_COMPACT) return -1;
   if (c->ev_kind.size() >= kEvPool) return -1;            // every pool entry is waiting to be added up
   const size_t p = (c->ev_base + c->ev_kind.size()) % kEvPool;
@@ -289,10 +290,11 @@ void prof_collect(flover_ctx* c, size_t upto = (size_t)-1) {
     c->ev_base += 1;
   }
 }
+// `sampled`: this launch is one of those level 1 times (level 2 times every launch).
 hipError_t timed_gemm(flover_ctx* c, Lane& ln, int kind, const void* x, const void* w, int n, const flk::GemmPlan& p,
-                      size_t ss, int mtt) {
+                      size_t ss, int mtt, bool sampled) {
   const int64_t bytes = (int64_t)flk::gemm_tiled_bytes(c->cfg.dtype, p.N, p.K);
-  const int pi = (&ln == &c->step_lane && c->prof_now) ? prof_begin(c, kind, bytes) : -1;
+  const int pi = (&ln == &c->step_lane && c->prof_now && (sampled || c->profile >= 2)) ? prof_begin(c, kind, bytes) : -1;
   if (pi >= 0) (void)hipEventRecord(c->ev[2 * pi], ln.st);
   hipError_t e = flk::gemm(c->cfg.dtype, x, w, n, p, ln.part, ss, mtt, ln.st);
   if (pi >= 0) (void)hipEventRecord(c->ev[2 * pi + 1], ln.st);
@@ -375,6 +377,9 @@ int run_rows(flover_ctx* c, Lane& ln, const Row* rows, int n, bool want_tokens, 
   aw.out_mtt = mtt;
   const bool prof = &ln == &c->step_lane && (wait || want_tokens);
   if (&ln == &c->step_lane) c->prof_now = prof;
+  // level 1 keeps the event records few: the attention launch of one layer in four, and on every second iteration the
+  // four GEMMs of the middle layer and the output projection (two event records cost about as much as a small kernel)
+  const bool gemm_iter = prof && !context_pass && (c->prof_iter++ & 1) == 0;
 
   int launches = 0;
   // K slicing: the iteration's is fixed by the matrix shape; a context pass holds rows of one request only and may
@@ -398,7 +403,8 @@ int run_rows(flover_ctx* c, Lane& ln, const Row* rows, int n, bool want_tokens, 
                             w.ln1_g, w.ln1_b, ln.h, n, H, f.norm_eps, mtt, st));
     char* kl = c->kv + (size_t)(2 * l) * c->plane_bytes;
     char* vl = kl + c->plane_bytes;
-    HIPCHK(c, timed_gemm(c, ln, FLOVER_PROF_GEMM_QKV, ln.h, w.wqkv, n, p_qkv, ss_qkv, mtt));
+    const bool gs = gemm_iter && l == L / 2;
+    HIPCHK(c, timed_gemm(c, ln, FLOVER_PROF_GEMM_QKV, ln.h, w.wqkv, n, p_qkv, ss_qkv, mtt, gs));
     HIPCHK(c, flk::qkv_post(f.dtype, ln.part, p_qkv.S, ss_qkv, p_qkv.ldc, w.bqkv, c->rope_cs, d_slot, d_pos, ln.q, kl, vl, n, H, nh,
                             d, f.max_seq, st));
     if (context_pass && l == L - 1) {
@@ -414,17 +420,17 @@ int run_rows(flover_ctx* c, Lane& ln, const Row* rows, int n, bool want_tokens, 
       HIPCHK(c, flk::decode_attention(f.dtype, d, ln.q, kl, vl, aw, n, nh, f.max_seq, ln.att, st,
                                       pi >= 0 ? c->ev[2 * pi] : nullptr, pi >= 0 ? c->ev[2 * pi + 1] : nullptr));
     }
-    HIPCHK(c, timed_gemm(c, ln, FLOVER_PROF_GEMM_OUT, ln.att, w.wo, n, p_o, ss_h, mtt));
+    HIPCHK(c, timed_gemm(c, ln, FLOVER_PROF_GEMM_OUT, ln.att, w.wo, n, p_o, ss_h, mtt, gs));
     HIPCHK(c, flk::add_norm(f.dtype, !gpt, ln.x, ln.part, p_o.S, ss_h, p_o.ldc, w.bo, w.ln2_g, w.ln2_b, ln.h, n, H, f.norm_eps, mtt, st));
-    HIPCHK(c, timed_gemm(c, ln, FLOVER_PROF_GEMM_FF1, ln.h, w.w1, n, p_1, ss_1, mtt));
+    HIPCHK(c, timed_gemm(c, ln, FLOVER_PROF_GEMM_FF1, ln.h, w.w1, n, p_1, ss_1, mtt, gs));
     HIPCHK(c, flk::activation(f.dtype, !gpt, ln.part, p_1.S, ss_1, p_1.ldc, w.b1, ln.act, n, F, mtt, st));
-    HIPCHK(c, timed_gemm(c, ln, FLOVER_PROF_GEMM_FF2, ln.act, w.w2, n, p_2, ss_h, mtt));
+    HIPCHK(c, timed_gemm(c, ln, FLOVER_PROF_GEMM_FF2, ln.act, w.w2, n, p_2, ss_h, mtt, gs));
     launches += 10;
   }
   if (want_tokens) {
     HIPCHK(c, flk::add_norm(f.dtype, !gpt, ln.x, ln.part, c->p_2.S, ss_h, c->p_2.ldc, c->lw[L - 1].b2, c->lnf_g, c->lnf_b, ln.h, n, H,
                             f.norm_eps, mtt, st));
-    HIPCHK(c, timed_gemm(c, ln, FLOVER_PROF_GEMM_LM, ln.h, c->wlm, n, c->p_lm, ss_v, mtt));
+    HIPCHK(c, timed_gemm(c, ln, FLOVER_PROF_GEMM_LM, ln.h, c->wlm, n, c->p_lm, ss_v, mtt, gemm_iter));
     HIPCHK(c, flk::logits_argmax(ln.part, c->p_lm.S, ss_v, c->p_lm.ldc, logits_out, ln.tok_out, n, V, st));
     const int ti = ln.tok_next;       // at most kStageRing - 1 iterations are outstanding, so this entry is free
     ln.tok_next = (ln.tok_next + 1) % kStageRing;
@@ -1109,6 +1115,7 @@ int32_t flover_set_profile(flover_ctx* c, int32_t level) {
   if (!c || level < 0 || level > 2) return fail(c, FLOVER_E_INVAL, "profile level must be 0, 1 or 2");
   std::lock_guard<std::mutex> lock(c->mu);
   c->profile = level;
+  c->prof_iter = 0;
   for (int k = 0; k < FLOVER_PROF_KINDS; ++k) {
     c->prof_ms[k] = 0;
     c->prof_launches[k] = 0;
