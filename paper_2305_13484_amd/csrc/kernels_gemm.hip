@@ -491,10 +491,10 @@ static void launch_direct(const void* x, const void* wt, float* part, int M, con
   gemm16_direct_kernel<DT, MT, NT, PFW, PFA><<<grid, 256, 0, st>>>((const uint16_t*)x, (const u32x4_t*)wt, part, M, p.N, p.K,
                                                              ngroups, p.KB, p.kbs, ss, p.ldc, xmtt);
 }
-template <int DT, int MT, int NT, int NTW, int PF>
+template <int DT, int MT, int NT, int NTW, int PF, int GPB = 4>
 static void launch_lds(const void* x, const void* wt, float* part, int M, const GemmPlan& p, size_t ss, int xmtt,
                        hipStream_t st) {
-  constexpr int GPB = 4;                        // column groups per block: 256 columns, or 128 for the 32-column groups
+                                                // GPB column groups per block: 256 columns, or 128 for the 32-column groups
                                                 // (8 groups per block measured 3 % slower on the 7B stream)
   const int ngroups = p.Npad / (16 * NT);
   const int nx = (ngroups + GPB - 1) / GPB, nz = (M + 16 * MT - 1) / (16 * MT);

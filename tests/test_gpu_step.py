@@ -796,3 +796,66 @@ def test_async_preprocess_matches_the_oracle_per_request(name, pipelined):
     worst = assert_matches_oracle_per_request(cfg, got, want, reqs)
     print("async vs oracle", name, "pipelined" if pipelined else "synchronous", st, "max rel err", worst)
     assert st["moves"] > 0
+
+
+@pytest.mark.parametrize("make", [lambda: synth.tiny_gpt(C=5, S=128), lambda: synth.small_llama16(synth.DT_BF16, C=5, S=128),
+                                  lambda: synth.small_gpt16(synth.DT_F16, C=5, S=128)])
+def test_cache_rows_match_the_oracle_after_context_pass_append_and_shuffle(make):
+    """The KV cache itself against the oracle's cache, slot by slot: after pre-processing (rows written by the context
+    pass, rotary applied to K for LLaMA), after a few iterations (rows appended one per iteration), and after a shuffle
+    has moved requests between slots -- every layer, K and V, every head, rows [0, len) of every occupied slot.
+    Two layers deep there is little depth noise yet: values agree to within a step or two of the 16-bit format."""
+    cfg = make()
+    w = synth.make_weights(cfg, 55)
+    ls = Lockstep(cfg, w)
+    rng = np.random.default_rng(56)
+    plan = [(0, 70, 30), (1, 3, 2), (2, 33, 30), (3, 1, 3), (4, 17, 30)]          # (id, prompt length, generation length)
+    for rid, P, G in plan:
+        ls.add(synth.Request(rid, 0, rng.integers(0, cfg.V, size=P).astype(np.int32), G))
+    rel = {synth.DT_BF16: 1.2e-2, synth.DT_F16: 1.5e-3, synth.DT_F32: 1e-5}[cfg.dtype]     # of the largest cached value
+
+    def compare(tag):
+        st = ls.gpu.state()
+        kv = ls.gpu.kv_cache()
+        worst, n_rows = 0.0, 0
+        for slot in range(cfg.C):
+            n = int(st["len"][slot])
+            if st["state"][slot] == 0 or n == 0:
+                continue
+            for l in range(cfg.L):
+                for which in (0, 1):
+                    ref = np.stack([ls.cpu.read_kv(l, which, slot, h, n) for h in range(cfg.nh)])
+                    got = kv[l, which, slot, :, :n].float().cpu().double().numpy()
+                    e = float(np.abs(got - ref).max() / np.abs(ref).max())
+                    worst = max(worst, e)
+                    assert e <= rel, (tag, slot, l, which, e)
+            n_rows += n
+        print(cfg.name, tag, "cached rows compared", n_rows, "max |diff| / max |ref|", worst)
+        assert n_rows > 0
+
+    compare("after pre-processing")
+    for _ in range(3):
+        ls.step()
+        ls.reorder()                      # requests 1 and 3 finish on the way: the request in slot 4 moves into slot 1
+    assert ls.moves >= 1
+    compare("after three iterations and the shuffle")
+    ls.close()
+
+
+def test_sampled_kernel_timing_at_level_one():
+    """Profile level 1 (what the benchmark runs with): the attention launch of one layer in four every iteration, and
+    on every second iteration the four GEMMs of the middle layer and the output projection."""
+    import paper_2305_13484_amd as fl
+    cfg = synth.small_llama16(synth.DT_BF16, L=4)
+    w = to_device(synth.make_weights(cfg, 22))
+    srv = fl.Flover(cfg, w)
+    srv.set_profile(1)
+    srv.add_request(1, [5, 6, 7, 8], 8)
+    for _ in range(6):
+        srv.step()
+    p = srv.get_profile()
+    assert p["attention"]["launches"] == 6 * 1                 # layers 0 of 4
+    for k in ("gemm_qkv", "gemm_out", "gemm_ff1", "gemm_ff2", "gemm_lm"):
+        assert p[k]["launches"] == 3 and p[k]["ms"] > 0, k      # iterations 0, 2, 4
+    assert p["gemm_ff1"]["bytes"] == 3 * 2 * cfg.F * cfg.H * 2
+    srv.close()
