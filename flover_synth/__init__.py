@@ -238,6 +238,17 @@ def stream_c5(seed: int, V: int = 32000, n: int = 512, S: int = 2048) -> List[Re
     return _finish(rng, arr, P, G, V)
 
 
+def stream_bursty(seed: int, V: int, n: int, period: int, rate_lo: float, rate_hi: float, p_lo: int, p_hi: int, g_lo: int,
+                  g_hi: int) -> List[Request]:
+    """The arrival pattern of the 30B configuration at any scale: Poisson counts per step whose rate alternates between
+    rate_lo and rate_hi every `period` steps; prompt and generation lengths uniform."""
+    rng = np.random.default_rng(seed)
+    arr = poisson_arrivals(rng, n, lambda s: rate_lo if (s // period) % 2 == 0 else rate_hi)
+    P = rng.integers(p_lo, p_hi + 1, size=n)
+    G = rng.integers(g_lo, g_hi + 1, size=n)
+    return _finish(rng, arr, P, G, V)
+
+
 def stream_small(seed: int, V: int, n: int, arrive_hi: int, p_lo: int, p_hi: int, g_lo: int, g_hi: int) -> List[Request]:
     rng = np.random.default_rng(seed)
     arr = rng.integers(0, arrive_hi + 1, size=n)

@@ -859,3 +859,36 @@ def test_sampled_kernel_timing_at_level_one():
         assert p[k]["launches"] == 3 and p[k]["ms"] > 0, k      # iterations 0, 2, 4
     assert p["gemm_ff1"]["bytes"] == 3 * 2 * cfg.F * cfg.H * 2
     srv.close()
+
+
+@pytest.mark.parametrize("by_length", [False, True])
+def test_bursty_stream_with_heavy_eviction_churn(by_length):
+    """The 30B configuration's scheduling regime at a size the oracle follows step by step: 300 requests in bursts (Poisson
+    rate alternating 0.5 and 6 per step every 40 steps) contend for 32 slots, so requests queue for slots during a
+    burst, the window fills to capacity, wraps below, and nearly every iteration evicts and shuffles.  Slot assignment,
+    window, Algorithm 3 results, move lists, evictions, tokens and logits against the oracle at every step."""
+    cfg = dataclasses.replace(synth.tiny_gpt(), C=32, S=128)
+    w = synth.make_weights(cfg, 5)
+    reqs = synth.stream_bursty(7, cfg.V, 300, 40, 0.5, 6.0, 2, 30, 2, 80)
+    ls = Lockstep(cfg, w, by_length=by_length)
+    pending = sorted(reqs, key=lambda r: (r.arrival_step, r.req_id))
+    i = done = s = 0
+    max_wait = max_live = shuffles = 0
+    while done < len(reqs):
+        while i < len(pending) and pending[i].arrival_step <= s:
+            ls.add(pending[i])
+            i += 1
+        g, _ = ls.step()
+        done += int(g.finished.sum())
+        max_live = max(max_live, g.n_live)
+        rg, _ = ls.reorder()
+        shuffles += bool(rg.moves)
+        max_wait = max(max_wait, ls.gpu.state()["waiting"])
+        s += 1
+        assert s < 5000
+    print("bursty: steps", s, "rows", ls.compared_rows, "max live", max_live, "max waiting", max_wait, "moves", ls.moves,
+          "iterations with a shuffle", shuffles, "max rel err", ls.max_err)
+    assert max_live == cfg.C and max_wait > 20 and shuffles > s // 4 and ls.ties == 0
+    for r in reqs:
+        assert len(ls.tokens[r.req_id]) == r.gen_len
+    ls.close()
