@@ -78,3 +78,28 @@ def test_bench_refuses_more_than_one_gpu():
     import sys
     r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True, timeout=120)
     assert r.returncode != 0 and "ONE GPU" in (r.stderr + r.stdout)
+
+
+def test_profile_summary_splits_a_trace_into_iterations(tmp_path):
+    """Host logic of the per-iteration summary of a kernel trace: iterations run from one embedding launch to the next,
+    only those with an argmax launch count, busy time is the sum of kernel durations, gaps are start minus previous end."""
+    import sqlite3
+    from paper_2305_13484_amd import profile_summary as ps
+    db = str(tmp_path / "kt.db")
+    c = sqlite3.connect(db)
+    c.execute("create table kernels(name text, start int, end int)")
+    t = 0
+    for it in range(4):
+        names = ["void flk::embed_kernel<2>", "void flk::add_norm_kernel<2, 1>", "void flk::gemm16_direct_kernel<2, 1, 4, 8, 8>"]
+        if it != 2:                                   # iteration 2 is a context pass: no argmax
+            names.append("flk::argmax_kernel")
+        for n in names:
+            c.execute("insert into kernels values(?,?,?)", (n, t, t + 5000))
+            t += 7000                                 # 5 us busy, 2 us gap
+    c.execute("insert into kernels values(?,?,?)", ("void at::native::something", 1, 2))     # foreign kernels are ignored
+    c.commit()
+    c.close()
+    out = ps.iterations(db)
+    assert "fused iterations 3, launches per iteration (median) 4" in out
+    assert "kernels busy per iteration: median 20.0 us; iteration span: median 26.0 us" in out
+    assert "gaps between consecutive launches of an iteration: median 2.00 us" in out
