@@ -38,7 +38,8 @@ def test_config1_tiny_gpt_fp32_full_stream():
 
 
 @pytest.mark.parametrize("make", [lambda: synth.tiny_llama(synth.DT_F32), lambda: synth.small_gpt16(synth.DT_F16),
-                                  lambda: synth.small_llama16(synth.DT_BF16), lambda: synth.tiny_llama(synth.DT_BF16)])
+                                  lambda: synth.small_llama16(synth.DT_BF16), lambda: synth.tiny_llama(synth.DT_BF16),
+                                  lambda: synth.small_gpt16(synth.DT_BF16), lambda: synth.small_llama16(synth.DT_F16)])
 def test_small_models_all_dtypes(make):
     cfg = make()
     print(cfg.name, flush=True)
@@ -758,6 +759,7 @@ def test_context_pass_waits_for_the_shuffle_copy_that_vacated_its_slot():
     (lambda: synth.tiny_gpt(C=5, S=96), 3, False, 82),
     (lambda: synth.tiny_llama(synth.DT_F32, C=4, S=96), 3, True, 83),
     (lambda: synth.small_llama16(synth.DT_BF16, C=6), 2, False, 84),
+    (lambda: synth.tiny_gpt(C=5, S=96), 3, "by_length", 85),
 ])
 def test_pipelined_iterations_in_lockstep_with_the_oracle(make, depth, shuffle_off, seed):
     """flover_step_submit / flover_step_collect against the oracle: slot assignment, window, evictions and move lists
@@ -766,7 +768,9 @@ def test_pipelined_iterations_in_lockstep_with_the_oracle(make, depth, shuffle_o
     cfg = make()
     w = synth.make_weights(cfg, seed)
     reqs = synth.stream_small(seed + 100, cfg.V, n=20, arrive_hi=18, p_lo=1, p_hi=40, g_lo=1, g_hi=18)
-    ls = LockstepPipelined(cfg, w, depth=depth, shuffle_off=shuffle_off)
+    by_length = shuffle_off == "by_length"
+    shuffle_off = shuffle_off is True
+    ls = LockstepPipelined(cfg, w, depth=depth, shuffle_off=shuffle_off, by_length=by_length)
     ls.run(reqs)
     print("pipelined lockstep", cfg.name, "depth", depth, "iterations", ls.steps, "rows", ls.compared_rows, "max rel err",
           ls.max_err, "moves", ls.moves, "max outstanding", ls.max_outstanding)
@@ -889,6 +893,21 @@ def test_bursty_stream_with_heavy_eviction_churn(by_length):
     print("bursty: steps", s, "rows", ls.compared_rows, "max live", max_live, "max waiting", max_wait, "moves", ls.moves,
           "iterations with a shuffle", shuffles, "max rel err", ls.max_err)
     assert max_live == cfg.C and max_wait > 20 and shuffles > s // 4 and ls.ties == 0
+    for r in reqs:
+        assert len(ls.tokens[r.req_id]) == r.gen_len
+    ls.close()
+
+
+def test_a_single_slot_serves_requests_one_after_the_other():
+    """max_concurrency = 1: the window is [0,1) or empty, every other request waits in the request queue and is admitted
+    by the step after its predecessor's eviction; nothing ever moves.  Against the oracle, step by step."""
+    cfg = dataclasses.replace(synth.tiny_gpt(), C=1, S=64)
+    w = synth.make_weights(cfg, 9)
+    reqs = synth.stream_small(10, cfg.V, n=6, arrive_hi=3, p_lo=1, p_hi=20, g_lo=1, g_hi=12)
+    ls = Lockstep(cfg, w)
+    live = ls.run(reqs)
+    assert max(live) == 1 and ls.moves == 0 and ls.ties == 0
+    assert ls.steps == sum(r.gen_len for r in reqs)              # one request at a time, one token per iteration
     for r in reqs:
         assert len(ls.tokens[r.req_id]) == r.gen_len
     ls.close()
