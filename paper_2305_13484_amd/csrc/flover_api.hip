@@ -366,9 +366,9 @@ int run_rows(flover_ctx* c, Lane& ln, const Row* rows, int n, bool want_tokens, 
     ln.staged_busy[ri] = true;
   }
   int* ds = ln.d_stage;
-  const int *d_tok = ds, *d_pos = ds + R, *d_slot = ds + 2 * R, *d_len = ds + 3 * R, *d_item0 = ds + 4 * R,
-            *d_nchunk = ds + 5 * R;
-  flk::AttnWork aw{(const int4*)(ds + 6 * R), d_slot, d_len, d_item0, d_nchunk, ln.pml, ln.po, n_items, flk::attn_chunk()};
+  const int *d_tok = ds, *d_pos = ds + R, *d_slot = ds + 2 * R, *d_len = ds + 3 * R;
+  flk::AttnWork aw{(const int4*)(ds + 6 * R), d_slot, d_len, ln.pml, ln.po, n_items, flk::attn_chunk(),
+                   (f.max_seq + flk::attn_chunk() - 1) / flk::attn_chunk()};
   aw.blocks = (const int4*)(ds + 6 * R + 4 * n_items);
   aw.n_blocks = n_blocks;
   // what feeds a GEMM (norm output, attention output, MLP activation) is written in the order the GEMM's MFMA reads
@@ -1210,8 +1210,8 @@ int32_t flover_k_decode_attention(int32_t dtype, const void* q, const void* kcac
   HIPCHK(nullptr, hipMemcpyAsync(ws + o_items, items.data(), items.size() * 4, hipMemcpyHostToDevice, st));
   HIPCHK(nullptr, hipStreamSynchronize(st));
   int* ds = (int*)ws;
-  flk::AttnWork aw{(const int4*)(ws + o_items), ds, ds + M, ds + 2 * M, ds + 3 * M, (float*)(ws + o_pml), (float*)(ws + o_po),
-                   (int)items.size() / 4, flk::attn_chunk()};
+  flk::AttnWork aw{(const int4*)(ws + o_items), ds, ds + M, (float*)(ws + o_pml), (float*)(ws + o_po),
+                   (int)items.size() / 4, flk::attn_chunk(), (max_len + flk::attn_chunk() - 1) / flk::attn_chunk()};
   HIPCHK(nullptr, flk::decode_attention(dtype, d, q, kcache, vcache, aw, M, nh, S, out, st));
   return FLOVER_OK;
 }
@@ -1257,8 +1257,7 @@ struct NoallocRows {
 // One block of kNoallocMaxRows threads: thread t owns row t, writes its descriptors and its (row, chunk, slot, len)
 // work items; first-item indices are an exclusive scan of the rows' chunk counts.
 __global__ __launch_bounds__(kNoallocMaxRows) void noalloc_rows_kernel(NoallocRows r, int M, int chunk, int* __restrict__ row_slot,
-                                                                       int* __restrict__ row_len, int* __restrict__ row_item0,
-                                                                       int* __restrict__ row_nchunk, int4* __restrict__ items) {
+                                                                       int* __restrict__ row_len, int4* __restrict__ items) {
   __shared__ int scan[kNoallocMaxRows];
   const int t = threadIdx.x;
   const int slot = t < M ? r.slot[t] : 0, len = t < M ? r.len[t] : 0;
@@ -1275,8 +1274,6 @@ __global__ __launch_bounds__(kNoallocMaxRows) void noalloc_rows_kernel(NoallocRo
   const int first = scan[t] - nc;
   row_slot[t] = slot;
   row_len[t] = len;
-  row_item0[t] = first;
-  row_nchunk[t] = nc;
   for (int ch = 0; ch < nc; ++ch) items[first + ch] = make_int4(t, ch, slot, len);
 }
 
@@ -1316,11 +1313,10 @@ int32_t flover_k_decode_attention_noalloc(int32_t dtype, const void* q, const vo
   int* ds = (int*)ws;
   hipStream_t st = (hipStream_t)stream;
   // every part of the scratch this call reads is written first by this call's own kernels: nothing has to start at zero
-  noalloc_rows_kernel<<<1, kNoallocMaxRows, 0, st>>>(rows, M, flk::attn_chunk(), ds, ds + M, ds + 2 * M, ds + 3 * M,
-                                                     (int4*)(ws + o_items));
+  noalloc_rows_kernel<<<1, kNoallocMaxRows, 0, st>>>(rows, M, flk::attn_chunk(), ds, ds + M, (int4*)(ws + o_items));
   HIPCHK(nullptr, hipGetLastError());
-  flk::AttnWork aw{(const int4*)(ws + o_items), ds, ds + M, ds + 2 * M, ds + 3 * M, (float*)(ws + o_pml), (float*)(ws + o_po),
-                   n_items, flk::attn_chunk()};
+  flk::AttnWork aw{(const int4*)(ws + o_items), ds, ds + M, (float*)(ws + o_pml), (float*)(ws + o_po),
+                   n_items, flk::attn_chunk(), (max_len + flk::attn_chunk() - 1) / flk::attn_chunk()};
   HIPCHK(nullptr, flk::decode_attention(dtype, d, q, kcache, vcache, aw, M, nh, S, out, st));
   return FLOVER_OK;
 }

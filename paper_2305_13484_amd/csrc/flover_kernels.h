@@ -58,12 +58,11 @@ struct AttnWork {          // all device pointers
   const int4* items;       // [n_items] (row, chunk, slot of the row, cache rows of the row)
   const int* row_slot;     // [M]
   const int* row_len;      // [M] rows of cache attended to (>= 1)
-  const int* row_item0;    // [M] first item of the row
-  const int* row_nchunk;   // [M]
-  float* pml;              // [n_items][nh][2]
-  float* po;               // [n_items][nh][d]
+  float* pml;              // [M][maxch][nh][2]: (m, l) of chunk ch of row r at ((r * maxch + ch) * nh + head)
+  float* po;               // [M][maxch][nh][d]
   int n_items;
   int chunk;
+  int maxch;               // chunk slots per row in pml / po: at least ceil(longest row / chunk)
   const int4* blocks = nullptr;   // pre-processing passes: (first row, rows <= prefill_rows_per_block, chunk, -)
   int n_blocks = 0;
   int out_mtt = 0;                // layout of the attention output: 0 row-major, else fragment order (see add_norm)

@@ -17,11 +17,13 @@
 namespace flk {
 
 // grid = (n_items, n_head / 4), block = 256: wave w handles head blockIdx.y * 4 + w of item blockIdx.x.
-// items[i] = (row, chunk, slot, len).  Writes unnormalised partial (m, l, o[D]) per (item, head).
+// items[i] = (row, chunk, slot, len).  Writes the unnormalised partial (m, l, o[D]) of (row, chunk, head) at index
+// (row * maxch + chunk) * n_head + head: the place depends on the row and the chunk alone, so the merge kernel finds a
+// row's partials without looking anything up.
 template <int DT, int D, int U>
 __global__ __launch_bounds__(256) void attn_partial_kernel(const void* __restrict__ q, const void* __restrict__ kc,
                                                            const void* __restrict__ vc, const int4* __restrict__ items, int nh,
-                                                           int Smax, int chunk,
+                                                           int Smax, int chunk, int maxch,
                                                            float scale, float* __restrict__ pml, float* __restrict__ po) {
   constexpr int EB = (DT == DT_F32) ? 4 : 2;
   constexpr int EPL = 16 / EB;          // elements per lane
@@ -129,7 +131,7 @@ __global__ __launch_bounds__(256) void attn_partial_kernel(const void* __restric
     m = mt;
   }
   if (grp == 0) {
-    const size_t pi = (size_t)item * nh + hd;
+    const size_t pi = ((size_t)row * maxch + ch) * nh + hd;
     float* op = po + pi * D + li * EPL;
 #pragma unroll
     for (int e = 0; e < EPL; ++e) op[e] = o[e];
@@ -142,37 +144,53 @@ __global__ __launch_bounds__(256) void attn_partial_kernel(const void* __restric
 
 // grid = (M, n_head), block = D: merges a row's chunks in chunk order, normalises, rounds to dtype.
 // out is [M][nh * D] row-major (mtt == 0) or in the GEMM's fragment order with mtt row tiles.
+// The partials of a row sit at a place known from the row index alone, so the loads of the first four chunks go out
+// together with the load of the row's length (one memory round trip for rows of up to 4 chunks; slots of chunks the row
+// does not have are read and never used); longer rows fetch the rest in a second round.
 template <int DT, int D>
 __global__ void attn_merge_kernel(const float* __restrict__ pml, const float* __restrict__ po,
-                                  const int* __restrict__ row_item0, const int* __restrict__ row_nchunk, int nh,
+                                  const int* __restrict__ row_len, int chunk, int maxch, int nh,
                                   void* __restrict__ out, int mtt) {
-  float red_m = 0.f;
+  constexpr int FIRST = 4;
   const int row = blockIdx.x, hd = blockIdx.y, i = threadIdx.x;
-  const int it0 = row_item0[row], nc = row_nchunk[row];
+  const size_t base = ((size_t)row * maxch) * nh + hd;       // + ch * nh
+  float mc[FIRST], lc[FIRST], oc[FIRST];
+#pragma unroll
+  for (int j = 0; j < FIRST; ++j) {
+    const size_t pi = base + (size_t)min(j, maxch - 1) * nh;
+    mc[j] = pml[pi * 2];
+    lc[j] = pml[pi * 2 + 1];
+    oc[j] = po[pi * D + i];
+  }
+  const int nc = (row_len[row] + chunk - 1) / chunk;
+  float red_m = -INFINITY;                                    // the global maximum needs the m of every chunk
+#pragma unroll
+  for (int j = 0; j < FIRST; ++j)
+    if (j < nc) red_m = fmaxf(red_m, mc[j]);
+  for (int c = FIRST; c < nc; ++c) red_m = fmaxf(red_m, pml[(base + (size_t)c * nh) * 2]);
   float l = 0.f, o = 0.f;
-  for (int c0 = 0; c0 < nc; c0 += 8) {          // 8 chunks at a time: all loads first, then the arithmetic in chunk order
-    float mc[8], lc[8], oc[8];
 #pragma unroll
-    for (int j = 0; j < 8; ++j) {
-      const size_t pi = (size_t)(it0 + min(c0 + j, nc - 1)) * nh + hd;
-      mc[j] = pml[pi * 2];
-      lc[j] = pml[pi * 2 + 1];
-      oc[j] = po[pi * D + i];
+  for (int j = 0; j < FIRST; ++j)
+    if (j < nc) {
+      const float w = __expf(mc[j] - red_m);
+      l += w * lc[j];
+      o += w * oc[j];
     }
-    if (c0 == 0) {                                // the global maximum needs the m of every chunk
-      float mt = -INFINITY;
+  for (int c0 = FIRST; c0 < nc; c0 += 4) {      // longer rows: 4 chunks at a time, loads first, arithmetic in chunk order
+    float m2[4], l2[4], o2[4];
 #pragma unroll
-      for (int j = 0; j < 8; ++j)
-        if (j < nc) mt = fmaxf(mt, mc[j]);
-      for (int c = 8; c < nc; ++c) mt = fmaxf(mt, pml[((size_t)(it0 + c) * nh + hd) * 2]);
-      red_m = mt;
+    for (int j = 0; j < 4; ++j) {
+      const size_t pi = base + (size_t)min(c0 + j, nc - 1) * nh;
+      m2[j] = pml[pi * 2];
+      l2[j] = pml[pi * 2 + 1];
+      o2[j] = po[pi * D + i];
     }
 #pragma unroll
-    for (int j = 0; j < 8; ++j)
+    for (int j = 0; j < 4; ++j)
       if (c0 + j < nc) {
-        const float w = __expf(mc[j] - red_m);
-        l += w * lc[j];
-        o += w * oc[j];
+        const float w = __expf(m2[j] - red_m);
+        l += w * l2[j];
+        o += w * o2[j];
       }
   }
   st<DT>(out, xrow_index(row, hd * D + i, nh * D, mtt), o / l);
@@ -188,10 +206,9 @@ template <int DT, int D, int QB>
 __global__ __launch_bounds__(256) void attn_prefill_kernel(const void* __restrict__ q, const void* __restrict__ kc,
                                                            const void* __restrict__ vc, const int4* __restrict__ blocks,
                                                            const int* __restrict__ row_slot,
-                                                           const int* __restrict__ row_len,
-                                                           const int* __restrict__ row_item0,
-                                                           const int* __restrict__ row_nchunk, int nh, int Smax, int chunk,
-                                                           float scale, float* __restrict__ pml, float* __restrict__ po) {
+                                                           const int* __restrict__ row_len, int nh, int Smax, int chunk,
+                                                           int maxch, float scale, float* __restrict__ pml,
+                                                           float* __restrict__ po) {
   constexpr int EB = (DT == DT_F32) ? 4 : 2;
   constexpr int EPL = 16 / EB;
   constexpr int LPR = D / EPL;
@@ -290,8 +307,8 @@ __global__ __launch_bounds__(256) void attn_prefill_kernel(const void* __restric
       mi = mt;
     }
     const int r = first + i;
-    if (i < nr && ch < row_nchunk[r] && grp == 0) {          // this chunk holds keys this query may see
-      const size_t pi = (size_t)(row_item0[r] + ch) * nh + hd;
+    if (i < nr && ch * chunk < len0 + i && grp == 0) {       // this chunk holds keys this query may see
+      const size_t pi = ((size_t)r * maxch + ch) * nh + hd;
       float* op = po + pi * D + li * EPL;
 #pragma unroll
       for (int e = 0; e < EPL; ++e) op[e] = o[i][e];
@@ -330,11 +347,9 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
                                                                 const void* __restrict__ vc,
                                                                 const int4* __restrict__ blocks,
                                                                 const int* __restrict__ row_slot,
-                                                                const int* __restrict__ row_len,
-                                                                const int* __restrict__ row_item0,
-                                                                const int* __restrict__ row_nchunk, int nh, int Smax,
-                                                                int chunk, float scale, float* __restrict__ pml,
-                                                                float* __restrict__ po) {
+                                                                const int* __restrict__ row_len, int nh, int Smax,
+                                                                int chunk, int maxch, float scale,
+                                                                float* __restrict__ pml, float* __restrict__ po) {
   static_assert(DT != DT_F32, "16-bit models only");
   constexpr int QT = kPrefillMfmaQB / 16;   // query tiles per wave
   constexpr int KS = D / 32;                // MFMA steps over the head dimension
@@ -473,8 +488,8 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
     lv += __shfl_xor(lv, 32, 64);
     const int qi = t * 16 + n;
     const int r = first + min(qi, nr - 1);
-    if (qi < nr && ch < row_nchunk[r]) {                         // this chunk holds keys this query may see
-      const size_t pi = (size_t)(row_item0[r] + ch) * nh + hd;
+    if (qi < nr && ch * chunk < len0 + qi) {                     // this chunk holds keys this query may see
+      const size_t pi = ((size_t)r * maxch + ch) * nh + hd;
 #pragma unroll
       for (int dt = 0; dt < DTL; ++dt) *(f32x4_t*)(po + pi * D + dt * 16 + 4 * g) = oacc[dt][t];
       if (g == 0) {
@@ -495,10 +510,10 @@ static void launch_attn(const void* q, const void* kc, const void* vc, const Att
                         void* out, hipStream_t st, hipEvent_t ev0, hipEvent_t ev1) {
   const float scale = 1.0f / sqrtf((float)D);
   if (ev0) (void)hipEventRecord(ev0, st);
-  attn_partial_kernel<DT, D, 4><<<dim3(w.n_items, nh / 4), 256, 0, st>>>(q, kc, vc, w.items, nh, Smax, w.chunk, scale,
-                                                                       w.pml, w.po);
+  attn_partial_kernel<DT, D, 4><<<dim3(w.n_items, nh / 4), 256, 0, st>>>(q, kc, vc, w.items, nh, Smax, w.chunk, w.maxch,
+                                                                       scale, w.pml, w.po);
   if (ev1) (void)hipEventRecord(ev1, st);
-  attn_merge_kernel<DT, D><<<dim3(M, nh), D, 0, st>>>(w.pml, w.po, w.row_item0, w.row_nchunk, nh, out, w.out_mtt);
+  attn_merge_kernel<DT, D><<<dim3(M, nh), D, 0, st>>>(w.pml, w.po, w.row_len, w.chunk, w.maxch, nh, out, w.out_mtt);
 }
 
 hipError_t decode_attention(int dtype, int d, const void* q, const void* kc, const void* vc, const AttnWork& w, int M,
@@ -522,11 +537,11 @@ static void launch_prefill(const void* q, const void* kc, const void* vc, const 
   const float scale = 1.0f / sqrtf((float)D);
   if constexpr (DT == DT_F32)
     attn_prefill_kernel<DT, D, kPrefillQB><<<dim3(w.n_blocks, nh / 4), 256, 0, st>>>(
-        q, kc, vc, w.blocks, w.row_slot, w.row_len, w.row_item0, w.row_nchunk, nh, Smax, w.chunk, scale, w.pml, w.po);
+        q, kc, vc, w.blocks, w.row_slot, w.row_len, nh, Smax, w.chunk, w.maxch, scale, w.pml, w.po);
   else
     attn_prefill_mfma_kernel<DT, D><<<dim3(w.n_blocks, nh / 4), 256, 0, st>>>(
-        q, kc, vc, w.blocks, w.row_slot, w.row_len, w.row_item0, w.row_nchunk, nh, Smax, w.chunk, scale, w.pml, w.po);
-  attn_merge_kernel<DT, D><<<dim3(M, nh), D, 0, st>>>(w.pml, w.po, w.row_item0, w.row_nchunk, nh, out, w.out_mtt);
+        q, kc, vc, w.blocks, w.row_slot, w.row_len, nh, Smax, w.chunk, w.maxch, scale, w.pml, w.po);
+  attn_merge_kernel<DT, D><<<dim3(M, nh), D, 0, st>>>(w.pml, w.po, w.row_len, w.chunk, w.maxch, nh, out, w.out_mtt);
 }
 
 hipError_t prefill_attention(int dtype, int d, const void* q, const void* kc, const void* vc, const AttnWork& w, int M,

@@ -121,17 +121,29 @@ __global__ void qkv_post_kernel(const float* __restrict__ part, int S, size_t st
   const int c0 = which * H + hd * d + i, c1 = c0 + half;
   const float* p0 = part + (size_t)m * ldp + c0;
   const float* p1 = part + (size_t)m * ldp + c1;
+  // Load order: the row's position first, then every split-K slice (their addresses need nothing else), and only then
+  // the rotary table row, whose address waits for the position -- so that wait overlaps the slices' flight.
   const int p = pos[m];
   const bool rot = rope_cs && which < 2;
-  f32x4_t t0 = {1.f, 0.f, 1.f, 0.f}, t1 = t0;          // (cos, sin) of 4 consecutive pairs, fetched early
+  f32x4_t a0 = ld4(p0), a1 = ld4(p1);
+  f32x4_t u0[8], u1[8];
+#pragma unroll
+  for (int j = 0; j < 8; ++j)                             // slices 1..8; S is uniform over the grid: scalar branches
+    if (1 + j < S) {
+      u0[j] = ld4(p0 + (size_t)(1 + j) * stride);
+      u1[j] = ld4(p1 + (size_t)(1 + j) * stride);
+    }
+  __builtin_amdgcn_sched_barrier(0);
+  f32x4_t t0 = {1.f, 0.f, 1.f, 0.f}, t1 = t0;          // (cos, sin) of 4 consecutive pairs
   if (rot) {
     const float* t = rope_cs + ((size_t)p * half + i) * 2;
     t0 = ld4(t);
     t1 = ld4(t + 4);
   }
-  f32x4_t a0 = ld4(p0), a1 = ld4(p1);
-  for (int s0 = 1; s0 < S; s0 += 8) {
-    f32x4_t u0[8], u1[8];
+#pragma unroll
+  for (int j = 0; j < 8; ++j)
+    if (1 + j < S) { a0 += u0[j]; a1 += u1[j]; }
+  for (int s0 = 9; s0 < S; s0 += 8) {                     // more than 9 slices: context passes of short prompts only
 #pragma unroll
     for (int j = 0; j < 8; ++j) {
       const size_t o = (size_t)min(s0 + j, S - 1) * stride;
