@@ -169,7 +169,7 @@ def test_llama7b_shape_reduced_depth():
 STATED_TOL = 2e-2          # the logits tolerance the target states for 16-bit models
 
 
-def _full_depth_case(cfg, seed, prompts, gen, check_kv_of=None):
+def _full_depth_case(cfg, seed, prompts, gen, check_kv_of=None, oracle_cache=False):
     """The benchmark's own configuration (full depth, full arena, its strides and launch shapes) on a sample the oracle
     can follow: every generated token's logits against the oracle.  The oracle runs the same weights with a small cache
     of its own (slots and positions used are the same on both sides).  Returns (per-row errors, near ties)."""
@@ -185,8 +185,21 @@ def _full_depth_case(cfg, seed, prompts, gen, check_kv_of=None):
     rng = np.random.default_rng(seed + 1)
     for rid, p in enumerate(prompts):
         prompt = rng.integers(0, cfg.V, size=p).astype(np.int32)
-        assert gpu.add_request(rid, prompt, gen) == cpu.add_request(rid, prompt, gen) == rid
-        print("  request", rid, "prompt", p, "pre-processed on both sides", flush=True)
+        if not oracle_cache:
+            assert gpu.add_request(rid, prompt, gen) == cpu.add_request(rid, prompt, gen) == rid
+            print("  request", rid, "prompt", p, "pre-processed on both sides", flush=True)
+            continue
+        # decode only: the HIP side joins on a copy of the ORACLE's context cache (no context pass of its own), so that
+        # whatever distance remains comes from the fused iterations alone
+        assert cpu.add_request(rid, prompt, gen) == rid
+        kv = gpu.kv_cache()
+        for l in range(cfg.L):
+            for which in (0, 1):
+                if p > 1:
+                    rows = np.stack([cpu.read_kv(l, which, rid, h, p - 1) for h in range(cfg.nh)])
+                    kv[l, which, rid, :, :p - 1] = torch.from_numpy(rows).to(kv.dtype).cuda()
+        assert gpu.add_request_cached(rid, p - 1, int(prompt[-1]), gen) == rid
+        print("  request", rid, "prompt", p, "joined on the oracle's cache", flush=True)
     kv_err = None
     if check_kv_of is not None:
         # the context cache itself, straight after pre-processing: the slot's K and V rows, every head, against the
@@ -259,6 +272,17 @@ def test_llama7b_full_depth_sampled_requests(seed):
     print(cfg.name, "seed", seed, flush=True)
     errs, ties, _ = _full_depth_case(cfg, seed, (2, 5, 7), 3)
     _report_against_stated_tolerance(cfg.name, errs, ties)
+
+
+def test_llama7b_full_depth_decode_only_on_the_oracles_cache():
+    """The error budget split: the same three requests as the first draw above, but the HIP side joins on a copy of the
+    oracle's context cache instead of running its own context passes, so only the fused iterations can differ from the
+    oracle (their own new cache rows included).  What the other test measures on top of this figure is what the
+    context passes' cache rows -- every one of them a rounding point that can land on the neighbouring value -- add."""
+    cfg = synth.llama_7b()
+    print(cfg.name, "decode only", flush=True)
+    errs, ties, _ = _full_depth_case(cfg, 21, (2, 5, 7), 3, oracle_cache=True)
+    _report_against_stated_tolerance(cfg.name + " decode only", errs, ties)
 
 
 def test_llama7b_full_depth_seventeen_rows_and_a_context_pass():
