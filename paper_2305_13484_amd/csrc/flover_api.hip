@@ -57,7 +57,7 @@ struct Lane {
   void *h = nullptr, *q = nullptr, *att = nullptr, *act = nullptr;
   float* part = nullptr;
   int* tok_out = nullptr;
-  int* d_stage = nullptr;   // tok | pos | slot | len | item0 | nchunk | items(4x) | context-pass blocks(4x)
+  int* d_stage = nullptr;   // tok | pos | slot | len | (2 host-only arrays) | items(4x) | context-pass blocks(4x)
   float *pml = nullptr, *po = nullptr;
   // pinned host staging; a ring so that passes can be queued without waiting for the previous copy
   int* h_stage[kStageRing] = {nullptr, nullptr, nullptr, nullptr};
@@ -319,7 +319,7 @@ int run_rows(flover_ctx* c, Lane& ln, const Row* rows, int n, bool want_tokens, 
     ln.staged_busy[ri] = false;
   }
   int* hs = ln.h_stage[ri];
-  int *tok = hs, *pos = hs + R, *slot = hs + 2 * R, *len = hs + 3 * R, *item0 = hs + 4 * R, *nchunk = hs + 5 * R;
+  int *tok = hs, *pos = hs + R, *slot = hs + 2 * R, *len = hs + 3 * R, *nchunk = hs + 5 * R;   // nchunk: host use only
   int* items = hs + 6 * R;
   int n_items = 0;
   int64_t attn_bytes = 0;   // K and V rows [0,len) of every row, all heads: what one attention launch has to read
@@ -329,7 +329,6 @@ int run_rows(flover_ctx* c, Lane& ln, const Row* rows, int n, bool want_tokens, 
     pos[i] = rows[i].pos;
     slot[i] = rows[i].slot;
     len[i] = rows[i].pos + 1;
-    item0[i] = n_items;
     const int nc = (len[i] + flk::attn_chunk() - 1) / flk::attn_chunk();
     nchunk[i] = nc;
     for (int ch = 0; ch < nc; ++ch) {
@@ -1185,18 +1184,12 @@ int32_t flover_k_decode_attention(int32_t dtype, const void* q, const void* kcac
   size_t o_items, o_pml, o_po;
   const size_t need = attn_ws_layout(M, nh, d, max_len, &o_items, &o_pml, &o_po);
   if (need > workspace_bytes) return fail(nullptr, FLOVER_E_NOMEM, "attention workspace too small");
-  std::vector<int> hs(o_items / 4 + 0);
+  std::vector<int> hs((size_t)2 * M);       // slot[M] | len[M]
   std::vector<int> items;
-  int* h_slot = hs.data();
-  int* h_len = hs.data() + M;
-  int* h_item0 = hs.data() + 2 * M;
-  int* h_nchunk = hs.data() + 3 * M;
   for (int i = 0; i < M; ++i) {
-    h_slot[i] = slot[i];
-    h_len[i] = len[i];
-    h_item0[i] = (int)items.size() / 4;
+    hs[i] = slot[i];
+    hs[M + i] = len[i];
     const int nc = (len[i] + flk::attn_chunk() - 1) / flk::attn_chunk();
-    h_nchunk[i] = nc;
     for (int ch = 0; ch < nc; ++ch) {
       items.push_back(i);
       items.push_back(ch);
@@ -1206,7 +1199,7 @@ int32_t flover_k_decode_attention(int32_t dtype, const void* q, const void* kcac
   }
   hipStream_t st = (hipStream_t)stream;
   char* ws = (char*)workspace;
-  HIPCHK(nullptr, hipMemcpyAsync(ws, hs.data(), (size_t)4 * M * 4, hipMemcpyHostToDevice, st));
+  HIPCHK(nullptr, hipMemcpyAsync(ws, hs.data(), (size_t)2 * M * 4, hipMemcpyHostToDevice, st));
   HIPCHK(nullptr, hipMemcpyAsync(ws + o_items, items.data(), items.size() * 4, hipMemcpyHostToDevice, st));
   HIPCHK(nullptr, hipStreamSynchronize(st));
   int* ds = (int*)ws;
