@@ -392,3 +392,83 @@ def test_iteration_counters_follow_section_vi_c():
         sd = math.sqrt(31) * lam / ms_per_iter
         assert abs(total - mean_total) < 4 * sd + 2
         assert abs(iters - mean_total) < 4 * sd + 2        # the printed totals sit in the same band
+
+
+@pytest.mark.parametrize("mode", ["slots", "by_length"])
+def test_scheduler_invariants_under_random_operations(tiny_gpt, mode):
+    """Properties the paper's text fixes for the scheduler, checked on the oracle after every call of a long random
+    sequence of arrivals, iterations, forced finishes and reorders (capacity 5, so the window fills up, wraps below and
+    requests queue):
+      * a new request's slot is adjacent to the live region -- the slot behind its end, or the one before its start --
+        and an empty region restarts at slot 0 (Section V-C: new request memory is placed adjacent to the current space);
+      * a request waits only when neither neighbour is free, and waiting requests are served first come first served
+        (Section V-A: more requests wait until a running one finishes);
+      * after a reorder the occupied slots are exactly the window [lo, hi): no hole is left (Section V-D);
+      * a reorder never changes which requests are live, nor their lengths or budgets; evicted are exactly the finished;
+      * every iteration advances every live request by exactly one token."""
+    cfg, w = tiny_gpt
+    cfg = dataclasses.replace(cfg, C=5, S=48)
+    srv = orc.OracleServer(cfg, w, by_length=mode == "by_length")
+    rng = np.random.default_rng(17 if mode == "slots" else 18)
+    next_id, arrival_order, admitted_order = 0, [], []
+    events = {"wait": 0, "wrap": 0, "moves": 0, "restart": 0}
+    for op in range(400):
+        st = srv.state()
+        kind = rng.choice(["add", "add", "step", "step", "step", "finish"])
+        if kind == "add":
+            P, G = int(rng.integers(1, 9)), int(rng.integers(1, 12))
+            lo, hi, waiting = st["lo"], st["hi"], st["waiting"]
+            slot = srv.add_request(next_id, rng.integers(0, cfg.V, size=P), G)
+            arrival_order.append(next_id)
+            if slot >= 0:
+                admitted_order.append(next_id)
+                assert waiting == 0                                   # nobody overtakes the queue
+                assert st["state"][slot] == 0                         # the slot was free
+                if lo == hi:
+                    assert slot == 0
+                    events["restart"] += 1
+                else:
+                    assert slot in (hi, lo - 1)
+                    events["wrap"] += slot == lo - 1
+            else:
+                events["wait"] += 1
+                assert waiting > 0 or (lo == 0 and hi == cfg.C)       # waits only when no neighbour is free
+            next_id += 1
+        elif kind == "step":
+            before = srv.state()
+            out = srv.step(False)
+            after = srv.state()
+            # requests that were waiting and got a slot in this call, in queue order
+            newly = [int(after["req_id"][s]) for s in range(cfg.C)
+                     if after["state"][s] != 0 and int(after["req_id"][s]) not in
+                     [int(before["req_id"][t]) for t in range(cfg.C) if before["state"][t] != 0]]
+            admitted_order += sorted(newly, key=arrival_order.index)
+            assert list(out.slot) == sorted(out.slot)                  # rows in slot order
+            for j in range(out.n_live):
+                s = int(out.slot[j])
+                was = before["generated"][s] if before["state"][s] in (1, 2) and before["req_id"][s] == out.req_id[j] else 0
+                assert after["generated"][s] == was + 1
+                if before["state"][s] in (1, 2) and before["req_id"][s] == out.req_id[j]:
+                    assert after["len"][s] == before["len"][s] + 1     # one more cached position
+            live_before = {int(before["req_id"][s]) for s in range(cfg.C) if before["state"][s] in (1, 2)}
+            assert live_before <= {int(r) for r in out.req_id}         # every live request advanced
+            rr = srv.reorder_evict()
+            st2 = srv.state()
+            fin = {int(out.req_id[j]) for j in range(out.n_live) if out.finished[j]}
+            assert fin <= {int(r) for r in rr.evicted}
+            occ = [int(x != 0) for x in st2["state"]]
+            assert occ == [0] * st2["lo"] + [1] * (st2["hi"] - st2["lo"]) + [0] * (cfg.C - st2["hi"])
+            survivors = {int(after["req_id"][s]): (int(after["len"][s]), int(after["generated"][s]))
+                         for s in range(cfg.C) if after["state"][s] in (1, 2)}
+            kept = {int(st2["req_id"][s]): (int(st2["len"][s]), int(st2["generated"][s]))
+                    for s in range(cfg.C) if st2["state"][s] != 0}
+            assert kept == survivors
+            events["moves"] += len(rr.moves)
+        else:
+            live = [int(st["req_id"][s]) for s in range(cfg.C) if st["state"][s] in (1, 2)]
+            if live:
+                srv.mark_finished(live[int(rng.integers(len(live)))])
+    # first come, first served: slots were handed out in arrival order
+    assert admitted_order == arrival_order[:len(admitted_order)]
+    assert all(v > 0 for v in events.values()), events
+    srv.close()
