@@ -302,6 +302,23 @@ int32_t flover_k_gemm_retile(int32_t dtype, const void* W, int32_t N, int32_t K,
 int32_t flover_k_gemm(int32_t dtype, const void* x, const void* w_tiled, int32_t M, int32_t N, int32_t K, float* y,
                       void* workspace, uint64_t workspace_bytes, void* stream);
 
+/* Input half of a gated MLP over the fused rows (the MLP call of Algorithm 2 / Section V-C for LLaMA-style models):
+ * act[M][F] = silu(x . Wgate^T) * (x . Wup^T), fp32 accumulation, rounded once to the model dtype -- the contraction
+ * and the activation in one launch, as the fused iteration runs it.  16-bit dtypes only (fp16, bf16); F % 32 == 0 and
+ * K % 512 == 0, INVAL otherwise (the step then uses flover_k_gemm's kernels and a separate activation).
+ * flover_k_gated_retile writes both matrices ([device][F][K] each) into w_tiled ([device],
+ * flover_k_gemm_tiled_bytes(dtype, 2F, K) bytes) with gate and up columns interleaved in tiles of 16;
+ * flover_k_gated_mlp streams that copy.  x [device][Mpad][K] row-major with the rows flover_k_gemm asks for readable;
+ * act [device][M][F] row-major, model dtype.  A row's result depends on that row of x alone, not on M: up to 64 rows
+ * it is one launch; above that the two halves of K go through `workspace` ([device], flover_k_gated_workspace_bytes
+ * bytes, 0 up to 64 rows; NOMEM if smaller) as partial sums and the activation is a second launch, with the same
+ * result bit for bit. */
+int32_t flover_k_gated_retile(int32_t dtype, const void* Wgate, const void* Wup, int32_t F, int32_t K, void* w_tiled,
+                              void* stream);
+int32_t flover_k_gated_workspace_bytes(int32_t dtype, int32_t M, int32_t F, int32_t K, uint64_t* out);
+int32_t flover_k_gated_mlp(int32_t dtype, const void* x, const void* w_tiled, int32_t M, int32_t F, int32_t K,
+                           void* act, void* workspace, uint64_t workspace_bytes, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

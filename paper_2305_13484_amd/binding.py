@@ -21,7 +21,7 @@ EXPORTED_SYMBOLS = [
     "flover_get_kv_cache", "flover_last_step_launches", "flover_step_submit", "flover_step_collect", "flover_set_layer_weights", "flover_k_gemm_plan", "flover_set_profile", "flover_get_profile", "flover_k_find_window", "flover_k_attention_workspace_bytes",
     "flover_k_decode_attention", "flover_k_compact_workspace_bytes", "flover_k_compact", "flover_k_gemm_tiled_bytes",
     "flover_k_gemm_workspace_bytes", "flover_k_gemm_retile", "flover_k_gemm", "flover_add_request_cached",
-    "flover_k_copy_probe", "flover_k_decode_attention_noalloc",
+    "flover_k_copy_probe", "flover_k_decode_attention_noalloc", "flover_k_gated_retile", "flover_k_gated_workspace_bytes", "flover_k_gated_mlp",
 ]
 
 WEIGHT_FIELDS = ["wte", "wpe", "ln1_g", "ln1_b", "wqkv", "bqkv", "wo", "bo", "ln2_g", "ln2_b", "w1", "b1", "wu", "w2",
@@ -108,6 +108,10 @@ def load_library():
     L.flover_k_gemm_retile.argtypes = [C.c_int32, C.c_void_p, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p]
     L.flover_k_gemm.argtypes = [C.c_int32, C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_void_p,
                                 C.c_void_p, C.c_uint64, C.c_void_p]
+    L.flover_k_gated_retile.argtypes = [C.c_int32, C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p]
+    L.flover_k_gated_workspace_bytes.argtypes = [C.c_int32] * 4 + [C.POINTER(C.c_uint64)]
+    L.flover_k_gated_mlp.argtypes = [C.c_int32, C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_void_p,
+                                     C.c_void_p, C.c_uint64, C.c_void_p]
     _lib = L
     return L
 
@@ -399,6 +403,41 @@ def k_gemm(x: torch.Tensor, W, out: Optional[torch.Tensor] = None, workspace: Op
     _check(load_library().flover_k_gemm(tw.dtype, xp.data_ptr(), tw.buf.data_ptr(), M, tw.N, K, out.data_ptr(),
                                         workspace.data_ptr(), workspace.numel(), _stream_ptr()))
     torch.cuda.current_stream().synchronize()
+    return out
+
+
+class GatedWeight:
+    """Gate and up projections [F][K] of a gated MLP, re-tiled together for k_gated_mlp."""
+
+    def __init__(self, Wgate: torch.Tensor, Wup: torch.Tensor):
+        assert Wgate.shape == Wup.shape and Wgate.dtype == Wup.dtype and Wgate.is_contiguous() and Wup.is_contiguous()
+        self.F, self.K = Wgate.shape
+        self.dtype = _DT_OF[Wgate.dtype]
+        n = C.c_uint64()
+        _check(load_library().flover_k_gemm_tiled_bytes(self.dtype, 2 * self.F, self.K, C.byref(n)))
+        self.buf = torch.empty(int(n.value), dtype=torch.uint8, device="cuda")
+        _check(load_library().flover_k_gated_retile(self.dtype, Wgate.data_ptr(), Wup.data_ptr(), self.F, self.K,
+                                                    self.buf.data_ptr(), _stream_ptr()))
+
+
+def k_gated_mlp(x: torch.Tensor, gw: GatedWeight, out: Optional[torch.Tensor] = None, sync: bool = True):
+    """act[M][F] = silu(x . Wgate^T) * (x . Wup^T) in the model dtype, one launch."""
+    M, K = x.shape
+    assert K == gw.K and _DT_OF[x.dtype] == gw.dtype
+    rows = (M + 127) // 128 * 128 if M <= 128 else (M + 255) // 256 * 256
+    xp = x
+    if M != rows:
+        xp = torch.zeros((rows, K), dtype=x.dtype, device=x.device)
+        xp[:M] = x
+    if out is None:
+        out = torch.empty((M, gw.F), dtype=x.dtype, device=x.device)
+    n = C.c_uint64()
+    _check(load_library().flover_k_gated_workspace_bytes(gw.dtype, M, gw.F, K, C.byref(n)))
+    ws = torch.empty(max(int(n.value), 16), dtype=torch.uint8, device="cuda")
+    _check(load_library().flover_k_gated_mlp(gw.dtype, xp.data_ptr(), gw.buf.data_ptr(), M, gw.F, K, out.data_ptr(),
+                                             ws.data_ptr(), int(n.value), _stream_ptr()))
+    if sync:
+        torch.cuda.current_stream().synchronize()
     return out
 
 

@@ -190,7 +190,7 @@ size_t layout(flover_ctx* c, char* base) {
   Bump b{base};
   c->p_qkv = flk::gemm_plan(f.dtype, 3 * H, H);
   c->p_o = flk::gemm_plan(f.dtype, H, H);
-  c->p_1 = flk::gemm_plan(f.dtype, gpt ? F : 2 * F, H);
+  c->p_1 = gpt ? flk::gemm_plan(f.dtype, F, H) : flk::gemm_plan_gated(f.dtype, F, H);
   c->p_2 = flk::gemm_plan(f.dtype, H, F);
   c->p_lm = flk::gemm_plan(f.dtype, V, H);
   c->lw.resize(L);
@@ -291,12 +291,14 @@ void prof_collect(flover_ctx* c, size_t upto = (size_t)-1) {
   }
 }
 // `sampled`: this launch is one of those level 1 times (level 2 times every launch).
+// gated_out: the plan is a paired gate|up plan and the launch is the fused one that writes the activation there.
 hipError_t timed_gemm(flover_ctx* c, Lane& ln, int kind, const void* x, const void* w, int n, const flk::GemmPlan& p,
-                      size_t ss, int mtt, bool sampled) {
+                      size_t ss, int mtt, bool sampled, void* gated_out = nullptr) {
   const int64_t bytes = (int64_t)flk::gemm_tiled_bytes(c->cfg.dtype, p.N, p.K);
   const int pi = (&ln == &c->step_lane && c->prof_now && (sampled || c->profile >= 2)) ? prof_begin(c, kind, bytes) : -1;
   if (pi >= 0) (void)hipEventRecord(c->ev[2 * pi], ln.st);
-  hipError_t e = flk::gemm(c->cfg.dtype, x, w, n, p, ln.part, ss, mtt, ln.st);
+  hipError_t e = gated_out ? flk::gemm_gated(c->cfg.dtype, x, w, n, p, gated_out, ln.part, ss, mtt, ln.st)
+                           : flk::gemm(c->cfg.dtype, x, w, n, p, ln.part, ss, mtt, ln.st);
   if (pi >= 0) (void)hipEventRecord(c->ev[2 * pi + 1], ln.st);
   return e;
 }
@@ -421,8 +423,14 @@ int run_rows(flover_ctx* c, Lane& ln, const Row* rows, int n, bool want_tokens, 
     }
     HIPCHK(c, timed_gemm(c, ln, FLOVER_PROF_GEMM_OUT, ln.att, w.wo, n, p_o, ss_h, mtt, gs));
     HIPCHK(c, flk::add_norm(f.dtype, !gpt, ln.x, ln.part, p_o.S, ss_h, p_o.ldc, w.bo, w.ln2_g, w.ln2_b, ln.h, n, H, f.norm_eps, mtt, st));
-    HIPCHK(c, timed_gemm(c, ln, FLOVER_PROF_GEMM_FF1, ln.h, w.w1, n, p_1, ss_1, mtt, gs));
-    HIPCHK(c, flk::activation(f.dtype, !gpt, ln.part, p_1.S, ss_1, p_1.ldc, w.b1, ln.act, n, F, mtt, st));
+    if (p_1.paired && !context_pass) {
+      // fused iterations of a gated model: the activation is the epilogue of the gate|up contraction
+      HIPCHK(c, timed_gemm(c, ln, FLOVER_PROF_GEMM_FF1, ln.h, w.w1, n, p_1, ss_1, mtt, gs, ln.act));
+      if (n <= flk::kGatedFusedRows) launches -= 1;
+    } else {
+      HIPCHK(c, timed_gemm(c, ln, FLOVER_PROF_GEMM_FF1, ln.h, w.w1, n, p_1, ss_1, mtt, gs));
+      HIPCHK(c, flk::activation(f.dtype, !gpt, ln.part, p_1.S, ss_1, p_1.ldc, w.b1, ln.act, n, F, mtt, st, p_1.paired));
+    }
     HIPCHK(c, timed_gemm(c, ln, FLOVER_PROF_GEMM_FF2, ln.act, w.w2, n, p_2, ss_h, mtt, gs));
     launches += 10;
   }
@@ -551,8 +559,13 @@ int load_layer(flover_ctx* c, int l, const flover_weights* w, int src_l) {
   }
   HIPCHK(c, flk::retile(f.dtype, at(w->wqkv, 3 * H * H), 3 * f.hidden, f.hidden, lw.wqkv, 0, c->p_qkv.NT, st));
   HIPCHK(c, flk::retile(f.dtype, at(w->wo, H * H), f.hidden, f.hidden, lw.wo, 0, c->p_o.NT, st));
-  HIPCHK(c, flk::retile(f.dtype, at(w->w1, F * H), f.ffn, f.hidden, lw.w1, 0, c->p_1.NT, st));
-  if (!gpt) HIPCHK(c, flk::retile(f.dtype, at(w->wu, F * H), f.ffn, f.hidden, lw.w1, f.ffn, c->p_1.NT, st));
+  if (c->p_1.paired) {   // gate and up tiles alternate: a 32-column group holds both projections of 16 MLP columns
+    HIPCHK(c, flk::retile(f.dtype, at(w->w1, F * H), f.ffn, f.hidden, lw.w1, 0, c->p_1.NT, st, 2));
+    HIPCHK(c, flk::retile(f.dtype, at(w->wu, F * H), f.ffn, f.hidden, lw.w1, 16, c->p_1.NT, st, 2));
+  } else {
+    HIPCHK(c, flk::retile(f.dtype, at(w->w1, F * H), f.ffn, f.hidden, lw.w1, 0, c->p_1.NT, st));
+    if (!gpt) HIPCHK(c, flk::retile(f.dtype, at(w->wu, F * H), f.ffn, f.hidden, lw.w1, f.ffn, c->p_1.NT, st));
+  }
   HIPCHK(c, flk::retile(f.dtype, at(w->w2, H * F), f.hidden, f.ffn, lw.w2, 0, c->p_2.NT, st));
   if (gpt) {
     if ((rc = copy_in(c, lw.ln1_b, at(w->ln1_b, H), H * e, "ln1_b")) != FLOVER_OK) return rc;
@@ -1437,5 +1450,42 @@ extern "C" int32_t flover_k_gemm(int32_t dtype, const void* x, const void* w_til
     flk::slice_sum_kernel<<<(unsigned)((total + 255) / 256), 256, 0, st>>>((const float*)workspace, p.S, stride, p.ldc, y, M, N);
     HIPCHK(nullptr, hipGetLastError());
   }
+  return FLOVER_OK;
+}
+
+extern "C" int32_t flover_k_gated_retile(int32_t dtype, const void* Wgate, const void* Wup, int32_t F, int32_t K,
+                                         void* w_tiled, void* stream) {
+  if (dtype < FLOVER_F16 || dtype > FLOVER_BF16 || !Wgate || !Wup || !w_tiled || F < 32 || K < 32 || K % 32)
+    return fail(nullptr, FLOVER_E_INVAL, "bad argument");
+  const flk::GemmPlan p = flk::gemm_plan_gated(dtype, F, K);
+  if (!p.paired) return fail(nullptr, FLOVER_E_INVAL, "shape not served by the fused gated kernels");
+  hipStream_t st = (hipStream_t)stream;
+  HIPCHK(nullptr, flk::zero_fill(w_tiled, flk::gemm_tiled_bytes(dtype, 2 * F, K), st));
+  HIPCHK(nullptr, flk::retile(dtype, Wgate, F, K, w_tiled, 0, p.NT, st, 2));
+  HIPCHK(nullptr, flk::retile(dtype, Wup, F, K, w_tiled, 16, p.NT, st, 2));
+  return FLOVER_OK;
+}
+
+extern "C" int32_t flover_k_gated_workspace_bytes(int32_t dtype, int32_t M, int32_t F, int32_t K, uint64_t* out) {
+  if (dtype < FLOVER_F16 || dtype > FLOVER_BF16 || M < 0 || F < 32 || K < 32 || K % 32 || !out)
+    return fail(nullptr, FLOVER_E_INVAL, "bad argument");
+  const flk::GemmPlan p = flk::gemm_plan_gated(dtype, F, K);
+  if (!p.paired) return fail(nullptr, FLOVER_E_INVAL, "shape not served by the fused gated kernels");
+  *out = M > flk::kGatedFusedRows ? align_up((size_t)p.S * M * p.ldc * 4, 256) : 0;
+  return FLOVER_OK;
+}
+
+extern "C" int32_t flover_k_gated_mlp(int32_t dtype, const void* x, const void* w_tiled, int32_t M, int32_t F, int32_t K,
+                                      void* act, void* workspace, uint64_t workspace_bytes, void* stream) {
+  if (dtype < FLOVER_F16 || dtype > FLOVER_BF16 || M < 0 || F < 32 || K < 32 || K % 32)
+    return fail(nullptr, FLOVER_E_INVAL, "bad argument");
+  const flk::GemmPlan p = flk::gemm_plan_gated(dtype, F, K);
+  if (!p.paired) return fail(nullptr, FLOVER_E_INVAL, "shape not served by the fused gated kernels");
+  if (M == 0) return FLOVER_OK;
+  if (!x || !w_tiled || !act) return fail(nullptr, FLOVER_E_INVAL, "null argument");
+  const size_t stride = (size_t)M * p.ldc;
+  if (M > flk::kGatedFusedRows && (!workspace || (size_t)p.S * stride * 4 > workspace_bytes))
+    return fail(nullptr, FLOVER_E_NOMEM, "gated workspace too small");
+  HIPCHK(nullptr, flk::gemm_gated(dtype, x, w_tiled, M, p, act, (float*)workspace, stride, 0, (hipStream_t)stream));
   return FLOVER_OK;
 }

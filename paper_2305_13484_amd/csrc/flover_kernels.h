@@ -15,22 +15,37 @@ struct GemmPlan {
   int S;      // split-K slices, a function of (N, K) only
   int kbs;    // k-blocks per slice
   int ldc;    // row length of the partial-sum slices (N rounded up to 4)
+  int paired = 0;   // gate|up of a gated MLP in paired 32-column groups (see gemm_plan_gated)
 };
 inline int part_ld(int N) { return (N + 3) / 4 * 4; }
 GemmPlan gemm_plan(int dtype, int N, int K);
+// gate|up of a gated MLP with F columns each.  paired = 1: group j of the layout holds gate columns 16j..16j+15 then up
+// columns 16j..16j+15 (re-tile gate with n_off = 0 and up with n_off = 16, both with tile_step = 2), K is cut in two
+// halves, gemm_gated() serves the fused iterations, and gemm() writes its partial sums in that column order (gate column
+// j at (j/16)*32 + j%16, up column j 16 further).  paired = 0 (fp32, or a shape the fused kernels do not take): gemm_plan(2F, K), up after gate.
+GemmPlan gemm_plan_gated(int dtype, int F, int K);
 size_t gemm_tiled_bytes(int dtype, int N, int K);
 // Slicing for a context pass of M rows of one request (a function of the matrix shape and of that request's own row
 // count only): same tiling, its own number of K slices, at most max_slices (what the partial-sum buffer holds) and 16.
 GemmPlan context_plan(const GemmPlan& p, int dtype, int M, int max_slices);
 // Re-tile W [N][K] into `tiled` starting at output column n_off (multiple of 16) of a possibly larger matrix whose
 // plan uses NT n-tiles per column group.
-hipError_t retile(int dtype, const void* W, int N, int K, void* tiled, int n_off, int NT, hipStream_t st);
+// Tile t of W lands at tile position n_off/16 + t * tile_step of the layout.
+hipError_t retile(int dtype, const void* W, int N, int K, void* tiled, int n_off, int NT, hipStream_t st,
+                  int tile_step = 1);
 hipError_t zero_fill(void* p, size_t bytes, hipStream_t st);
 // part[s][m][p.ldc] (slice stride in floats) = x[M][K] . W^T over slice s of K.
 // xmtt == 0: x is row-major [gemm_rows_read(M)][K]; xmtt = ceil(M/16) (16-bit dtypes only): x is in fragment order
 // (tiles of 16 rows x 32 k, [k-block][row tile], see xrow_index) and the buffer holds K/32 * gemm_rows_read(M)/16 tiles.
 hipError_t gemm(int dtype, const void* x, const void* w_tiled, int M, const GemmPlan& p, float* part,
                 size_t slice_stride, int xmtt, hipStream_t st);
+// act[M][F] = silu(x . Wgate^T) * (x . Wup^T) rounded to the model dtype, for a paired plan (16-bit dtypes); x and act
+// are both row-major (xmtt == 0) or both in fragment order with xmtt row tiles per k-block; reads the rows gemm() reads.
+// part / slice_stride as for gemm(): used above kGatedFusedRows rows, where the contraction and the activation are
+// two launches (same result, bit for bit).
+constexpr int kGatedFusedRows = 64;
+hipError_t gemm_gated(int dtype, const void* x, const void* w_tiled, int M, const GemmPlan& p, void* act, float* part,
+                      size_t slice_stride, int xmtt, hipStream_t st);
 // rows of x that gemm() may read for M live rows
 inline int gemm_rows_read(int M) {
   return M <= 16 ? 16 : M <= 32 ? 32 : M <= 64 ? 64 : M <= 128 ? 128 : (M + 255) / 256 * 256;
@@ -48,8 +63,9 @@ hipError_t add_norm(int dtype, bool rms, float* x, const float* part, int S, siz
 hipError_t qkv_post(int dtype, const float* part, int S, size_t stride, int ldp, const void* bias, const float* rope_cs,
                     const int* slot, const int* pos, void* q, void* kcache, void* vcache, int M, int H, int nh, int d,
                     int Smax, hipStream_t st);
+// paired: gate and up columns of `part` interleaved in tiles of 16 (see gemm_plan_gated); gated activation only.
 hipError_t activation(int dtype, bool swiglu, const float* part, int S, size_t stride, int ldp, const void* bias, void* a,
-                      int M, int F, int mtt, hipStream_t st);
+                      int M, int F, int mtt, hipStream_t st, bool paired = false);
 hipError_t logits_argmax(const float* part, int S, size_t stride, int ldp, float* logits, int* tok, int M, int V,
                          hipStream_t st);
 

@@ -177,7 +177,7 @@ __global__ void qkv_post_kernel(const float* __restrict__ part, int S, size_t st
 template <int DT, int SWIGLU>
 __global__ __launch_bounds__(256) void act_kernel(const float* __restrict__ part, int S, size_t stride, int ldp,
                                                   const void* __restrict__ bias, void* __restrict__ a, int F, long total4,
-                                                  int mtt) {
+                                                  int mtt, int paired) {
   const long idx = (long)blockIdx.x * 256 + threadIdx.x;
   if (idx >= total4) return;
   const int F4 = F >> 2;
@@ -185,8 +185,10 @@ __global__ __launch_bounds__(256) void act_kernel(const float* __restrict__ part
   const int j = (int)(idx - m * F4) * 4;
   f32x4_t o;
   if (SWIGLU) {
-    const f32x4_t g = psum4(part, S, stride, (size_t)m * ldp + j);
-    const f32x4_t u = psum4(part, S, stride, (size_t)m * ldp + F + j);
+    // gate column j and up column j: side by side halves of the row, or (paired) tiles of 16 interleaved
+    const size_t gj = paired ? (size_t)(j >> 4) * 32 + (j & 15) : (size_t)j, uj = paired ? gj + 16 : (size_t)F + j;
+    const f32x4_t g = psum4(part, S, stride, (size_t)m * ldp + gj);
+    const f32x4_t u = psum4(part, S, stride, (size_t)m * ldp + uj);
     o = act_swiglu(g, u);
   } else {
     const f32x4_t t = psum4(part, S, stride, (size_t)m * ldp + j) + ldv4<DT>(bias, j);
@@ -266,14 +268,15 @@ hipError_t qkv_post(int dtype, const float* part, int S, size_t stride, int ldp,
 }
 
 hipError_t activation(int dtype, bool swiglu, const float* part, int S, size_t stride, int ldp, const void* bias, void* a,
-                      int M, int F, int mtt, hipStream_t st) {
+                      int M, int F, int mtt, hipStream_t st, bool paired) {
   if (M <= 0) return hipSuccess;
+  if (paired && !swiglu) return hipErrorInvalidValue;
   const long total = (long)M * (F / 4);
   const unsigned grid = (unsigned)((total + 255) / 256);
   if (swiglu) {
-    FLK_DT_SWITCH(dtype, (act_kernel<DT, 1><<<grid, 256, 0, st>>>(part, S, stride, ldp, bias, a, F, total, mtt)));
+    FLK_DT_SWITCH(dtype, (act_kernel<DT, 1><<<grid, 256, 0, st>>>(part, S, stride, ldp, bias, a, F, total, mtt, paired ? 1 : 0)));
   } else {
-    FLK_DT_SWITCH(dtype, (act_kernel<DT, 0><<<grid, 256, 0, st>>>(part, S, stride, ldp, bias, a, F, total, mtt)));
+    FLK_DT_SWITCH(dtype, (act_kernel<DT, 0><<<grid, 256, 0, st>>>(part, S, stride, ldp, bias, a, F, total, mtt, 0)));
   }
   return hipGetLastError();
 }

@@ -33,7 +33,7 @@ namespace flk {
 // ---------------------------------------------------------------- re-tiling (init time)
 
 __global__ void retile16_kernel(const uint16_t* __restrict__ W, u32x4_t* __restrict__ wt, int N, int K, int KB,
-                                int ntile0, int NT, long total) {
+                                int ntile0, int tstep, int NT, long total) {
   long i = (long)blockIdx.x * blockDim.x + threadIdx.x;
   if (i >= total) return;
   int lane = (int)(i & 63);
@@ -44,7 +44,7 @@ __global__ void retile16_kernel(const uint16_t* __restrict__ W, u32x4_t* __restr
   int k = kb * 32 + (lane >> 4) * 8;
   u32x4_t v = {0u, 0u, 0u, 0u};
   if (n < N) v = *(const u32x4_t*)(W + (size_t)n * K + k);
-  const int tile = ntile0 + ntile, g = tile / NT, tt = tile - g * NT;
+  const int tile = ntile0 + ntile * tstep, g = tile / NT, tt = tile - g * NT;
   wt[(((size_t)g * KB + kb) * NT + tt) * 64 + lane] = v;
 }
 
@@ -259,6 +259,126 @@ __global__ __launch_bounds__(64 * GPB * (NT / NTW)) void gemm16_lds_kernel(const
     }
 }
 
+// ---- gated MLP input (fused iterations of 16-bit gated models): the gate|up contraction with the activation as its
+// epilogue, so that neither partial sums nor the two projections reach memory and the activation needs no launch.
+// The matrix is laid out in "paired" groups of 32 columns -- group j = [gate columns 16j..16j+15 | up columns
+// 16j..16j+15] -- so a lane's accumulators of a group's two n-tiles are gate and up of the same four MLP columns.
+// K is split in two halves inside the block: 8 waves = 4 column groups x 2 halves, each wave the MFMA chain over its
+// half's k-blocks in order, each half with its own x tile in LDS (fragment order, double-buffered chunks of KC
+// k-blocks, W ring PF k-blocks deep); at the end the second half hands its sums to the first through LDS, which adds
+// first half + second half, applies silu(gate) * up and writes the result, rounded to the model dtype, as the next
+// GEMM's row operand (row-major or fragment order).  The result of a row is the same for every MT and equal, bit for
+// bit, to gemm() with the halves as two K slices followed by the stand-alone activation.
+// Every chunk is full and the last ring turn is the only one whose chunks may lack a successor, so the steady state
+// is free of branches.  Requires KB % 16 == 0.
+template <int DT, int MT, int KC, int PF>
+__global__ __launch_bounds__(512) void gated_lds_kernel(const uint16_t* __restrict__ x, const u32x4_t* __restrict__ wt,
+                                                        void* __restrict__ act, int M, int F, int ngroups, int KB,
+                                                        int nx, int nz, int xmtt) {
+  static_assert(PF % KC == 0 && KC >= 2, "ring shape; the hand-over below reuses the x tiles' LDS");
+  constexpr int GPB = 4;                         // column groups per block (128 columns); waves that stage one x tile
+  __shared__ u32x4_t lds[2][2][KC * MT * 64];    // [half][buffer]
+  constexpr int FPW = (KC * MT + GPB - 1) / GPB;
+  constexpr int CPR = PF / KC;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int half = wave / GPB, gw = wave % GPB;
+  const int xcd = blockIdx.x & 7, qq = blockIdx.x >> 3;     // row blocks of one column block share an XCD's L2
+  const int zb = qq % nz, bx = (qq / nz) * 8 + xcd;
+  if (bx >= nx) return;                          // padding of the grid (whole block)
+  const int g = bx * GPB + gw;
+  const int gl = min(g, ngroups - 1);            // surplus waves repeat the last group (they still serve the barriers)
+  const int m0 = zb * (16 * MT);
+  const int K = KB * 32;
+  const int kb0 = half * (KB >> 1), kb1 = kb0 + (KB >> 1);
+  const int nchunks = (kb1 - kb0) / KC;
+
+  f32x4_t acc[MT][2];
+#pragma unroll
+  for (int i = 0; i < MT; ++i)
+#pragma unroll
+    for (int t = 0; t < 2; ++t) acc[i][t] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+
+  const u32x4_t* wp = wt + ((size_t)gl * KB) * 2 * 64 + lane;                    // + (kb*2 + t)*64
+  const size_t tstride = xmtt ? 512 : (size_t)16 * K, kstride = xmtt ? (size_t)xmtt * 512 : 32;
+  const uint16_t* xp = xmtt ? x + (size_t)(m0 >> 4) * 512 + lane * 8
+                            : x + (size_t)(m0 + (lane & 15)) * K + (lane >> 4) * 8;     // + i*tstride + kb*kstride
+
+  u32x4_t bq[PF][2], areg[FPW];
+#pragma unroll
+  for (int j = 0; j < PF; ++j)
+#pragma unroll
+    for (int t = 0; t < 2; ++t) bq[j][t] = __builtin_nontemporal_load(wp + ((size_t)(kb0 + j) * 2 + t) * 64);
+  auto load_a = [&](int chunk) {
+#pragma unroll
+    for (int j = 0; j < FPW; ++j) {
+      const int f = min(gw + GPB * j, KC * MT - 1), kc = f / MT, i = f - kc * MT;
+      areg[j] = *(const u32x4_t*)(xp + i * tstride + (kb0 + chunk * KC + kc) * kstride);
+    }
+  };
+  auto store_a = [&](int buf) {      // surplus fragments store the last one once more (same data, no branch)
+#pragma unroll
+    for (int j = 0; j < FPW; ++j) lds[half][buf][min(gw + GPB * j, KC * MT - 1) * 64 + lane] = areg[j];
+  };
+  load_a(0);
+  store_a(0);
+  __syncthreads();
+  // One chunk: stage the next x tile, multiply this one, refill the W ring.
+  auto chunk = [&](auto cc_, auto last_, int c) {
+    constexpr int cc = decltype(cc_)::value;
+    constexpr bool last = decltype(last_)::value;
+    const bool more = !last || c + 1 < nchunks;
+    if (more) load_a(c + 1);
+    __builtin_amdgcn_sched_barrier(0);
+    const u32x4_t* la = lds[half][c & 1];
+#pragma unroll
+    for (int kc = 0; kc < KC; ++kc) {
+      const int kb = kb0 + c * KC + kc;
+      u32x4_t af[MT];
+#pragma unroll
+      for (int i = 0; i < MT; ++i) af[i] = la[(kc * MT + i) * 64 + lane];
+#pragma unroll
+      for (int i = 0; i < MT; ++i)
+#pragma unroll
+        for (int t = 0; t < 2; ++t) acc[i][t] = mfma16<DT>(bq[cc * KC + kc][t], af[i], acc[i][t]);
+      const int kk = min(kb + PF, kb1 - 1);      // the last turn re-reads the last block (in bounds, unused)
+#pragma unroll
+      for (int t = 0; t < 2; ++t) bq[cc * KC + kc][t] = __builtin_nontemporal_load(wp + ((size_t)kk * 2 + t) * 64);
+      __builtin_amdgcn_sched_barrier(0);
+    }
+    if (more) store_a((c + 1) & 1);
+    __syncthreads();
+  };
+  auto ring_turn = [&](auto last_, int c) {
+    static_assert(CPR <= 4, "chunks per ring turn");
+    if constexpr (CPR >= 1) chunk(std::integral_constant<int, 0>{}, last_, c);
+    if constexpr (CPR >= 2) chunk(std::integral_constant<int, 1>{}, last_, c + 1);
+    if constexpr (CPR >= 3) chunk(std::integral_constant<int, 2>{}, last_, c + 2);
+    if constexpr (CPR >= 4) chunk(std::integral_constant<int, 3>{}, last_, c + 3);
+  };
+  int c = 0;
+  for (; c + CPR < nchunks; c += CPR) ring_turn(std::false_type{}, c);
+  ring_turn(std::true_type{}, c);
+  // second half -> first half through LDS (the x tiles are no longer read: every wave is past the last barrier)
+  f32x4_t* red = (f32x4_t*)&lds[0][0][0];
+  static_assert(sizeof(lds) >= (size_t)GPB * MT * 2 * 64 * sizeof(f32x4_t), "hand-over space");
+  if (half == 1) {
+#pragma unroll
+    for (int i = 0; i < MT; ++i)
+#pragma unroll
+      for (int t = 0; t < 2; ++t) red[((gw * MT + i) * 2 + t) * 64 + lane] = acc[i][t];
+  }
+  __syncthreads();
+  if (half == 1 || g >= ngroups) return;
+  const int j = g * 16 + (lane >> 4) * 4;
+#pragma unroll
+  for (int i = 0; i < MT; ++i) {
+    const f32x4_t gate = acc[i][0] + red[((gw * MT + i) * 2 + 0) * 64 + lane];
+    const f32x4_t up = acc[i][1] + red[((gw * MT + i) * 2 + 1) * 64 + lane];
+    const int m = m0 + i * 16 + (lane & 15);
+    if (m < M) stv4<DT>(act, xrow_index(m, j, F, xmtt), act_swiglu(gate, up));
+  }
+}
+
 // ---- context passes (hundreds of rows): the contraction is MFMA-bound there, so each wave keeps a 128 x 64 output
 // tile (MTW = 8 row tiles x NT = 4 n-tiles, 128 accumulator registers): per k-block 32 MFMAs for 8 KiB of LDS reads and
 // 4 KiB of W loads, which halves the operand traffic per flop of the 128-row kernel above (whose waves own 128 x 32).
@@ -437,6 +557,21 @@ GemmPlan gemm_plan(int dtype, int N, int K) {
   return p;
 }
 
+// gate|up of a gated MLP (N = 2F): paired 32-column groups, no K slices (the fused kernels split K in two inside),
+// when the shape allows it; otherwise the plain plan of a 2F-column matrix with gate and up side by side.
+GemmPlan gemm_plan_gated(int dtype, int F, int K) {
+  GemmPlan p = gemm_plan(dtype, 2 * F, K);
+#ifdef FLK_NO_GATED
+  return p;
+#endif
+  if (dtype == DT_F32 || F % 32 != 0 || (K / 32) % 16 != 0) return p;
+  p.NT = 2;
+  p.S = 2;               // the two halves of K: partial sums of gemm(), the two in-kernel chains of the fused kernels
+  p.kbs = p.KB / 2;
+  p.paired = 1;
+  return p;
+}
+
 size_t gemm_tiled_bytes(int dtype, int N, int K) {
   if (dtype == DT_F32) return (size_t)N * K * 4;
   const size_t Npad = (size_t)(N + 63) / 64 * 64;
@@ -470,14 +605,16 @@ GemmPlan context_plan(const GemmPlan& p, int dtype, int M, int max_slices) {
   return q;
 }
 
-hipError_t retile(int dtype, const void* W, int N, int K, void* tiled, int n_off, int NT, hipStream_t st) {
-  if (dtype == DT_F32)
+hipError_t retile(int dtype, const void* W, int N, int K, void* tiled, int n_off, int NT, hipStream_t st, int tile_step) {
+  if (dtype == DT_F32) {
+    if (tile_step != 1) return hipErrorInvalidValue;
     return hipMemcpyAsync((char*)tiled + (size_t)n_off * K * 4, W, (size_t)N * K * 4, hipMemcpyDeviceToDevice, st);
+  }
   const int KB = K / 32;
   const int ntiles = (N + 15) / 16;
   const long total = (long)ntiles * KB * 64;
   retile16_kernel<<<dim3((unsigned)((total + 255) / 256)), 256, 0, st>>>((const uint16_t*)W, (u32x4_t*)tiled, N, K, KB,
-                                                                         n_off / 16, NT, total);
+                                                                         n_off / 16, tile_step, NT, total);
   return hipGetLastError();
 }
 
@@ -491,7 +628,7 @@ static void launch_direct(const void* x, const void* wt, float* part, int M, con
   gemm16_direct_kernel<DT, MT, NT, PFW, PFA><<<grid, 256, 0, st>>>((const uint16_t*)x, (const u32x4_t*)wt, part, M, p.N, p.K,
                                                              ngroups, p.KB, p.kbs, ss, p.ldc, xmtt);
 }
-template <int DT, int MT, int NT, int NTW, int PF, int GPB = 4>
+template <int DT, int MT, int NT, int NTW, int PF, int GPB = 4, int KC = 2>
 static void launch_lds(const void* x, const void* wt, float* part, int M, const GemmPlan& p, size_t ss, int xmtt,
                        hipStream_t st) {
                                                 // GPB column groups per block: 256 columns, or 128 for the 32-column groups
@@ -499,7 +636,7 @@ static void launch_lds(const void* x, const void* wt, float* part, int M, const 
   const int ngroups = p.Npad / (16 * NT);
   const int nx = (ngroups + GPB - 1) / GPB, nz = (M + 16 * MT - 1) / (16 * MT);
   const int tasks8 = (nx * p.S + 7) / 8 * 8;
-  gemm16_lds_kernel<DT, MT, NT, NTW, 2, PF, GPB><<<dim3(tasks8 * nz), 64 * GPB * (NT / NTW), 0, st>>>(
+  gemm16_lds_kernel<DT, MT, NT, NTW, KC, PF, GPB><<<dim3(tasks8 * nz), 64 * GPB * (NT / NTW), 0, st>>>(
       (const uint16_t*)x, (const u32x4_t*)wt, part, M, p.N, p.K, ngroups, p.KB, p.kbs, ss, p.ldc, nx, p.S, nz, xmtt);
 }
 
@@ -519,8 +656,40 @@ static void dispatch16(const void* x, const void* wt, float* part, int M, const 
   if (M <= 16) launch_direct<DT, 1, NT, 8, 8>(x, wt, part, M, p, ss, xmtt, st);
   else if (M <= 32) launch_lds<DT, 2, NT, NT, 4>(x, wt, part, M, p, ss, xmtt, st);     // 4 waves, one per column group
   else if (M <= 64) launch_lds<DT, 4, NT, 2, 4>(x, wt, part, M, p, ss, xmtt, st);      // 8 waves, two per column group
-  else if (M <= 128) launch_lds<DT, 8, NT, 2, 4>(x, wt, part, M, p, ss, xmtt, st);
-  else launch_rows<DT, NT>(x, wt, part, M, p, ss, xmtt, st);             // row blocks of 256
+  else if (M <= 128) {
+    if (NT == 2 && p.paired) launch_lds<DT, 8, NT, 2, 4, 8>(x, wt, part, M, p, ss, xmtt, st);   // 8 groups: 256 columns
+    else launch_lds<DT, 8, NT, 2, 4>(x, wt, part, M, p, ss, xmtt, st);
+  } else launch_rows<DT, NT>(x, wt, part, M, p, ss, xmtt, st);             // row blocks of 256
+}
+
+template <int DT>
+static void dispatch_gated(const void* x, const void* wt, void* act, int M, const GemmPlan& p, int xmtt, hipStream_t st) {
+  const int F = p.N / 2, ngroups = F / 16, nx = (ngroups + 3) / 4, nx8 = (nx + 7) / 8 * 8;
+  const uint16_t* xx = (const uint16_t*)x;
+  const u32x4_t* ww = (const u32x4_t*)wt;
+  if (M <= 16)
+    gated_lds_kernel<DT, 1, 4, 8><<<dim3(nx8), 512, 0, st>>>(xx, ww, act, M, F, ngroups, p.KB, nx, 1, xmtt);
+  else if (M <= 32)
+    gated_lds_kernel<DT, 2, 2, 8><<<dim3(nx8), 512, 0, st>>>(xx, ww, act, M, F, ngroups, p.KB, nx, 1, xmtt);
+  else
+    gated_lds_kernel<DT, 4, 2, 8><<<dim3(nx8), 512, 0, st>>>(xx, ww, act, M, F, ngroups, p.KB, nx, 1, xmtt);
+}
+
+// Up to kGatedFusedRows rows one launch; above that the x tile of a 128-column block would weigh as much as its
+// weights, so the contraction runs as gemm() over 256-column blocks with the two K halves as partial sums and the
+// activation as its own launch -- the same two chains, added in the same order, rounded once: bit-identical results.
+hipError_t gemm_gated(int dtype, const void* x, const void* wt, int M, const GemmPlan& p, void* act, float* part,
+                      size_t slice_stride, int xmtt, hipStream_t st) {
+  if (M <= 0) return hipSuccess;
+  if (!p.paired || dtype == DT_F32 || p.S != 2) return hipErrorInvalidValue;
+  if (M > kGatedFusedRows) {
+    hipError_t e = gemm(dtype, x, wt, M, p, part, slice_stride, xmtt, st);
+    if (e != hipSuccess) return e;
+    return activation(dtype, true, part, p.S, slice_stride, p.ldc, nullptr, act, M, p.N / 2, xmtt, st, true);
+  }
+  if (dtype == DT_BF16) dispatch_gated<DT_BF16>(x, wt, act, M, p, xmtt, st);
+  else dispatch_gated<DT_F16>(x, wt, act, M, p, xmtt, st);
+  return hipGetLastError();
 }
 
 hipError_t gemm(int dtype, const void* x, const void* wt, int M, const GemmPlan& p, float* part, size_t slice_stride,

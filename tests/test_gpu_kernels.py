@@ -77,6 +77,79 @@ def test_gemm_full_size_sampled_columns(M):
         del W
 
 
+# ---------------------------------------------------------------- gated MLP input (contraction + activation, one launch)
+
+def _gated_reference(dtype, x, Wg, Wu):
+    """fp64 silu(g) * u before the final rounding, and a bound on what fp32 accumulation may move it by."""
+    g, u = orc.gemm(dtype, x, Wg), orc.gemm(dtype, x, Wu)
+    eg = 4e-6 * (x.double().abs() @ Wg.double().abs().T).numpy()
+    eu = 4e-6 * (x.double().abs() @ Wu.double().abs().T).numpy()
+    sg = g / (1.0 + np.exp(-g))
+    ref = sg * u
+    slack = 1.1 * np.abs(u) * eg + np.abs(sg) * eu          # |d silu / dg| <= 1.1
+    return ref, slack
+
+
+def _gated_check(dtype, got, ref, slack):
+    half_ulp = 2.0 ** -8 if dtype == synth.DT_BF16 else 2.0 ** -11       # relative, of the rounding to the model dtype
+    tiny = 0.0 if dtype == synth.DT_BF16 else 2.0 ** -25                  # fp16 subnormal spacing
+    assert np.all(np.abs(got - ref) <= half_ulp * np.abs(ref) * 1.001 + slack * (1 + half_ulp) + tiny + 1e-30)
+
+
+@pytest.mark.parametrize("dtype", [synth.DT_BF16, synth.DT_F16])
+@pytest.mark.parametrize("M,F,K", [(1, 32, 512), (7, 96, 512), (16, 352, 1024), (17, 64, 1024), (32, 160, 512),
+                                   (33, 96, 2048), (64, 224, 512), (65, 128, 1024), (128, 96, 512), (129, 64, 512),
+                                   (300, 160, 1024)])
+def test_gated_mlp_matches_oracle(dtype, M, F, K):
+    print("gated", dtype, M, F, K, flush=True)
+    g = torch.Generator().manual_seed(300 + M + F)
+    x = torch.randn((M, K), generator=g).to(TDT[dtype])
+    Wg = (torch.randn((F, K), generator=g) * 0.05).to(TDT[dtype])
+    Wu = (torch.randn((F, K), generator=g) * 0.05).to(TDT[dtype])
+    ref, slack = _gated_reference(dtype, x, Wg, Wu)
+    gw = fl.binding.GatedWeight(Wg.cuda(), Wu.cuda())
+    got = fl.k_gated_mlp(x.cuda(), gw).cpu().double().numpy()
+    _gated_check(dtype, got, ref, slack)
+
+
+@pytest.mark.parametrize("dtype", [synth.DT_BF16, synth.DT_F16])
+def test_gated_mlp_row_result_does_not_depend_on_other_rows(dtype):
+    g = torch.Generator().manual_seed(6)
+    K, F = 1024, 416
+    x = torch.randn((300, K), generator=g).to(TDT[dtype]).cuda()
+    gw = fl.binding.GatedWeight((torch.randn((F, K), generator=g) * 0.05).to(TDT[dtype]).cuda(),
+                                (torch.randn((F, K), generator=g) * 0.05).to(TDT[dtype]).cuda())
+    full = fl.k_gated_mlp(x, gw)
+    for M in (1, 16, 17, 32, 33, 64, 65, 128, 129, 200, 257):
+        part = fl.k_gated_mlp(x[:M].contiguous(), gw)
+        assert torch.equal(part, full[:M]), M
+    alone = fl.k_gated_mlp(x[77:78].contiguous(), gw)
+    assert torch.equal(alone[0], full[77])
+
+
+@pytest.mark.parametrize("M", [8, 24, 48, 128])
+def test_gated_mlp_full_size_sampled_columns(M):
+    """The 7B gate|up shape at row counts that select each variant; sampled MLP columns from the oracle."""
+    dtype, F, K = synth.DT_BF16, 11008, 4096
+    print("gated full", M, flush=True)
+    g = torch.Generator(device="cuda").manual_seed(F + M)
+    x = torch.randn((M, K), generator=g, device="cuda").to(TDT[dtype])
+    Wg = (torch.randn((F, K), generator=g, device="cuda") * 0.02).to(TDT[dtype])
+    Wu = (torch.randn((F, K), generator=g, device="cuda") * 0.02).to(TDT[dtype])
+    got = fl.k_gated_mlp(x, fl.binding.GatedWeight(Wg, Wu))
+    cols = np.concatenate([np.random.default_rng(M).choice(F, size=24, replace=False), [0, 15, 16, F - 1]])
+    ci = torch.as_tensor(cols, device="cuda").long()
+    ref, slack = _gated_reference(dtype, x.cpu(), Wg[ci].cpu().contiguous(), Wu[ci].cpu().contiguous())
+    _gated_check(dtype, got[:, ci].cpu().double().numpy(), ref, slack)
+
+
+def test_gated_mlp_rejects_shapes_it_does_not_serve():
+    lib = fl.load_library()
+    assert lib.flover_k_gated_mlp(2, None, None, 4, 48, 512, None, None, 0, None) == -1       # F not a multiple of 32
+    assert lib.flover_k_gated_mlp(2, None, None, 4, 64, 256, None, None, 0, None) == -1       # K not a multiple of 512
+    assert lib.flover_k_gated_mlp(0, None, None, 4, 64, 512, None, None, 0, None) == -1       # fp32
+
+
 # ---------------------------------------------------------------- ragged decode attention
 
 ATT_TOL = {synth.DT_F32: 2e-5, synth.DT_F16: 1.5e-3, synth.DT_BF16: 1e-2}   # |err| / max|ref row|: rounding of the output
