@@ -21,6 +21,9 @@
 //     of rows, where the fp32 partial sums would outweigh the weights, more for short prompts.
 //   * MFMA v_mfma_f32_16x16x32_{bf16,f16}: A = 16 columns of W, B = 16 rows of x, 32-deep: the accumulator tile is
 //     y^T, so a lane holds 4 consecutive output columns of one row and stores them as one 16-byte write.
+//   * gate|up of a gated MLP, up to 64 fused rows: no partial sums at all -- the two K halves are the two wave sets of
+//     a block and the activation is the kernel's epilogue (gated_lds_kernel), with gate and up columns interleaved in
+//     the layout so that a lane holds both; above 64 rows the same halves go through memory as two slices.
 // fp32 models (tiny configurations only) use a plain FMA kernel on the untiled matrix.
 #include <algorithm>
 #include <type_traits>
@@ -274,7 +277,7 @@ __global__ __launch_bounds__(64 * GPB * (NT / NTW)) void gemm16_lds_kernel(const
 template <int DT, int MT, int KC, int PF>
 __global__ __launch_bounds__(512) void gated_lds_kernel(const uint16_t* __restrict__ x, const u32x4_t* __restrict__ wt,
                                                         void* __restrict__ act, int M, int F, int ngroups, int KB,
-                                                        int nx, int nz, int xmtt) {
+                                                        int xmtt) {
   static_assert(PF % KC == 0 && KC >= 2, "ring shape; the hand-over below reuses the x tiles' LDS");
   constexpr int GPB = 4;                         // column groups per block (128 columns); waves that stage one x tile
   __shared__ u32x4_t lds[2][2][KC * MT * 64];    // [half][buffer]
@@ -282,12 +285,8 @@ __global__ __launch_bounds__(512) void gated_lds_kernel(const uint16_t* __restri
   constexpr int CPR = PF / KC;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int half = wave / GPB, gw = wave % GPB;
-  const int xcd = blockIdx.x & 7, qq = blockIdx.x >> 3;     // row blocks of one column block share an XCD's L2
-  const int zb = qq % nz, bx = (qq / nz) * 8 + xcd;
-  if (bx >= nx) return;                          // padding of the grid (whole block)
-  const int g = bx * GPB + gw;
+  const int g = blockIdx.x * GPB + gw;
   const int gl = min(g, ngroups - 1);            // surplus waves repeat the last group (they still serve the barriers)
-  const int m0 = zb * (16 * MT);
   const int K = KB * 32;
   const int kb0 = half * (KB >> 1), kb1 = kb0 + (KB >> 1);
   const int nchunks = (kb1 - kb0) / KC;
@@ -300,8 +299,7 @@ __global__ __launch_bounds__(512) void gated_lds_kernel(const uint16_t* __restri
 
   const u32x4_t* wp = wt + ((size_t)gl * KB) * 2 * 64 + lane;                    // + (kb*2 + t)*64
   const size_t tstride = xmtt ? 512 : (size_t)16 * K, kstride = xmtt ? (size_t)xmtt * 512 : 32;
-  const uint16_t* xp = xmtt ? x + (size_t)(m0 >> 4) * 512 + lane * 8
-                            : x + (size_t)(m0 + (lane & 15)) * K + (lane >> 4) * 8;     // + i*tstride + kb*kstride
+  const uint16_t* xp = xmtt ? x + lane * 8 : x + (size_t)(lane & 15) * K + (lane >> 4) * 8;   // + i*tstride + kb*kstride
 
   u32x4_t bq[PF][2], areg[FPW];
 #pragma unroll
@@ -374,7 +372,7 @@ __global__ __launch_bounds__(512) void gated_lds_kernel(const uint16_t* __restri
   for (int i = 0; i < MT; ++i) {
     const f32x4_t gate = acc[i][0] + red[((gw * MT + i) * 2 + 0) * 64 + lane];
     const f32x4_t up = acc[i][1] + red[((gw * MT + i) * 2 + 1) * 64 + lane];
-    const int m = m0 + i * 16 + (lane & 15);
+    const int m = i * 16 + (lane & 15);
     if (m < M) stv4<DT>(act, xrow_index(m, j, F, xmtt), act_swiglu(gate, up));
   }
 }
@@ -561,9 +559,6 @@ GemmPlan gemm_plan(int dtype, int N, int K) {
 // when the shape allows it; otherwise the plain plan of a 2F-column matrix with gate and up side by side.
 GemmPlan gemm_plan_gated(int dtype, int F, int K) {
   GemmPlan p = gemm_plan(dtype, 2 * F, K);
-#ifdef FLK_NO_GATED
-  return p;
-#endif
   if (dtype == DT_F32 || F % 32 != 0 || (K / 32) % 16 != 0) return p;
   p.NT = 2;
   p.S = 2;               // the two halves of K: partial sums of gemm(), the two in-kernel chains of the fused kernels
@@ -664,15 +659,13 @@ static void dispatch16(const void* x, const void* wt, float* part, int M, const 
 
 template <int DT>
 static void dispatch_gated(const void* x, const void* wt, void* act, int M, const GemmPlan& p, int xmtt, hipStream_t st) {
-  const int F = p.N / 2, ngroups = F / 16, nx = (ngroups + 3) / 4, nx8 = (nx + 7) / 8 * 8;
+  const int F = p.N / 2, ngroups = F / 16, nx = (ngroups + 3) / 4;
   const uint16_t* xx = (const uint16_t*)x;
   const u32x4_t* ww = (const u32x4_t*)wt;
-  if (M <= 16)
-    gated_lds_kernel<DT, 1, 4, 8><<<dim3(nx8), 512, 0, st>>>(xx, ww, act, M, F, ngroups, p.KB, nx, 1, xmtt);
-  else if (M <= 32)
-    gated_lds_kernel<DT, 2, 2, 8><<<dim3(nx8), 512, 0, st>>>(xx, ww, act, M, F, ngroups, p.KB, nx, 1, xmtt);
-  else
-    gated_lds_kernel<DT, 4, 2, 8><<<dim3(nx8), 512, 0, st>>>(xx, ww, act, M, F, ngroups, p.KB, nx, 1, xmtt);
+  // chunks of 4 k-blocks at one row tile (half the barriers), of 2 above
+  if (M <= 16) gated_lds_kernel<DT, 1, 4, 8><<<dim3(nx), 512, 0, st>>>(xx, ww, act, M, F, ngroups, p.KB, xmtt);
+  else if (M <= 32) gated_lds_kernel<DT, 2, 2, 8><<<dim3(nx), 512, 0, st>>>(xx, ww, act, M, F, ngroups, p.KB, xmtt);
+  else gated_lds_kernel<DT, 4, 2, 8><<<dim3(nx), 512, 0, st>>>(xx, ww, act, M, F, ngroups, p.KB, xmtt);
 }
 
 // Up to kGatedFusedRows rows one launch; above that the x tile of a 128-column block would weigh as much as its
