@@ -309,15 +309,19 @@ int32_t flover_k_gemm(int32_t dtype, const void* x, const void* w_tiled, int32_t
  * flover_k_gated_retile writes both matrices ([device][F][K] each) into w_tiled ([device],
  * flover_k_gemm_tiled_bytes(dtype, 2F, K) bytes) with gate and up columns interleaved in tiles of 16;
  * flover_k_gated_mlp streams that copy.  x [device][Mpad][K] row-major with the rows flover_k_gemm asks for readable;
- * act [device][M][F] row-major, model dtype.  A row's result depends on that row of x alone, not on M: up to 64 rows
- * it is one launch; above that the two halves of K go through `workspace` ([device], flover_k_gated_workspace_bytes
- * bytes, 0 up to 64 rows; NOMEM if smaller) as partial sums and the activation is a second launch, with the same
- * result bit for bit. */
+ * act [device][M][F] row-major, model dtype.
+ * context_pass == 0, the fused iteration: a row's result depends on that row of x alone, not on M.  Up to 64 rows it
+ * is one launch; above that the two halves of K go through `workspace` as partial sums and the activation is a second
+ * launch, with the same result bit for bit.
+ * context_pass != 0, the M rows of one request's pre-processing pass (Section V-B): K is sliced by M as well, as
+ * flover_k_gemm_plan reports for context rows; with one slice and more than 128 rows the activation is the epilogue of
+ * the 256-row-block kernel, otherwise partial sums and a second launch.
+ * workspace [device], flover_k_gated_workspace_bytes bytes (0 up to 64 rows); NOMEM if it is needed and smaller. */
 int32_t flover_k_gated_retile(int32_t dtype, const void* Wgate, const void* Wup, int32_t F, int32_t K, void* w_tiled,
                               void* stream);
 int32_t flover_k_gated_workspace_bytes(int32_t dtype, int32_t M, int32_t F, int32_t K, uint64_t* out);
 int32_t flover_k_gated_mlp(int32_t dtype, const void* x, const void* w_tiled, int32_t M, int32_t F, int32_t K,
-                           void* act, void* workspace, uint64_t workspace_bytes, void* stream);
+                           int32_t context_pass, void* act, void* workspace, uint64_t workspace_bytes, void* stream);
 
 #ifdef __cplusplus
 }

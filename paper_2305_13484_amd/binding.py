@@ -110,8 +110,8 @@ def load_library():
                                 C.c_void_p, C.c_uint64, C.c_void_p]
     L.flover_k_gated_retile.argtypes = [C.c_int32, C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p]
     L.flover_k_gated_workspace_bytes.argtypes = [C.c_int32] * 4 + [C.POINTER(C.c_uint64)]
-    L.flover_k_gated_mlp.argtypes = [C.c_int32, C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_void_p,
-                                     C.c_void_p, C.c_uint64, C.c_void_p]
+    L.flover_k_gated_mlp.argtypes = [C.c_int32, C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_int32,
+                                     C.c_void_p, C.c_void_p, C.c_uint64, C.c_void_p]
     _lib = L
     return L
 
@@ -420,8 +420,10 @@ class GatedWeight:
                                                     self.buf.data_ptr(), _stream_ptr()))
 
 
-def k_gated_mlp(x: torch.Tensor, gw: GatedWeight, out: Optional[torch.Tensor] = None, sync: bool = True):
-    """act[M][F] = silu(x . Wgate^T) * (x . Wup^T) in the model dtype, one launch."""
+def k_gated_mlp(x: torch.Tensor, gw: GatedWeight, out: Optional[torch.Tensor] = None, sync: bool = True,
+                context_pass: bool = False):
+    """act[M][F] = silu(x . Wgate^T) * (x . Wup^T) in the model dtype; rows of a fused iteration, or of one request's
+    context pass."""
     M, K = x.shape
     assert K == gw.K and _DT_OF[x.dtype] == gw.dtype
     rows = (M + 127) // 128 * 128 if M <= 128 else (M + 255) // 256 * 256
@@ -434,8 +436,9 @@ def k_gated_mlp(x: torch.Tensor, gw: GatedWeight, out: Optional[torch.Tensor] = 
     n = C.c_uint64()
     _check(load_library().flover_k_gated_workspace_bytes(gw.dtype, M, gw.F, K, C.byref(n)))
     ws = torch.empty(max(int(n.value), 16), dtype=torch.uint8, device="cuda")
-    _check(load_library().flover_k_gated_mlp(gw.dtype, xp.data_ptr(), gw.buf.data_ptr(), M, gw.F, K, out.data_ptr(),
-                                             ws.data_ptr(), int(n.value), _stream_ptr()))
+    _check(load_library().flover_k_gated_mlp(gw.dtype, xp.data_ptr(), gw.buf.data_ptr(), M, gw.F, K,
+                                             1 if context_pass else 0, out.data_ptr(), ws.data_ptr(), int(n.value),
+                                             _stream_ptr()))
     if sync:
         torch.cuda.current_stream().synchronize()
     return out

@@ -383,11 +383,14 @@ __global__ __launch_bounds__(512) void gated_lds_kernel(const uint16_t* __restri
 // A block is 4 column units x 2 row halves = 8 waves over 256 rows x 256 columns; a unit is 64 columns = one group of
 // the matrix layout or (NTL = 2) two consecutive ones; x tile and W ring as above.
 // The per-(m, n) arithmetic is again the same MFMA sequence over k.
-template <int DT, int MTW, int NT, int NTL, int KC, int PF>
+// GATED (a paired gate|up matrix taken in one slice): instead of partial sums the wave writes silu(gate) * up of its
+// two column groups, rounded to the model dtype, as the next GEMM's row operand (`part` is then that buffer, N = 2F).
+template <int DT, int MTW, int NT, int NTL, int KC, int PF, bool GATED = false>
 __global__ __launch_bounds__(512) void gemm16_rows_kernel(const uint16_t* __restrict__ x, const u32x4_t* __restrict__ wt,
                                                           float* __restrict__ part, int M, int N, int K, int ngroups,
                                                           int KB, int kbs, size_t slice_stride, int ldc, int nx,
                                                           int nslices, int nz, int xmtt) {
+  static_assert(!GATED || NTL == 2, "gate and up tiles alternate in groups of two");
   static_assert(PF % KC == 0 && NT % NTL == 0, "ring and tile shapes");
   constexpr int MTB = 2 * MTW;                   // row tiles per block
   constexpr int NW = 8;
@@ -482,6 +485,17 @@ __global__ __launch_bounds__(512) void gemm16_rows_kernel(const uint16_t* __rest
     if constexpr (CPR >= 2) if (c + 1 < nchunks) chunk(std::integral_constant<int, 1>{}, std::true_type{}, c + 1);
   }
   if (g >= ngroups) return;
+  if constexpr (GATED) {
+    const int F = N >> 1;
+#pragma unroll
+    for (int i = 0; i < MTW; ++i)
+#pragma unroll
+      for (int pr = 0; pr < NT / 2; ++pr) {
+        const int j = (g * (NT / 2) + pr) * 16 + (lane >> 4) * 4, m = m0 + (half * MTW + i) * 16 + (lane & 15);
+        if (m < M && j < F) stv4<DT>(part, xrow_index(m, j, F, xmtt), act_swiglu(acc[i][2 * pr], acc[i][2 * pr + 1]));
+      }
+    return;
+  }
   float* out = part + (size_t)s * slice_stride;
 #pragma unroll
   for (int i = 0; i < MTW; ++i)
@@ -589,7 +603,9 @@ GemmPlan context_plan(const GemmPlan& p, int dtype, int M, int max_slices) {
     const int kbs = (p.KB + S - 1) / S;
     if ((p.KB + kbs - 1) / kbs != S) continue;                       // slice counts that leave an empty last slice
     const double rounds = (double)((units * S + 255) / 256);
-    const double cost = rounds * kbs * 1.0 + (double)S * M * p.N * 8.0 / 5.0e6;   // microseconds
+    // a paired gate|up matrix in one slice writes the activation instead of partial sums (gemm_gated)
+    const double sums = (p.paired && S == 1) ? (double)M * p.N / 5.0e6 : (double)S * M * p.N * 8.0 / 5.0e6;
+    const double cost = rounds * kbs * 1.0 + sums;   // microseconds
     if (S == 1 || cost < best) {
       best = cost;
       bestS = S;
@@ -635,13 +651,13 @@ static void launch_lds(const void* x, const void* wt, float* part, int M, const 
       (const uint16_t*)x, (const u32x4_t*)wt, part, M, p.N, p.K, ngroups, p.KB, p.kbs, ss, p.ldc, nx, p.S, nz, xmtt);
 }
 
-template <int DT, int NTL>
+template <int DT, int NTL, bool GATED = false>
 static void launch_rows(const void* x, const void* wt, float* part, int M, const GemmPlan& p, size_t ss, int xmtt,
                         hipStream_t st) {
   const int ngroups = p.Npad / 64;            // units of 64 columns, whatever the layout's group width
   const int nx = (ngroups + 3) / 4, nz = (M + 255) / 256;
   const int tasks8 = (nx * p.S + 7) / 8 * 8;
-  gemm16_rows_kernel<DT, 8, 4, NTL, 2, 2><<<dim3(tasks8 * nz), 512, 0, st>>>(
+  gemm16_rows_kernel<DT, 8, 4, NTL, 2, 2, GATED><<<dim3(tasks8 * nz), 512, 0, st>>>(
       (const uint16_t*)x, (const u32x4_t*)wt, part, M, p.N, p.K, ngroups, p.KB, p.kbs, ss, p.ldc, nx, p.S, nz, xmtt);
 }
 
@@ -668,14 +684,21 @@ static void dispatch_gated(const void* x, const void* wt, void* act, int M, cons
   else gated_lds_kernel<DT, 4, 2, 8><<<dim3(nx), 512, 0, st>>>(xx, ww, act, M, F, ngroups, p.KB, xmtt);
 }
 
-// Up to kGatedFusedRows rows one launch; above that the x tile of a 128-column block would weigh as much as its
-// weights, so the contraction runs as gemm() over 256-column blocks with the two K halves as partial sums and the
-// activation as its own launch -- the same two chains, added in the same order, rounded once: bit-identical results.
+// The iteration's plan (two K halves): up to kGatedFusedRows rows one launch; above that the x tile of a 128-column
+// block would weigh as much as its weights, so the contraction runs as gemm() over 256-column blocks with the two K
+// halves as partial sums and the activation as its own launch -- the same two chains, added in the same order, rounded
+// once: bit-identical results.  A context pass's plan: one slice -> the 256-row-block kernel with the activation as
+// its epilogue; any other slice count -> gemm() and the activation launch.
 hipError_t gemm_gated(int dtype, const void* x, const void* wt, int M, const GemmPlan& p, void* act, float* part,
                       size_t slice_stride, int xmtt, hipStream_t st) {
   if (M <= 0) return hipSuccess;
-  if (!p.paired || dtype == DT_F32 || p.S != 2) return hipErrorInvalidValue;
-  if (M > kGatedFusedRows) {
+  if (!p.paired || dtype == DT_F32) return hipErrorInvalidValue;
+  if (p.S == 1 && M > 128) {
+    if (dtype == DT_BF16) launch_rows<DT_BF16, 2, true>(x, wt, (float*)act, M, p, 0, xmtt, st);
+    else launch_rows<DT_F16, 2, true>(x, wt, (float*)act, M, p, 0, xmtt, st);
+    return hipGetLastError();
+  }
+  if (M > kGatedFusedRows || p.S != 2) {
     hipError_t e = gemm(dtype, x, wt, M, p, part, slice_stride, xmtt, st);
     if (e != hipSuccess) return e;
     return activation(dtype, true, part, p.S, slice_stride, p.ldc, nullptr, act, M, p.N / 2, xmtt, st, true);

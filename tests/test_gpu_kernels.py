@@ -127,16 +127,36 @@ def test_gated_mlp_row_result_does_not_depend_on_other_rows(dtype):
     assert torch.equal(alone[0], full[77])
 
 
-@pytest.mark.parametrize("M", [8, 24, 48, 128])
-def test_gated_mlp_full_size_sampled_columns(M):
-    """The 7B gate|up shape at row counts that select each variant; sampled MLP columns from the oracle."""
+@pytest.mark.parametrize("dtype", [synth.DT_BF16, synth.DT_F16])
+@pytest.mark.parametrize("M,F,K", [(40, 96, 512), (130, 352, 1024), (300, 160, 1024), (600, 224, 512)])
+def test_gated_mlp_of_a_context_pass_matches_oracle(dtype, M, F, K):
+    g = torch.Generator().manual_seed(400 + M + F)
+    x = torch.randn((M, K), generator=g).to(TDT[dtype])
+    Wg = (torch.randn((F, K), generator=g) * 0.05).to(TDT[dtype])
+    Wu = (torch.randn((F, K), generator=g) * 0.05).to(TDT[dtype])
+    ref, slack = _gated_reference(dtype, x, Wg, Wu)
+    gw = fl.binding.GatedWeight(Wg.cuda(), Wu.cuda())
+    got = fl.k_gated_mlp(x.cuda(), gw, context_pass=True).cpu().double().numpy()
+    _gated_check(dtype, got, ref, slack)
+
+
+@pytest.mark.parametrize("M,context", [(8, False), (24, False), (48, False), (128, False), (300, True), (513, True),
+                                       (1024, True)])
+def test_gated_mlp_full_size_sampled_columns(M, context):
+    """The 7B gate|up shape at row counts that select each variant -- one launch up to 64 rows, two K halves through
+    memory above; as a context pass: one slice with the activation as the 256-row-block kernel's epilogue (300, 513 and
+    1024 rows, incl. ragged last blocks) -- sampled MLP columns from the oracle."""
     dtype, F, K = synth.DT_BF16, 11008, 4096
-    print("gated full", M, flush=True)
+    print("gated full", M, context, flush=True)
+    if context:
+        from paper_2305_13484_amd.binding import k_gemm_plan
+        # the plan of the plain 2F-column matrix is a lower bound of how attractive one slice is for the paired one
+        print("slices of a plain matrix of this shape:", k_gemm_plan(dtype, 2 * F, K, M))
     g = torch.Generator(device="cuda").manual_seed(F + M)
     x = torch.randn((M, K), generator=g, device="cuda").to(TDT[dtype])
     Wg = (torch.randn((F, K), generator=g, device="cuda") * 0.02).to(TDT[dtype])
     Wu = (torch.randn((F, K), generator=g, device="cuda") * 0.02).to(TDT[dtype])
-    got = fl.k_gated_mlp(x, fl.binding.GatedWeight(Wg, Wu))
+    got = fl.k_gated_mlp(x, fl.binding.GatedWeight(Wg, Wu), context_pass=context)
     cols = np.concatenate([np.random.default_rng(M).choice(F, size=24, replace=False), [0, 15, 16, F - 1]])
     ci = torch.as_tensor(cols, device="cuda").long()
     ref, slack = _gated_reference(dtype, x.cpu(), Wg[ci].cpu().contiguous(), Wu[ci].cpu().contiguous())
@@ -145,9 +165,9 @@ def test_gated_mlp_full_size_sampled_columns(M):
 
 def test_gated_mlp_rejects_shapes_it_does_not_serve():
     lib = fl.load_library()
-    assert lib.flover_k_gated_mlp(2, None, None, 4, 48, 512, None, None, 0, None) == -1       # F not a multiple of 32
-    assert lib.flover_k_gated_mlp(2, None, None, 4, 64, 256, None, None, 0, None) == -1       # K not a multiple of 512
-    assert lib.flover_k_gated_mlp(0, None, None, 4, 64, 512, None, None, 0, None) == -1       # fp32
+    assert lib.flover_k_gated_mlp(2, None, None, 4, 48, 512, 0, None, None, 0, None) == -1       # F not a multiple of 32
+    assert lib.flover_k_gated_mlp(2, None, None, 4, 64, 256, 0, None, None, 0, None) == -1       # K not a multiple of 512
+    assert lib.flover_k_gated_mlp(0, None, None, 4, 64, 512, 0, None, None, 0, None) == -1       # fp32
 
 
 # ---------------------------------------------------------------- ragged decode attention
