@@ -463,7 +463,8 @@ def main():
                 "traffic": traffic["bytes_per_launch"] if same_window else None,
                 "traffic_ratio": (traffic or {}).get("ratio"), "traffic_window": (traffic or {}).get("window"),
                 "traffic_detail": traffic,
-                "timed_launches": att["launches"], "timing": "HIP events around the launch, one layer in four at profile level 1",
+                "timed_launches": att["launches"], "timing": "HIP events that take the dispatch's own start and end time stamps; one layer in eight at "
+                                                               "profile level 1",
                 "avg_launch_us": round(1e3 * att["ms"] / att["launches"], 2),
                 "avg_bytes_per_launch": att["bytes"] // att["launches"]}
     per = res["per_step"]
@@ -499,9 +500,9 @@ def main():
         gms, gby = sum(p["ms"] for p in gk), sum(p["bytes"] for p in gk)
         gemms["weight_gemms_all"] = {"GB/s": round(gby / (gms * 1e-3) / 1e9, 1), "frac": round(gby / (gms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
                                      "launches": sum(p["launches"] for p in gk),
-                                     "timing": "HIP events around the launch (they read about 3.5 us more than the kernel alone); "
-                                               "at profile level 1 the middle layer's four GEMMs and the output projection, "
-                                               "every second iteration"}
+                                     "timing": "HIP events that take the dispatch's own start and end time stamps; at profile "
+                                               "level 1 the middle layer's four GEMMs and the output projection, every fourth "
+                                               "iteration"}
     line = {
         "metric": "generated tokens/s per fused decode stream", "value": round(res["tokens"] / total, 2),
         "unit": "tokens/s", "n_gpus": 1, "steps": K, "warmup": a.warmup, "ms_per_step": round(1e3 * total / K, 4),

@@ -219,11 +219,13 @@ int32_t flover_last_step_launches(const flover_ctx* ctx, int32_t* n);
 int32_t flover_add_request_cached(flover_ctx* ctx, uint64_t req_id, int32_t context_len, int32_t next_token,
                                   int32_t max_new_tokens, int32_t* out_slot);
 
-/* Kernel timing with HIP events on the context's stream (measurement aid, not in the paper).
- * level 0 = off; 1 = sampled: the attention streaming kernel of one layer in four (layers 0, 4, 8, ...) in every
- * iteration, and in every second iteration the four weight GEMMs of the middle layer (n_layer / 2) and the output
- * projection -- two event records per launch cost about as much as a small kernel, and the layers' launches are alike;
- * 2 = the attention kernel of every layer and every weight GEMM.  The shuffle copy is timed at levels 1 and 2.
+/* Kernel timing with HIP events on the context's stream (measurement aid, not in the paper): the events take the
+ * start and end time stamps of the timed kernel's own dispatch.
+ * level 0 = off; 1 = sampled: the attention streaming kernel of one layer in eight (layers 0, 8, 16, ...) in every
+ * iteration, and in every fourth iteration the four weight GEMMs of the middle layer (n_layer / 2) and the output
+ * projection -- a timed dispatch costs about as much as a small kernel, and the layers' launches are alike;
+ * 2 = the attention kernel of every layer and every weight GEMM.  The shuffle copy is timed at levels 1 and 2 (events
+ * recorded before and after its launch).
  * Iterations submitted with flover_step_submit are timed too (added up when they are collected).  Setting the level
  * clears the totals.  flover_get_profile returns, for one kind, the summed duration (ms), the number of TIMED launches
  * and the summed algorithmic bytes of those launches: for attention the K and V rows [0,len) of every row; for a GEMM

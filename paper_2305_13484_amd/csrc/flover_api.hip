@@ -296,11 +296,9 @@ hipError_t timed_gemm(flover_ctx* c, Lane& ln, int kind, const void* x, const vo
                       size_t ss, int mtt, bool sampled, void* gated_out = nullptr) {
   const int64_t bytes = (int64_t)flk::gemm_tiled_bytes(c->cfg.dtype, p.N, p.K);
   const int pi = (&ln == &c->step_lane && c->prof_now && (sampled || c->profile >= 2)) ? prof_begin(c, kind, bytes) : -1;
-  if (pi >= 0) (void)hipEventRecord(c->ev[2 * pi], ln.st);
-  hipError_t e = gated_out ? flk::gemm_gated(c->cfg.dtype, x, w, n, p, gated_out, ln.part, ss, mtt, ln.st)
-                           : flk::gemm(c->cfg.dtype, x, w, n, p, ln.part, ss, mtt, ln.st);
-  if (pi >= 0) (void)hipEventRecord(c->ev[2 * pi + 1], ln.st);
-  return e;
+  hipEvent_t ev0 = pi >= 0 ? c->ev[2 * pi] : nullptr, ev1 = pi >= 0 ? c->ev[2 * pi + 1] : nullptr;
+  return gated_out ? flk::gemm_gated(c->cfg.dtype, x, w, n, p, gated_out, ln.part, ss, mtt, ln.st, ev0, ev1)
+                   : flk::gemm(c->cfg.dtype, x, w, n, p, ln.part, ss, mtt, ln.st, ev0, ev1);
 }
 
 // One pass of the decoder over n rows on lane `ln`: a single launch per operation covers all of them.
@@ -378,9 +376,9 @@ int run_rows(flover_ctx* c, Lane& ln, const Row* rows, int n, bool want_tokens, 
   aw.out_mtt = mtt;
   const bool prof = &ln == &c->step_lane && (wait || want_tokens);
   if (&ln == &c->step_lane) c->prof_now = prof;
-  // level 1 keeps the event records few: the attention launch of one layer in four, and on every second iteration the
-  // four GEMMs of the middle layer and the output projection (two event records cost about as much as a small kernel)
-  const bool gemm_iter = prof && !context_pass && (c->prof_iter++ & 1) == 0;
+  // level 1 keeps the timed launches few: the attention launch of one layer in eight, and on every fourth iteration the
+  // four GEMMs of the middle layer and the output projection (a timed dispatch costs about as much as a small kernel)
+  const bool gemm_iter = prof && !context_pass && (c->prof_iter++ & 3) == 0;
 
   int launches = 0;
   // K slicing: the iteration's is fixed by the matrix shape; a context pass holds rows of one request only and may
@@ -415,9 +413,9 @@ int run_rows(flover_ctx* c, Lane& ln, const Row* rows, int n, bool want_tokens, 
     if (context_pass) {
       HIPCHK(c, flk::prefill_attention(f.dtype, d, ln.q, kl, vl, aw, n, nh, f.max_seq, ln.att, st));
     } else {
-      // level 1 times the attention launch of one layer in four: two event records per launch cost about as much
-      // as a small kernel, and the layers' launches are alike
-      const int pi = (prof && (c->profile >= 2 || l % 4 == 0)) ? prof_begin(c, FLOVER_PROF_ATTENTION, attn_bytes) : -1;
+      // level 1 times the attention launch of one layer in eight: a timed dispatch costs about as much as a small
+      // kernel, and the layers' launches are alike
+      const int pi = (prof && (c->profile >= 2 || l % 8 == 0)) ? prof_begin(c, FLOVER_PROF_ATTENTION, attn_bytes) : -1;
       HIPCHK(c, flk::decode_attention(f.dtype, d, ln.q, kl, vl, aw, n, nh, f.max_seq, ln.att, st,
                                       pi >= 0 ? c->ev[2 * pi] : nullptr, pi >= 0 ? c->ev[2 * pi + 1] : nullptr));
     }

@@ -3,9 +3,21 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <hip/hip_ext.h>
+
 namespace flk {
 
 enum { DT_F32 = 0, DT_F16 = 1, DT_BF16 = 2 };
+
+// Launch with optional timing: when ev0 / ev1 are given they take the start / end time stamps of this very dispatch
+// (no extra packets on the stream, so a timed launch costs what an untimed one does and the elapsed time between the two
+// is the kernel's own duration); without them a plain launch.
+template <typename... KArgs, typename... Args>
+inline void launch_timed(void (*kernel)(KArgs...), dim3 grid, dim3 block, hipStream_t st, hipEvent_t ev0, hipEvent_t ev1,
+                         Args... args) {
+  if (ev0 || ev1) hipExtLaunchKernelGGL(kernel, grid, block, 0, st, ev0, ev1, 0, static_cast<KArgs>(args)...);
+  else hipLaunchKernelGGL(kernel, grid, block, 0, st, static_cast<KArgs>(args)...);
+}
 
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8_t;
 typedef __attribute__((ext_vector_type(8))) _Float16 f16x8_t;

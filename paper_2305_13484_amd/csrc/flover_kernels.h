@@ -37,15 +37,16 @@ hipError_t zero_fill(void* p, size_t bytes, hipStream_t st);
 // part[s][m][p.ldc] (slice stride in floats) = x[M][K] . W^T over slice s of K.
 // xmtt == 0: x is row-major [gemm_rows_read(M)][K]; xmtt = ceil(M/16) (16-bit dtypes only): x is in fragment order
 // (tiles of 16 rows x 32 k, [k-block][row tile], see xrow_index) and the buffer holds K/32 * gemm_rows_read(M)/16 tiles.
+// ev0 / ev1 (optional, here and below): take the start / end time stamps of the call's first / last dispatch.
 hipError_t gemm(int dtype, const void* x, const void* w_tiled, int M, const GemmPlan& p, float* part,
-                size_t slice_stride, int xmtt, hipStream_t st);
+                size_t slice_stride, int xmtt, hipStream_t st, hipEvent_t ev0 = nullptr, hipEvent_t ev1 = nullptr);
 // act[M][F] = silu(x . Wgate^T) * (x . Wup^T) rounded to the model dtype, for a paired plan (16-bit dtypes); x and act
 // are both row-major (xmtt == 0) or both in fragment order with xmtt row tiles per k-block; reads the rows gemm() reads.
 // part / slice_stride as for gemm(): used above kGatedFusedRows rows, where the contraction and the activation are
 // two launches (same result, bit for bit).
 constexpr int kGatedFusedRows = 64;
 hipError_t gemm_gated(int dtype, const void* x, const void* w_tiled, int M, const GemmPlan& p, void* act, float* part,
-                      size_t slice_stride, int xmtt, hipStream_t st);
+                      size_t slice_stride, int xmtt, hipStream_t st, hipEvent_t ev0 = nullptr, hipEvent_t ev1 = nullptr);
 // rows of x that gemm() may read for M live rows
 inline int gemm_rows_read(int M) {
   return M <= 16 ? 16 : M <= 32 ? 32 : M <= 64 ? 64 : M <= 128 ? 128 : (M + 255) / 256 * 256;
@@ -65,7 +66,7 @@ hipError_t qkv_post(int dtype, const float* part, int S, size_t stride, int ldp,
                     int Smax, hipStream_t st);
 // paired: gate and up columns of `part` interleaved in tiles of 16 (see gemm_plan_gated); gated activation only.
 hipError_t activation(int dtype, bool swiglu, const float* part, int S, size_t stride, int ldp, const void* bias, void* a,
-                      int M, int F, int mtt, hipStream_t st, bool paired = false);
+                      int M, int F, int mtt, hipStream_t st, bool paired = false, hipEvent_t ev1 = nullptr);
 hipError_t logits_argmax(const float* part, int S, size_t stride, int ldp, float* logits, int* tok, int M, int V,
                          hipStream_t st);
 
@@ -86,7 +87,7 @@ struct AttnWork {          // all device pointers
 constexpr int kPrefillQB = 8;     // query rows one wave serves in a pre-processing pass (fp32 models)
 int prefill_rows_per_block(int dtype);   // rows per entry of AttnWork::blocks: 8 for fp32, 32 for the 16-bit (MFMA) kernel
 int attn_chunk();   // positions per wave task; fixed for the process, so chunking depends on a request's own length only
-// ev0 / ev1 (optional) are recorded right before / after the streaming kernel (the merge kernel follows ev1).
+// ev0 / ev1 (optional) take the start / end time stamps of the streaming kernel's dispatch (the merge kernel follows).
 hipError_t decode_attention(int dtype, int d, const void* q, const void* kc, const void* vc, const AttnWork& w, int M,
                             int nh, int Smax, void* out, hipStream_t st, hipEvent_t ev0 = nullptr,
                             hipEvent_t ev1 = nullptr);

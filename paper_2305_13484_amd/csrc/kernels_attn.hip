@@ -509,10 +509,8 @@ template <int DT, int D>
 static void launch_attn(const void* q, const void* kc, const void* vc, const AttnWork& w, int M, int nh, int Smax,
                         void* out, hipStream_t st, hipEvent_t ev0, hipEvent_t ev1) {
   const float scale = 1.0f / sqrtf((float)D);
-  if (ev0) (void)hipEventRecord(ev0, st);
-  attn_partial_kernel<DT, D, 4><<<dim3(w.n_items, nh / 4), 256, 0, st>>>(q, kc, vc, w.items, nh, Smax, w.chunk, w.maxch,
-                                                                       scale, w.pml, w.po);
-  if (ev1) (void)hipEventRecord(ev1, st);
+  launch_timed(attn_partial_kernel<DT, D, 4>, dim3(w.n_items, nh / 4), dim3(256), st, ev0, ev1, q, kc, vc, w.items, nh, Smax,
+               w.chunk, w.maxch, scale, w.pml, w.po);
   attn_merge_kernel<DT, D><<<dim3(M, nh), D, 0, st>>>(w.pml, w.po, w.row_len, w.chunk, w.maxch, nh, out, w.out_mtt);
 }
 

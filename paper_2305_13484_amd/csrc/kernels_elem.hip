@@ -268,13 +268,14 @@ hipError_t qkv_post(int dtype, const float* part, int S, size_t stride, int ldp,
 }
 
 hipError_t activation(int dtype, bool swiglu, const float* part, int S, size_t stride, int ldp, const void* bias, void* a,
-                      int M, int F, int mtt, hipStream_t st, bool paired) {
+                      int M, int F, int mtt, hipStream_t st, bool paired, hipEvent_t ev1) {
   if (M <= 0) return hipSuccess;
   if (paired && !swiglu) return hipErrorInvalidValue;
   const long total = (long)M * (F / 4);
   const unsigned grid = (unsigned)((total + 255) / 256);
   if (swiglu) {
-    FLK_DT_SWITCH(dtype, (act_kernel<DT, 1><<<grid, 256, 0, st>>>(part, S, stride, ldp, bias, a, F, total, mtt, paired ? 1 : 0)));
+    FLK_DT_SWITCH(dtype, (launch_timed(act_kernel<DT, 1>, dim3(grid), dim3(256), st, nullptr, ev1, part, S, stride, ldp, bias, a, F,
+                                       total, mtt, paired ? 1 : 0)));
   } else {
     FLK_DT_SWITCH(dtype, (act_kernel<DT, 0><<<grid, 256, 0, st>>>(part, S, stride, ldp, bias, a, F, total, mtt, 0)));
   }

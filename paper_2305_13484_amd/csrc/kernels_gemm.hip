@@ -266,7 +266,7 @@ __global__ __launch_bounds__(64 * GPB * (NT / NTW)) void gemm16_lds_kernel(const
 // epilogue, so that neither partial sums nor the two projections reach memory and the activation needs no launch.
 // The matrix is laid out in "paired" groups of 32 columns -- group j = [gate columns 16j..16j+15 | up columns
 // 16j..16j+15] -- so a lane's accumulators of a group's two n-tiles are gate and up of the same four MLP columns.
-// K is split in two halves inside the block: 8 waves = 4 column groups x 2 halves, each wave the MFMA chain over its
+// K is split in two halves inside the block: 2 * GPB waves = GPB column groups x 2 halves, each wave the MFMA chain over its
 // half's k-blocks in order, each half with its own x tile in LDS (fragment order, double-buffered chunks of KC
 // k-blocks, W ring PF k-blocks deep); at the end the second half hands its sums to the first through LDS, which adds
 // first half + second half, applies silu(gate) * up and writes the result, rounded to the model dtype, as the next
@@ -274,12 +274,12 @@ __global__ __launch_bounds__(64 * GPB * (NT / NTW)) void gemm16_lds_kernel(const
 // bit, to gemm() with the halves as two K slices followed by the stand-alone activation.
 // Every chunk is full and the last ring turn is the only one whose chunks may lack a successor, so the steady state
 // is free of branches.  Requires KB % 16 == 0.
-template <int DT, int MT, int KC, int PF>
-__global__ __launch_bounds__(512) void gated_lds_kernel(const uint16_t* __restrict__ x, const u32x4_t* __restrict__ wt,
+template <int DT, int MT, int KC, int PF, int GPB = 4>
+__global__ __launch_bounds__(128 * GPB) void gated_lds_kernel(const uint16_t* __restrict__ x, const u32x4_t* __restrict__ wt,
                                                         void* __restrict__ act, int M, int F, int ngroups, int KB,
                                                         int xmtt) {
   static_assert(PF % KC == 0 && KC >= 2, "ring shape; the hand-over below reuses the x tiles' LDS");
-  constexpr int GPB = 4;                         // column groups per block (128 columns); waves that stage one x tile
+  // GPB column groups per block (32 columns each) = waves that stage one half's x tile
   __shared__ u32x4_t lds[2][2][KC * MT * 64];    // [half][buffer]
   constexpr int FPW = (KC * MT + GPB - 1) / GPB;
   constexpr int CPR = PF / KC;
@@ -633,55 +633,60 @@ hipError_t zero_fill(void* p, size_t bytes, hipStream_t st) { return hipMemsetAs
 
 template <int DT, int MT, int NT, int PFW, int PFA>
 static void launch_direct(const void* x, const void* wt, float* part, int M, const GemmPlan& p, size_t ss, int xmtt,
-                          hipStream_t st) {
+                          hipStream_t st, hipEvent_t ev0, hipEvent_t ev1) {
   const int ngroups = p.Npad / (16 * NT);
   dim3 grid((ngroups + 3) / 4, p.S, (M + 16 * MT - 1) / (16 * MT));
-  gemm16_direct_kernel<DT, MT, NT, PFW, PFA><<<grid, 256, 0, st>>>((const uint16_t*)x, (const u32x4_t*)wt, part, M, p.N, p.K,
-                                                             ngroups, p.KB, p.kbs, ss, p.ldc, xmtt);
+  launch_timed(gemm16_direct_kernel<DT, MT, NT, PFW, PFA>, grid, dim3(256), st, ev0, ev1, (const uint16_t*)x,
+               (const u32x4_t*)wt, part, M, p.N, p.K, ngroups, p.KB, p.kbs, ss, p.ldc, xmtt);
 }
 template <int DT, int MT, int NT, int NTW, int PF, int GPB = 4, int KC = 2>
 static void launch_lds(const void* x, const void* wt, float* part, int M, const GemmPlan& p, size_t ss, int xmtt,
-                       hipStream_t st) {
+                       hipStream_t st, hipEvent_t ev0, hipEvent_t ev1) {
                                                 // GPB column groups per block: 256 columns, or 128 for the 32-column groups
                                                 // (8 groups per block measured 3 % slower on the 7B stream)
   const int ngroups = p.Npad / (16 * NT);
   const int nx = (ngroups + GPB - 1) / GPB, nz = (M + 16 * MT - 1) / (16 * MT);
   const int tasks8 = (nx * p.S + 7) / 8 * 8;
-  gemm16_lds_kernel<DT, MT, NT, NTW, KC, PF, GPB><<<dim3(tasks8 * nz), 64 * GPB * (NT / NTW), 0, st>>>(
-      (const uint16_t*)x, (const u32x4_t*)wt, part, M, p.N, p.K, ngroups, p.KB, p.kbs, ss, p.ldc, nx, p.S, nz, xmtt);
+  launch_timed(gemm16_lds_kernel<DT, MT, NT, NTW, KC, PF, GPB>, dim3(tasks8 * nz), dim3(64 * GPB * (NT / NTW)), st, ev0, ev1,
+               (const uint16_t*)x, (const u32x4_t*)wt, part, M, p.N, p.K, ngroups, p.KB, p.kbs, ss, p.ldc, nx, p.S, nz, xmtt);
 }
 
 template <int DT, int NTL, bool GATED = false>
 static void launch_rows(const void* x, const void* wt, float* part, int M, const GemmPlan& p, size_t ss, int xmtt,
-                        hipStream_t st) {
+                        hipStream_t st, hipEvent_t ev0, hipEvent_t ev1) {
   const int ngroups = p.Npad / 64;            // units of 64 columns, whatever the layout's group width
   const int nx = (ngroups + 3) / 4, nz = (M + 255) / 256;
   const int tasks8 = (nx * p.S + 7) / 8 * 8;
-  gemm16_rows_kernel<DT, 8, 4, NTL, 2, 2, GATED><<<dim3(tasks8 * nz), 512, 0, st>>>(
-      (const uint16_t*)x, (const u32x4_t*)wt, part, M, p.N, p.K, ngroups, p.KB, p.kbs, ss, p.ldc, nx, p.S, nz, xmtt);
+  launch_timed(gemm16_rows_kernel<DT, 8, 4, NTL, 2, 2, GATED>, dim3(tasks8 * nz), dim3(512), st, ev0, ev1, (const uint16_t*)x,
+               (const u32x4_t*)wt, part, M, p.N, p.K, ngroups, p.KB, p.kbs, ss, p.ldc, nx, p.S, nz, xmtt);
 }
 
 template <int DT, int NT>
 static void dispatch16(const void* x, const void* wt, float* part, int M, const GemmPlan& p, size_t ss, int xmtt,
-                       hipStream_t st) {
-  if (M <= 16) launch_direct<DT, 1, NT, 8, 8>(x, wt, part, M, p, ss, xmtt, st);
-  else if (M <= 32) launch_lds<DT, 2, NT, NT, 4>(x, wt, part, M, p, ss, xmtt, st);     // 4 waves, one per column group
-  else if (M <= 64) launch_lds<DT, 4, NT, 2, 4>(x, wt, part, M, p, ss, xmtt, st);      // 8 waves, two per column group
+                       hipStream_t st, hipEvent_t ev0, hipEvent_t ev1) {
+  if (M <= 16) launch_direct<DT, 1, NT, 8, 8>(x, wt, part, M, p, ss, xmtt, st, ev0, ev1);
+  else if (M <= 32) launch_lds<DT, 2, NT, NT, 4>(x, wt, part, M, p, ss, xmtt, st, ev0, ev1);     // 4 waves, one per column group
+  else if (M <= 64) launch_lds<DT, 4, NT, 2, 4>(x, wt, part, M, p, ss, xmtt, st, ev0, ev1);      // 8 waves, two per column group
   else if (M <= 128) {
-    if (NT == 2 && p.paired) launch_lds<DT, 8, NT, 2, 4, 8>(x, wt, part, M, p, ss, xmtt, st);   // 8 groups: 256 columns
-    else launch_lds<DT, 8, NT, 2, 4>(x, wt, part, M, p, ss, xmtt, st);
-  } else launch_rows<DT, NT>(x, wt, part, M, p, ss, xmtt, st);             // row blocks of 256
+    if (NT == 2 && p.paired) launch_lds<DT, 8, NT, 2, 4, 8>(x, wt, part, M, p, ss, xmtt, st, ev0, ev1);   // 8 groups: 256 columns
+    else launch_lds<DT, 8, NT, 2, 4>(x, wt, part, M, p, ss, xmtt, st, ev0, ev1);
+  } else launch_rows<DT, NT>(x, wt, part, M, p, ss, xmtt, st, ev0, ev1);             // row blocks of 256
 }
 
 template <int DT>
-static void dispatch_gated(const void* x, const void* wt, void* act, int M, const GemmPlan& p, int xmtt, hipStream_t st) {
+static void dispatch_gated(const void* x, const void* wt, void* act, int M, const GemmPlan& p, int xmtt, hipStream_t st,
+                           hipEvent_t ev0, hipEvent_t ev1) {
   const int F = p.N / 2, ngroups = F / 16, nx = (ngroups + 3) / 4;
   const uint16_t* xx = (const uint16_t*)x;
   const u32x4_t* ww = (const u32x4_t*)wt;
-  // chunks of 4 k-blocks at one row tile (half the barriers), of 2 above
-  if (M <= 16) gated_lds_kernel<DT, 1, 4, 8><<<dim3(nx), 512, 0, st>>>(xx, ww, act, M, F, ngroups, p.KB, xmtt);
-  else if (M <= 32) gated_lds_kernel<DT, 2, 2, 8><<<dim3(nx), 512, 0, st>>>(xx, ww, act, M, F, ngroups, p.KB, xmtt);
-  else gated_lds_kernel<DT, 4, 2, 8><<<dim3(nx), 512, 0, st>>>(xx, ww, act, M, F, ngroups, p.KB, xmtt);
+  // chunks of 4 k-blocks at one row tile (half the barriers), of 2 above.  33-64 rows of a matrix whose 128-column blocks
+  // outnumber the compute units (F > 16384: measured at the 30B shape, 280 blocks, 109 us against 92): 256-column blocks
+  // of 16 waves, half as many; at the 7B shape (172 against 86 blocks) the 128-column blocks are 1.5x faster.
+  if (M <= 16) launch_timed(gated_lds_kernel<DT, 1, 4, 8>, dim3(nx), dim3(512), st, ev0, ev1, xx, ww, act, M, F, ngroups, p.KB, xmtt);
+  else if (M <= 32) launch_timed(gated_lds_kernel<DT, 2, 2, 8>, dim3(nx), dim3(512), st, ev0, ev1, xx, ww, act, M, F, ngroups, p.KB, xmtt);
+  else if (nx > 256)
+    launch_timed(gated_lds_kernel<DT, 4, 4, 4, 8>, dim3((ngroups + 7) / 8), dim3(1024), st, ev0, ev1, xx, ww, act, M, F, ngroups, p.KB, xmtt);
+  else launch_timed(gated_lds_kernel<DT, 4, 2, 8>, dim3(nx), dim3(512), st, ev0, ev1, xx, ww, act, M, F, ngroups, p.KB, xmtt);
 }
 
 // The iteration's plan (two K halves): up to kGatedFusedRows rows one launch; above that the x tile of a 128-column
@@ -690,37 +695,37 @@ static void dispatch_gated(const void* x, const void* wt, void* act, int M, cons
 // once: bit-identical results.  A context pass's plan: one slice -> the 256-row-block kernel with the activation as
 // its epilogue; any other slice count -> gemm() and the activation launch.
 hipError_t gemm_gated(int dtype, const void* x, const void* wt, int M, const GemmPlan& p, void* act, float* part,
-                      size_t slice_stride, int xmtt, hipStream_t st) {
+                      size_t slice_stride, int xmtt, hipStream_t st, hipEvent_t ev0, hipEvent_t ev1) {
   if (M <= 0) return hipSuccess;
   if (!p.paired || dtype == DT_F32) return hipErrorInvalidValue;
   if (p.S == 1 && M > 128) {
-    if (dtype == DT_BF16) launch_rows<DT_BF16, 2, true>(x, wt, (float*)act, M, p, 0, xmtt, st);
-    else launch_rows<DT_F16, 2, true>(x, wt, (float*)act, M, p, 0, xmtt, st);
+    if (dtype == DT_BF16) launch_rows<DT_BF16, 2, true>(x, wt, (float*)act, M, p, 0, xmtt, st, ev0, ev1);
+    else launch_rows<DT_F16, 2, true>(x, wt, (float*)act, M, p, 0, xmtt, st, ev0, ev1);
     return hipGetLastError();
   }
   if (M > kGatedFusedRows || p.S != 2) {
-    hipError_t e = gemm(dtype, x, wt, M, p, part, slice_stride, xmtt, st);
-    if (e != hipSuccess) return e;
-    return activation(dtype, true, part, p.S, slice_stride, p.ldc, nullptr, act, M, p.N / 2, xmtt, st, true);
+    hipError_t e = gemm(dtype, x, wt, M, p, part, slice_stride, xmtt, st, ev0, nullptr);   // timed from the first launch's
+    if (e != hipSuccess) return e;                                                       // start to the second's end
+    return activation(dtype, true, part, p.S, slice_stride, p.ldc, nullptr, act, M, p.N / 2, xmtt, st, true, ev1);
   }
-  if (dtype == DT_BF16) dispatch_gated<DT_BF16>(x, wt, act, M, p, xmtt, st);
-  else dispatch_gated<DT_F16>(x, wt, act, M, p, xmtt, st);
+  if (dtype == DT_BF16) dispatch_gated<DT_BF16>(x, wt, act, M, p, xmtt, st, ev0, ev1);
+  else dispatch_gated<DT_F16>(x, wt, act, M, p, xmtt, st, ev0, ev1);
   return hipGetLastError();
 }
 
 hipError_t gemm(int dtype, const void* x, const void* wt, int M, const GemmPlan& p, float* part, size_t slice_stride,
-                int xmtt, hipStream_t st) {
+                int xmtt, hipStream_t st, hipEvent_t ev0, hipEvent_t ev1) {
   if (M <= 0) return hipSuccess;
   if (dtype == DT_F32) {
     if (xmtt) return hipErrorInvalidValue;   // fp32 rows are always row-major
     dim3 grid((p.N + 3) / 4, (M + 7) / 8);
-    gemm32_kernel<<<grid, 256, 0, st>>>((const float*)x, (const float*)wt, part, M, p.N, p.K, p.ldc);
+    launch_timed(gemm32_kernel, grid, dim3(256), st, ev0, ev1, (const float*)x, (const float*)wt, part, M, p.N, p.K, p.ldc);
   } else if (dtype == DT_BF16) {
-    if (p.NT == 4) dispatch16<DT_BF16, 4>(x, wt, part, M, p, slice_stride, xmtt, st);
-    else dispatch16<DT_BF16, 2>(x, wt, part, M, p, slice_stride, xmtt, st);
+    if (p.NT == 4) dispatch16<DT_BF16, 4>(x, wt, part, M, p, slice_stride, xmtt, st, ev0, ev1);
+    else dispatch16<DT_BF16, 2>(x, wt, part, M, p, slice_stride, xmtt, st, ev0, ev1);
   } else {
-    if (p.NT == 4) dispatch16<DT_F16, 4>(x, wt, part, M, p, slice_stride, xmtt, st);
-    else dispatch16<DT_F16, 2>(x, wt, part, M, p, slice_stride, xmtt, st);
+    if (p.NT == 4) dispatch16<DT_F16, 4>(x, wt, part, M, p, slice_stride, xmtt, st, ev0, ev1);
+    else dispatch16<DT_F16, 2>(x, wt, part, M, p, slice_stride, xmtt, st, ev0, ev1);
   }
   return hipGetLastError();
 }

@@ -163,6 +163,25 @@ def test_gated_mlp_full_size_sampled_columns(M, context):
     _gated_check(dtype, got[:, ci].cpu().double().numpy(), ref, slack)
 
 
+def test_gated_mlp_at_the_30b_shape_sampled_columns_and_row_invariance():
+    """F = 17920, K = 6656: more 128-column blocks than compute units, so 33-64 rows take the 256-column blocks of 16
+    waves; sampled MLP columns from the oracle, and every row count gives the same bits for a row."""
+    dtype, F, K = synth.DT_BF16, 17920, 6656
+    g = torch.Generator(device="cuda").manual_seed(30)
+    x = torch.randn((100, K), generator=g, device="cuda").to(TDT[dtype])
+    Wg = (torch.randn((F, K), generator=g, device="cuda") * 0.02).to(TDT[dtype])
+    Wu = (torch.randn((F, K), generator=g, device="cuda") * 0.02).to(TDT[dtype])
+    gw = fl.binding.GatedWeight(Wg, Wu)
+    full = fl.k_gated_mlp(x, gw)
+    for M in (8, 24, 48, 64):
+        print("gated 30b", M, flush=True)
+        assert torch.equal(fl.k_gated_mlp(x[:M].contiguous(), gw), full[:M]), M
+    cols = np.concatenate([np.random.default_rng(3).choice(F, size=20, replace=False), [0, 16, F - 1]])
+    ci = torch.as_tensor(cols, device="cuda").long()
+    ref, slack = _gated_reference(dtype, x[:48].cpu(), Wg[ci].cpu().contiguous(), Wu[ci].cpu().contiguous())
+    _gated_check(dtype, full[:48, ci].cpu().double().numpy(), ref, slack)
+
+
 def test_gated_mlp_rejects_shapes_it_does_not_serve():
     lib = fl.load_library()
     assert lib.flover_k_gated_mlp(2, None, None, 4, 48, 512, 0, None, None, 0, None) == -1       # F not a multiple of 32

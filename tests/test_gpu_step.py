@@ -871,20 +871,20 @@ def test_cache_rows_match_the_oracle_after_context_pass_append_and_shuffle(make)
 
 
 def test_sampled_kernel_timing_at_level_one():
-    """Profile level 1 (what the benchmark runs with): the attention launch of one layer in four every iteration, and
-    on every second iteration the four GEMMs of the middle layer and the output projection."""
+    """Profile level 1 (what the benchmark runs with): the attention launch of one layer in eight every iteration, and
+    on every fourth iteration the four GEMMs of the middle layer and the output projection."""
     import paper_2305_13484_amd as fl
-    cfg = synth.small_llama16(synth.DT_BF16, L=4)
+    cfg = synth.small_llama16(synth.DT_BF16, L=10)
     w = to_device(synth.make_weights(cfg, 22))
     srv = fl.Flover(cfg, w)
     srv.set_profile(1)
-    srv.add_request(1, [5, 6, 7, 8], 8)
-    for _ in range(6):
+    srv.add_request(1, [5, 6, 7, 8], 12)
+    for _ in range(10):
         srv.step()
     p = srv.get_profile()
-    assert p["attention"]["launches"] == 6 * 1                 # layers 0 of 4
+    assert p["attention"]["launches"] == 10 * 2 and p["attention"]["ms"] > 0      # layers 0 and 8 of 10
     for k in ("gemm_qkv", "gemm_out", "gemm_ff1", "gemm_ff2", "gemm_lm"):
-        assert p[k]["launches"] == 3 and p[k]["ms"] > 0, k      # iterations 0, 2, 4
+        assert p[k]["launches"] == 3 and p[k]["ms"] > 0, k      # iterations 0, 4, 8
     assert p["gemm_ff1"]["bytes"] == 3 * 2 * cfg.F * cfg.H * 2
     srv.close()
 
