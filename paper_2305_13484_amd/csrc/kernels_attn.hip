@@ -8,9 +8,11 @@
 //   * the lane group that holds a row reduces q.k over its LPR lanes with DPP, keeps its own online softmax
 //     state (m, l, o) over the rows it sees (rows r with r % (64/LPR) == group), and the groups are merged
 //     once at the end -- no LDS, no barriers, registers only, occupancy hides latency;
-//   * work is flattened to (row, chunk of CHUNK positions) x head so a launch has thousands of equal-sized
-//     wave tasks however ragged the lengths are; chunking depends on the request's own length only, and a
-//     second tiny kernel merges a row's chunks in chunk order (results never depend on other rows).
+//   * work is flattened to (row, chunk) x head so a launch has thousands of similar wave tasks however ragged the
+//     lengths are: a row of len positions has ceil(len / CHUNK) chunks of equal length (no short remainder task, which
+//     would leave the memory system under-used while the full-length tasks finish); chunking depends on the
+//     request's own length only, and a second tiny kernel merges a row's chunks in chunk order (results never depend
+//     on other rows).
 #include "flover_dev.h"
 #include "flover_kernels.h"
 
@@ -34,7 +36,9 @@ __global__ __launch_bounds__(256) void attn_partial_kernel(const void* __restric
   const int hd = blockIdx.y * 4 + wave;
   const int4 it = items[item];          // one load: the cache addresses below depend on nothing else
   const int row = it.x, ch = it.y, slot = it.z, len = it.w;
-  const int j0 = ch * chunk, j1 = min(len, j0 + chunk);
+  // the row's ceil(len / chunk) chunks are made equally long, so that no wave task of a row is a short remainder
+  const int nch = (len + chunk - 1) / chunk, cr = (len + nch - 1) / nch;
+  const int j0 = ch * cr, j1 = min(len, j0 + cr);
   const int grp = lane / LPR, li = lane % LPR;
 
   float qf[EPL];
