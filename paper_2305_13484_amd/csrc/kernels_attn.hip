@@ -146,25 +146,30 @@ __global__ __launch_bounds__(256) void attn_partial_kernel(const void* __restric
   }
 }
 
-// grid = (M, n_head), block = D: merges a row's chunks in chunk order, normalises, rounds to dtype.
+// grid = (M, ceil(n_head / HPB)), block = 256: merges a row's chunks in chunk order, normalises, rounds to dtype.  A
+// thread owns 4 consecutive elements of one head's output (D / 4 threads per head, HPB = 1024 / D heads per block).
 // out is [M][nh * D] row-major (mtt == 0) or in the GEMM's fragment order with mtt row tiles.
 // The partials of a row sit at a place known from the row index alone, so the loads of the first four chunks go out
 // together with the load of the row's length (one memory round trip for rows of up to 4 chunks; slots of chunks the row
 // does not have are read and never used); longer rows fetch the rest in a second round.
 template <int DT, int D>
-__global__ void attn_merge_kernel(const float* __restrict__ pml, const float* __restrict__ po,
-                                  const int* __restrict__ row_len, int chunk, int maxch, int nh,
-                                  void* __restrict__ out, int mtt) {
+__global__ __launch_bounds__(256) void attn_merge_kernel(const float* __restrict__ pml, const float* __restrict__ po,
+                                                         const int* __restrict__ row_len, int chunk, int maxch, int nh,
+                                                         void* __restrict__ out, int mtt) {
   constexpr int FIRST = 4;
-  const int row = blockIdx.x, hd = blockIdx.y, i = threadIdx.x;
+  constexpr int TPH = D / 4, HPB = 256 / TPH;
+  const int row = blockIdx.x, hd = blockIdx.y * HPB + threadIdx.x / TPH, i = (threadIdx.x % TPH) * 4;
+  if (hd >= nh) return;
   const size_t base = ((size_t)row * maxch) * nh + hd;       // + ch * nh
-  float mc[FIRST], lc[FIRST], oc[FIRST];
+  float mc[FIRST], lc[FIRST];
+  f32x4_t oc[FIRST];
 #pragma unroll
   for (int j = 0; j < FIRST; ++j) {
     const size_t pi = base + (size_t)min(j, maxch - 1) * nh;
-    mc[j] = pml[pi * 2];
-    lc[j] = pml[pi * 2 + 1];
-    oc[j] = po[pi * D + i];
+    const float2 ml = *(const float2*)(pml + pi * 2);
+    mc[j] = ml.x;
+    lc[j] = ml.y;
+    oc[j] = ld4(po + pi * D + i);
   }
   const int nc = (row_len[row] + chunk - 1) / chunk;
   float red_m = -INFINITY;                                    // the global maximum needs the m of every chunk
@@ -172,7 +177,8 @@ __global__ void attn_merge_kernel(const float* __restrict__ pml, const float* __
   for (int j = 0; j < FIRST; ++j)
     if (j < nc) red_m = fmaxf(red_m, mc[j]);
   for (int c = FIRST; c < nc; ++c) red_m = fmaxf(red_m, pml[(base + (size_t)c * nh) * 2]);
-  float l = 0.f, o = 0.f;
+  float l = 0.f;
+  f32x4_t o = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
   for (int j = 0; j < FIRST; ++j)
     if (j < nc) {
@@ -181,13 +187,15 @@ __global__ void attn_merge_kernel(const float* __restrict__ pml, const float* __
       o += w * oc[j];
     }
   for (int c0 = FIRST; c0 < nc; c0 += 4) {      // longer rows: 4 chunks at a time, loads first, arithmetic in chunk order
-    float m2[4], l2[4], o2[4];
+    float m2[4], l2[4];
+    f32x4_t o2[4];
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
       const size_t pi = base + (size_t)min(c0 + j, nc - 1) * nh;
-      m2[j] = pml[pi * 2];
-      l2[j] = pml[pi * 2 + 1];
-      o2[j] = po[pi * D + i];
+      const float2 ml = *(const float2*)(pml + pi * 2);
+      m2[j] = ml.x;
+      l2[j] = ml.y;
+      o2[j] = ld4(po + pi * D + i);
     }
 #pragma unroll
     for (int j = 0; j < 4; ++j)
@@ -197,7 +205,7 @@ __global__ void attn_merge_kernel(const float* __restrict__ pml, const float* __
         o += w * o2[j];
       }
   }
-  st<DT>(out, xrow_index(row, hd * D + i, nh * D, mtt), o / l);
+  stv4<DT>(out, xrow_index(row, hd * D + i, nh * D, mtt), o / l);
 }
 
 // ---------------------------------------------------------------- pre-processing variant (context decoder)
@@ -515,7 +523,7 @@ static void launch_attn(const void* q, const void* kc, const void* vc, const Att
   const float scale = 1.0f / sqrtf((float)D);
   launch_timed(attn_partial_kernel<DT, D, 4>, dim3(w.n_items, nh / 4), dim3(256), st, ev0, ev1, q, kc, vc, w.items, nh, Smax,
                w.chunk, w.maxch, scale, w.pml, w.po);
-  attn_merge_kernel<DT, D><<<dim3(M, nh), D, 0, st>>>(w.pml, w.po, w.row_len, w.chunk, w.maxch, nh, out, w.out_mtt);
+  attn_merge_kernel<DT, D><<<dim3(M, (nh * D + 1023) / 1024), 256, 0, st>>>(w.pml, w.po, w.row_len, w.chunk, w.maxch, nh, out, w.out_mtt);
 }
 
 hipError_t decode_attention(int dtype, int d, const void* q, const void* kc, const void* vc, const AttnWork& w, int M,
@@ -543,7 +551,7 @@ static void launch_prefill(const void* q, const void* kc, const void* vc, const 
   else
     attn_prefill_mfma_kernel<DT, D><<<dim3(w.n_blocks, nh / 4), 256, 0, st>>>(
         q, kc, vc, w.blocks, w.row_slot, w.row_len, nh, Smax, w.chunk, w.maxch, scale, w.pml, w.po);
-  attn_merge_kernel<DT, D><<<dim3(M, nh), D, 0, st>>>(w.pml, w.po, w.row_len, w.chunk, w.maxch, nh, out, w.out_mtt);
+  attn_merge_kernel<DT, D><<<dim3(M, (nh * D + 1023) / 1024), 256, 0, st>>>(w.pml, w.po, w.row_len, w.chunk, w.maxch, nh, out, w.out_mtt);
 }
 
 hipError_t prefill_attention(int dtype, int d, const void* q, const void* kc, const void* vc, const AttnWork& w, int M,
