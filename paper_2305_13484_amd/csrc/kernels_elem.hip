@@ -207,14 +207,20 @@ __global__ __launch_bounds__(1024) void argmax_kernel(const float* __restrict__ 
   const int m = blockIdx.x;
   float best = -INFINITY;
   int arg = 0x7fffffff;
-  for (int j = threadIdx.x * 4; j < V; j += 4096) {
-    const f32x4_t v = psum4(part, S, stride, (size_t)m * ldp + j);
+  for (int j0 = threadIdx.x * 4; j0 < V; j0 += 4 * 4096) {      // four strides at a time: their loads go out together
+    f32x4_t v[4];
 #pragma unroll
-    for (int e = 0; e < 4; ++e)
-      if (j + e < V) {
-        if (logits) logits[(size_t)m * V + j + e] = v[e];
-        if (v[e] > best) { best = v[e]; arg = j + e; }      // ascending j: the first maximum stays
-      }
+    for (int u = 0; u < 4; ++u) v[u] = psum4(part, S, stride, (size_t)m * ldp + min(j0 + u * 4096, ldp - 4));
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const int j = j0 + u * 4096;
+#pragma unroll
+      for (int e = 0; e < 4; ++e)
+        if (j + e < V) {
+          if (logits) logits[(size_t)m * V + j + e] = v[u][e];
+          if (v[u][e] > best) { best = v[u][e]; arg = j + e; }      // ascending j: the first maximum stays
+        }
+    }
   }
 #pragma unroll
   for (int dlt = 1; dlt < 64; dlt <<= 1) {
