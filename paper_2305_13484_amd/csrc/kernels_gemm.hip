@@ -665,12 +665,13 @@ template <int DT, int NT>
 static void dispatch16(const void* x, const void* wt, float* part, int M, const GemmPlan& p, size_t ss, int xmtt,
                        hipStream_t st, hipEvent_t ev0, hipEvent_t ev1) {
   if (M <= 16) launch_direct<DT, 1, NT, 8, 8>(x, wt, part, M, p, ss, xmtt, st, ev0, ev1);
-  else if (M <= 32) launch_lds<DT, 2, NT, NT, 4>(x, wt, part, M, p, ss, xmtt, st, ev0, ev1);     // 4 waves, one per column group
+  else if (M <= 32) launch_lds<DT, 2, NT, NT, 4, 4, (NT == 2 ? 4 : 2)>(x, wt, part, M, p, ss, xmtt, st, ev0, ev1);     // 4 waves, one per column group
   else if (NT == 2 && !p.paired && M <= 128) {
     // 32-column groups above 32 rows: two waves per group, one n-tile each (8 waves per 128-column block); measured
-    // 0.6 us (33-64 rows) and 1.5 us (65-128 rows) faster per launch than one wave per group
-    if (M <= 64) launch_lds<DT, 4, NT, 1, 4>(x, wt, part, M, p, ss, xmtt, st, ev0, ev1);
-    else launch_lds<DT, 8, NT, 1, 4>(x, wt, part, M, p, ss, xmtt, st, ev0, ev1);
+    // 0.6 us (33-64 rows) and 1.5 us (65-128 rows) faster per launch than one wave per group.  For these groups chunks
+    // of 4 k-blocks (half the barriers) are 0.2-1.5 us faster per launch at every row count; for the 64-column ones not.
+    if (M <= 64) launch_lds<DT, 4, NT, 1, 4, 4, 4>(x, wt, part, M, p, ss, xmtt, st, ev0, ev1);
+    else launch_lds<DT, 8, NT, 1, 4, 4, 4>(x, wt, part, M, p, ss, xmtt, st, ev0, ev1);
   }
   else if (M <= 64) launch_lds<DT, 4, NT, 2, 4>(x, wt, part, M, p, ss, xmtt, st, ev0, ev1);      // 8 waves, two per column group
   else if (M <= 128) {
