@@ -686,13 +686,18 @@ static void dispatch_gated(const void* x, const void* wt, void* act, int M, cons
   const int F = p.N / 2, ngroups = F / 16, nx = (ngroups + 3) / 4;
   const uint16_t* xx = (const uint16_t*)x;
   const u32x4_t* ww = (const u32x4_t*)wt;
-  // chunks of 4 k-blocks at one row tile (half the barriers), of 2 above.  33-64 rows of a matrix whose 128-column blocks
-  // outnumber the compute units (F > 16384: measured at the 30B shape, 280 blocks, 109 us against 92): 256-column blocks
-  // of 16 waves, half as many; at the 7B shape (172 against 86 blocks) the 128-column blocks are 1.5x faster.
-  if (M <= 16) launch_timed(gated_lds_kernel<DT, 1, 4, 8>, dim3(nx), dim3(512), st, ev0, ev1, xx, ww, act, M, F, ngroups, p.KB, xmtt);
+  // chunks of 4 k-blocks at one row tile (half the barriers), of 2 above.  A matrix whose 128-column blocks outnumber
+  // the compute units (F > 16384; measured at the 30B shape, 280 blocks: 97 / 101 / 109 us at <= 16 / 17-32 / 33-64 rows
+  // against 92 for the wider blocks at 33-64) takes 256-column blocks of 16 waves, half as many; at the 7B shape (172
+  // against 86 blocks) the 128-column blocks are 1.5x faster.
+  if (nx > 256) {
+    const dim3 g8((ngroups + 7) / 8), b16(1024);
+    if (M <= 16) launch_timed(gated_lds_kernel<DT, 1, 4, 8, 8>, g8, b16, st, ev0, ev1, xx, ww, act, M, F, ngroups, p.KB, xmtt);
+    else if (M <= 32) launch_timed(gated_lds_kernel<DT, 2, 4, 8, 8>, g8, b16, st, ev0, ev1, xx, ww, act, M, F, ngroups, p.KB, xmtt);
+    else launch_timed(gated_lds_kernel<DT, 4, 4, 4, 8>, g8, b16, st, ev0, ev1, xx, ww, act, M, F, ngroups, p.KB, xmtt);
+  }
+  else if (M <= 16) launch_timed(gated_lds_kernel<DT, 1, 4, 8>, dim3(nx), dim3(512), st, ev0, ev1, xx, ww, act, M, F, ngroups, p.KB, xmtt);
   else if (M <= 32) launch_timed(gated_lds_kernel<DT, 2, 2, 8>, dim3(nx), dim3(512), st, ev0, ev1, xx, ww, act, M, F, ngroups, p.KB, xmtt);
-  else if (nx > 256)
-    launch_timed(gated_lds_kernel<DT, 4, 4, 4, 8>, dim3((ngroups + 7) / 8), dim3(1024), st, ev0, ev1, xx, ww, act, M, F, ngroups, p.KB, xmtt);
   else launch_timed(gated_lds_kernel<DT, 4, 2, 8>, dim3(nx), dim3(512), st, ev0, ev1, xx, ww, act, M, F, ngroups, p.KB, xmtt);
 }
 
