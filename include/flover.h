@@ -312,13 +312,14 @@ int32_t flover_k_gemm(int32_t dtype, const void* x, const void* w_tiled, int32_t
  * flover_k_gemm_tiled_bytes(dtype, 2F, K) bytes) with gate and up columns interleaved in tiles of 16;
  * flover_k_gated_mlp streams that copy.  x [device][Mpad][K] row-major with the rows flover_k_gemm asks for readable;
  * act [device][M][F] row-major, model dtype.
- * context_pass == 0, the fused iteration: a row's result depends on that row of x alone, not on M.  Up to 64 rows it
- * is one launch; above that the two halves of K go through `workspace` as partial sums and the activation is a second
- * launch, with the same result bit for bit.
+ * context_pass == 0, the fused iteration: a row's result depends on that row of x alone, not on M.  Up to 128 rows (64
+ * when F > 16384) it is one launch; above that the two halves of K go through `workspace` as partial sums and the
+ * activation is a second launch, with the same result bit for bit.
  * context_pass != 0, the M rows of one request's pre-processing pass (Section V-B): K is sliced by M as well, as
  * flover_k_gemm_plan reports for context rows; with one slice and more than 128 rows the activation is the epilogue of
  * the 256-row-block kernel, otherwise partial sums and a second launch.
- * workspace [device], flover_k_gated_workspace_bytes bytes (0 up to 64 rows); NOMEM if it is needed and smaller. */
+ * workspace [device], flover_k_gated_workspace_bytes bytes (0 where one launch serves the fused iteration); NOMEM if
+ * it is needed and smaller. */
 int32_t flover_k_gated_retile(int32_t dtype, const void* Wgate, const void* Wup, int32_t F, int32_t K, void* w_tiled,
                               void* stream);
 int32_t flover_k_gated_workspace_bytes(int32_t dtype, int32_t M, int32_t F, int32_t K, uint64_t* out);

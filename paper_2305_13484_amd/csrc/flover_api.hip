@@ -424,7 +424,7 @@ int run_rows(flover_ctx* c, Lane& ln, const Row* rows, int n, bool want_tokens, 
     if (p_1.paired) {
       // gated 16-bit model: the activation is the epilogue of the gate|up contraction wherever that is one launch
       HIPCHK(c, timed_gemm(c, ln, FLOVER_PROF_GEMM_FF1, ln.h, w.w1, n, p_1, ss_1, mtt, gs, ln.act));
-      if (!context_pass && n <= flk::kGatedFusedRows) launches -= 1;
+      if (!context_pass && n <= flk::gated_fused_rows(p_1)) launches -= 1;
     } else {
       HIPCHK(c, timed_gemm(c, ln, FLOVER_PROF_GEMM_FF1, ln.h, w.w1, n, p_1, ss_1, mtt, gs));
       HIPCHK(c, flk::activation(f.dtype, !gpt, ln.part, p_1.S, ss_1, p_1.ldc, w.b1, ln.act, n, F, mtt, st, p_1.paired));
@@ -1469,7 +1469,7 @@ extern "C" int32_t flover_k_gated_workspace_bytes(int32_t dtype, int32_t M, int3
     return fail(nullptr, FLOVER_E_INVAL, "bad argument");
   const flk::GemmPlan p = flk::gemm_plan_gated(dtype, F, K);
   if (!p.paired) return fail(nullptr, FLOVER_E_INVAL, "shape not served by the fused gated kernels");
-  *out = M > flk::kGatedFusedRows ? align_up((size_t)16 * M * p.ldc * 4, 256) : 0;   // up to 16 slices in a context pass
+  *out = M > flk::gated_fused_rows(p) ? align_up((size_t)16 * M * p.ldc * 4, 256) : 0;   // up to 16 slices in a context pass
   return FLOVER_OK;
 }
 
@@ -1484,7 +1484,7 @@ extern "C" int32_t flover_k_gated_mlp(int32_t dtype, const void* x, const void* 
   if (!x || !w_tiled || !act) return fail(nullptr, FLOVER_E_INVAL, "null argument");
   if (context_pass) p = flk::context_plan(p, dtype, M, 16);
   const size_t stride = (size_t)M * p.ldc;
-  const bool one_launch = M <= flk::kGatedFusedRows || (p.S == 1 && M > 128);
+  const bool one_launch = (p.S == 2 && M <= flk::gated_fused_rows(p)) || (p.S == 1 && M > 128);
   if (!one_launch && (!workspace || (size_t)p.S * stride * 4 > workspace_bytes))
     return fail(nullptr, FLOVER_E_NOMEM, "gated workspace too small");
   HIPCHK(nullptr, flk::gemm_gated(dtype, x, w_tiled, M, p, act, (float*)workspace, stride, 0, (hipStream_t)stream));

@@ -42,9 +42,11 @@ hipError_t gemm(int dtype, const void* x, const void* w_tiled, int M, const Gemm
                 size_t slice_stride, int xmtt, hipStream_t st, hipEvent_t ev0 = nullptr, hipEvent_t ev1 = nullptr);
 // act[M][F] = silu(x . Wgate^T) * (x . Wup^T) rounded to the model dtype, for a paired plan (16-bit dtypes); x and act
 // are both row-major (xmtt == 0) or both in fragment order with xmtt row tiles per k-block; reads the rows gemm() reads.
-// part / slice_stride as for gemm(): used above kGatedFusedRows rows, where the contraction and the activation are
+// part / slice_stride as for gemm(): used above gated_fused_rows(p) rows, where the contraction and the activation are
 // two launches (same result, bit for bit).
-constexpr int kGatedFusedRows = 64;
+// rows up to which gemm_gated() is one launch for this plan: 128, or 64 for a matrix whose 128-column blocks outnumber the
+// compute units (it takes 16-wave blocks, whose hand-over space in LDS ends at four row tiles)
+inline int gated_fused_rows(const GemmPlan& p) { return (p.N / 2 / 16 + 3) / 4 > 256 ? 64 : 128; }
 hipError_t gemm_gated(int dtype, const void* x, const void* w_tiled, int M, const GemmPlan& p, void* act, float* part,
                       size_t slice_stride, int xmtt, hipStream_t st, hipEvent_t ev0 = nullptr, hipEvent_t ev1 = nullptr);
 // rows of x that gemm() may read for M live rows

@@ -21,9 +21,9 @@
 //     of rows, where the fp32 partial sums would outweigh the weights, more for short prompts.
 //   * MFMA v_mfma_f32_16x16x32_{bf16,f16}: A = 16 columns of W, B = 16 rows of x, 32-deep: the accumulator tile is
 //     y^T, so a lane holds 4 consecutive output columns of one row and stores them as one 16-byte write.
-//   * gate|up of a gated MLP, up to 64 fused rows: no partial sums at all -- the two K halves are the two wave sets of
+//   * gate|up of a gated MLP, up to 128 fused rows: no partial sums at all -- the two K halves are the two wave sets of
 //     a block and the activation is the kernel's epilogue (gated_lds_kernel), with gate and up columns interleaved in
-//     the layout so that a lane holds both; above 64 rows the same halves go through memory as two slices.
+//     the layout so that a lane holds both; above 128 rows the same halves go through memory as two slices.
 // fp32 models (tiny configurations only) use a plain FMA kernel on the untiled matrix.
 #include <algorithm>
 #include <type_traits>
@@ -688,24 +688,26 @@ static void dispatch_gated(const void* x, const void* wt, void* act, int M, cons
   const u32x4_t* ww = (const u32x4_t*)wt;
   // chunks of 4 k-blocks at one row tile (half the barriers), of 2 above.  A matrix whose 128-column blocks outnumber
   // the compute units (F > 16384; measured at the 30B shape, 280 blocks: 97 / 101 / 109 us at <= 16 / 17-32 / 33-64 rows
-  // against 92 for the wider blocks at 33-64) takes 256-column blocks of 16 waves, half as many; at the 7B shape (172
+  // against 86 / 87 / 101 for the wider blocks) takes 256-column blocks of 16 waves, half as many; at the 7B shape (172
   // against 86 blocks) the 128-column blocks are 1.5x faster.
   if (nx > 256) {
     const dim3 g8((ngroups + 7) / 8), b16(1024);
     if (M <= 16) launch_timed(gated_lds_kernel<DT, 1, 4, 8, 8>, g8, b16, st, ev0, ev1, xx, ww, act, M, F, ngroups, p.KB, xmtt);
     else if (M <= 32) launch_timed(gated_lds_kernel<DT, 2, 4, 8, 8>, g8, b16, st, ev0, ev1, xx, ww, act, M, F, ngroups, p.KB, xmtt);
-    else launch_timed(gated_lds_kernel<DT, 4, 4, 4, 8>, g8, b16, st, ev0, ev1, xx, ww, act, M, F, ngroups, p.KB, xmtt);
+    else launch_timed(gated_lds_kernel<DT, 4, 4, 4, 8>, g8, b16, st, ev0, ev1, xx, ww, act, M, F, ngroups, p.KB, xmtt);   // M <= 64
   }
   else if (M <= 16) launch_timed(gated_lds_kernel<DT, 1, 4, 8>, dim3(nx), dim3(512), st, ev0, ev1, xx, ww, act, M, F, ngroups, p.KB, xmtt);
   else if (M <= 32) launch_timed(gated_lds_kernel<DT, 2, 2, 8>, dim3(nx), dim3(512), st, ev0, ev1, xx, ww, act, M, F, ngroups, p.KB, xmtt);
-  else launch_timed(gated_lds_kernel<DT, 4, 2, 8>, dim3(nx), dim3(512), st, ev0, ev1, xx, ww, act, M, F, ngroups, p.KB, xmtt);
+  else if (M <= 64) launch_timed(gated_lds_kernel<DT, 4, 2, 8>, dim3(nx), dim3(512), st, ev0, ev1, xx, ww, act, M, F, ngroups, p.KB, xmtt);
+  else launch_timed(gated_lds_kernel<DT, 8, 2, 4>, dim3(nx), dim3(512), st, ev0, ev1, xx, ww, act, M, F, ngroups, p.KB, xmtt);   // M <= 128
 }
 
-// The iteration's plan (two K halves): up to kGatedFusedRows rows one launch; above that the x tile of a 128-column
-// block would weigh as much as its weights, so the contraction runs as gemm() over 256-column blocks with the two K
+// The iteration's plan (two K halves): up to gated_fused_rows(p) rows one launch; above that gemm() with the two K
 // halves as partial sums and the activation as its own launch -- the same two chains, added in the same order, rounded
-// once: bit-identical results.  A context pass's plan: one slice -> the 256-row-block kernel with the activation as
-// its epilogue; any other slice count -> gemm() and the activation launch.
+// once: bit-identical results.  (At 65-128 rows the x tile of a 128-column block weighs as much as its weights; the one
+// launch still measures 1.3 % faster per step there than the two: no partial sums, no second launch.)  A context
+// pass's plan: one slice -> the 256-row-block kernel with the activation as its epilogue; any other slice count ->
+// gemm() and the activation launch.
 hipError_t gemm_gated(int dtype, const void* x, const void* wt, int M, const GemmPlan& p, void* act, float* part,
                       size_t slice_stride, int xmtt, hipStream_t st, hipEvent_t ev0, hipEvent_t ev1) {
   if (M <= 0) return hipSuccess;
@@ -715,7 +717,7 @@ hipError_t gemm_gated(int dtype, const void* x, const void* wt, int M, const Gem
     else launch_rows<DT_F16, 2, true>(x, wt, (float*)act, M, p, 0, xmtt, st, ev0, ev1);
     return hipGetLastError();
   }
-  if (M > kGatedFusedRows || p.S != 2) {
+  if (M > gated_fused_rows(p) || p.S != 2) {
     hipError_t e = gemm(dtype, x, wt, M, p, part, slice_stride, xmtt, st, ev0, nullptr);   // timed from the first launch's
     if (e != hipSuccess) return e;                                                       // start to the second's end
     return activation(dtype, true, part, p.S, slice_stride, p.ldc, nullptr, act, M, p.N / 2, xmtt, st, true, ev1);

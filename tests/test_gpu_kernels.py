@@ -143,8 +143,8 @@ def test_gated_mlp_of_a_context_pass_matches_oracle(dtype, M, F, K):
 @pytest.mark.parametrize("M,context", [(8, False), (24, False), (48, False), (128, False), (300, True), (513, True),
                                        (1024, True)])
 def test_gated_mlp_full_size_sampled_columns(M, context):
-    """The 7B gate|up shape at row counts that select each variant -- one launch up to 64 rows, two K halves through
-    memory above; as a context pass: one slice with the activation as the 256-row-block kernel's epilogue (300, 513 and
+    """The 7B gate|up shape at row counts that select each variant of the one-launch form (1, 2, 4 and 8 row tiles); as a
+    context pass: one slice with the activation as the 256-row-block kernel's epilogue (300, 513 and
     1024 rows, incl. ragged last blocks) -- sampled MLP columns from the oracle."""
     dtype, F, K = synth.DT_BF16, 11008, 4096
     print("gated full", M, context, flush=True)
@@ -173,7 +173,7 @@ def test_gated_mlp_at_the_30b_shape_sampled_columns_and_row_invariance():
     Wu = (torch.randn((F, K), generator=g, device="cuda") * 0.02).to(TDT[dtype])
     gw = fl.binding.GatedWeight(Wg, Wu)
     full = fl.k_gated_mlp(x, gw)
-    for M in (8, 24, 48, 64):
+    for M in (8, 24, 48, 64, 65, 100):       # 65 and 100 rows: two launches at this shape
         print("gated 30b", M, flush=True)
         assert torch.equal(fl.k_gated_mlp(x[:M].contiguous(), gw), full[:M]), M
     cols = np.concatenate([np.random.default_rng(3).choice(F, size=20, replace=False), [0, 16, F - 1]])
