@@ -1469,7 +1469,9 @@ extern "C" int32_t flover_k_gated_workspace_bytes(int32_t dtype, int32_t M, int3
     return fail(nullptr, FLOVER_E_INVAL, "bad argument");
   const flk::GemmPlan p = flk::gemm_plan_gated(dtype, F, K);
   if (!p.paired) return fail(nullptr, FLOVER_E_INVAL, "shape not served by the fused gated kernels");
-  *out = M > flk::gated_fused_rows(p) ? align_up((size_t)16 * M * p.ldc * 4, 256) : 0;   // up to 16 slices in a context pass
+  // enough for either use of M rows: the iteration's two halves, or the slices a context pass of M rows takes
+  const int slices = std::max(p.S, flk::context_plan(p, dtype, M, 16).S);
+  *out = M > flk::gated_fused_rows(p) ? align_up((size_t)slices * M * p.ldc * 4, 256) : 0;
   return FLOVER_OK;
 }
 

@@ -72,6 +72,21 @@ def test_gemm_slicing_is_a_function_of_the_matrix_shape_only():
     assert k_gemm_plan(0, 1000, 256) == (1, 8)          # fp32 models: one slice
 
 
+def test_gated_mlp_workspace_sizes_host_only():
+    """Where the gated MLP input is one launch it needs no workspace: up to 128 rows, up to 64 where F > 16384; above
+    that the two K halves (or a context pass's slices) go through it."""
+    lib = fl.load_library()
+    n = ctypes.c_uint64()
+    for M in (1, 64, 128):
+        assert lib.flover_k_gated_workspace_bytes(2, M, 11008, 4096, ctypes.byref(n)) == 0 and n.value == 0
+    assert lib.flover_k_gated_workspace_bytes(2, 129, 11008, 4096, ctypes.byref(n)) == 0
+    assert n.value >= 2 * 129 * 22016 * 4 and n.value % 256 == 0
+    assert lib.flover_k_gated_workspace_bytes(2, 64, 17920, 6656, ctypes.byref(n)) == 0 and n.value == 0
+    assert lib.flover_k_gated_workspace_bytes(2, 65, 17920, 6656, ctypes.byref(n)) == 0 and n.value >= 2 * 65 * 35840 * 4
+    assert lib.flover_k_gated_workspace_bytes(2, 8, 48, 512, ctypes.byref(n)) == -1      # F not a multiple of 32
+    assert lib.flover_k_gated_workspace_bytes(0, 8, 64, 512, ctypes.byref(n)) == -1      # fp32
+
+
 def test_bench_refuses_more_than_one_gpu():
     """The benchmark measures one GPU's throughput; asking for more is refused with a message, before anything touches a GPU."""
     import subprocess
