@@ -209,8 +209,20 @@ __global__ __launch_bounds__(1024) void argmax_kernel(const float* __restrict__ 
   int arg = 0x7fffffff;
   for (int j0 = threadIdx.x * 4; j0 < V; j0 += 4 * 4096) {      // four strides at a time: their loads go out together
     f32x4_t v[4];
+    if (S == 2) {          // the output projection's usual slicing: straight-line, all eight loads in flight at once
+      f32x4_t w[4];
 #pragma unroll
-    for (int u = 0; u < 4; ++u) v[u] = psum4(part, S, stride, (size_t)m * ldp + min(j0 + u * 4096, ldp - 4));
+      for (int u = 0; u < 4; ++u) {
+        const float* p = part + (size_t)m * ldp + min(j0 + u * 4096, ldp - 4);
+        v[u] = ld4(p);
+        w[u] = ld4(p + stride);
+      }
+#pragma unroll
+      for (int u = 0; u < 4; ++u) v[u] += w[u];
+    } else {
+#pragma unroll
+      for (int u = 0; u < 4; ++u) v[u] = psum4(part, S, stride, (size_t)m * ldp + min(j0 + u * 4096, ldp - 4));
+    }
 #pragma unroll
     for (int u = 0; u < 4; ++u) {
       const int j = j0 + u * 4096;
