@@ -9,11 +9,33 @@
 
 namespace flk {
 
-// Sum of S split-K slices at 4 consecutive elements, added in slice order (s = 0, 1, 2, ...).  The loads of up to 16
-// slices (no plan has more) are all issued before the first addition, so a thread pays the memory latency once; S is
-// uniform over the grid, so the predicates are scalar branches.
+// Sum of S split-K slices at 4 consecutive elements, added in slice order (s = 0, 1, 2, ...).  Up to 8 slices (every
+// plan of the fused iteration) the code is straight-line for the given count -- one scalar jump on S, which is uniform
+// over the grid, then all loads issued before the first addition, so a thread pays the memory latency once; beyond
+// that (context passes of short prompts) the loads are predicated one by one.
+template <int S>
+__device__ __forceinline__ f32x4_t psum4_fixed(const float* __restrict__ p, size_t stride) {
+  f32x4_t pv[S];
+#pragma unroll
+  for (int j = 0; j < S; ++j) pv[j] = ld4(p + (size_t)j * stride);
+  f32x4_t v = pv[0];
+#pragma unroll
+  for (int j = 1; j < S; ++j) v += pv[j];
+  return v;
+}
 __device__ __forceinline__ f32x4_t psum4(const float* __restrict__ part, int S, size_t stride, size_t idx) {
   const float* p = part + idx;
+  switch (S) {
+    case 1: return psum4_fixed<1>(p, stride);
+    case 2: return psum4_fixed<2>(p, stride);
+    case 3: return psum4_fixed<3>(p, stride);
+    case 4: return psum4_fixed<4>(p, stride);
+    case 5: return psum4_fixed<5>(p, stride);
+    case 6: return psum4_fixed<6>(p, stride);
+    case 7: return psum4_fixed<7>(p, stride);
+    case 8: return psum4_fixed<8>(p, stride);
+    default: break;
+  }
   f32x4_t pv[16];
 #pragma unroll
   for (int j = 0; j < 16; ++j)
