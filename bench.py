@@ -39,6 +39,11 @@ def parse():
     ap.add_argument("--async-preprocess", action="store_true",
                     help="pre-processing on the library's second stream, beside the fused iterations (Section V-B); "
                          "flover_add_request then only enqueues, and tokens_per_s_incl_preprocess is the figure to read")
+    ap.add_argument("--no-overlap-contexts", dest="overlap_contexts", action="store_false",
+                    help="pre-processing inside flover_add_request on the iterations' stream (async_preprocess = 0).  The "
+                         "default is async_preprocess = 2: the library's two pre-processing streams, waited for by the "
+                         "next iteration, so that the context passes of requests that arrive together run side by side; "
+                         "same schedule and results, the iterations are not overlapped")
     ap.add_argument("--pipeline", type=int, default=2, metavar="D",
                     help="pipelined token return: keep up to D (1..3) iterations submitted before collecting the oldest "
                          "(flover_step_submit / flover_step_collect); 0 = the synchronous flover_step, which also gives the "
@@ -393,7 +398,7 @@ def main():
         cfg = None
         for slots in range(64, 7, -4):
             cand = synth.llama_30b(L=a.layers or 60, C=slots)
-            if fl.arena_bytes(cand) + (6 << 30) <= free:
+            if fl.arena_bytes(cand, 1 if a.async_preprocess else (2 if a.overlap_contexts else 0)) + (6 << 30) <= free:
                 cfg = cand
                 break
         assert cfg is not None, "not enough free device memory for the 30B shape"
@@ -411,11 +416,13 @@ def main():
         run_c2(a)
         return
 
+    # pre-processing mode of the library: 1 = beside the iterations, 2 = two overlapped streams joined by the next iteration
+    a.pre_mode = 1 if a.async_preprocess else (2 if a.overlap_contexts else 0)
     t0 = time.perf_counter()
     cpu = None
     if a.workload == "c5":
         glob, layers = synth.make_weights_layerwise(cfg, a.seed, device="cuda")
-        srv = fl.Flover(cfg, glob, shuffle_off=a.shuffle_off, by_length=a.by_length, async_preprocess=a.async_preprocess)
+        srv = fl.Flover(cfg, glob, shuffle_off=a.shuffle_off, by_length=a.by_length, async_preprocess=a.pre_mode)
         for l, wl_ in enumerate(layers):
             srv.set_layer_weights(l, wl_)
         del glob, layers, wl_
@@ -425,7 +432,7 @@ def main():
         weights = synth.make_weights(cfg, a.seed, device="cuda")
         torch.cuda.synchronize()
         t_w = time.perf_counter() - t0
-        srv = fl.Flover(cfg, weights, shuffle_off=a.shuffle_off, by_length=a.by_length, async_preprocess=a.async_preprocess)
+        srv = fl.Flover(cfg, weights, shuffle_off=a.shuffle_off, by_length=a.by_length, async_preprocess=a.pre_mode)
         if not a.no_cpu_baseline:
             cpu = cpu_baseline(cfg, weights, reqs)
         del weights
@@ -510,7 +517,7 @@ def main():
         "data": "synthetic",
         "config": {"workload": wl, "layers": cfg.L, "requests": len(reqs), "whole_stream": res["all_done"],
                    "seed": a.seed, "cached_context": a.cached_context, "shuffle_off": a.shuffle_off, "by_length": a.by_length,
-                   "async_preprocess": a.async_preprocess, "pipeline": piped},
+                   "async_preprocess": a.async_preprocess, "overlap_contexts": a.pre_mode == 2, "pipeline": piped},
         "tokens": res["tokens"], "mean_live": round(res["tokens"] / K, 2),
         "step_hbm_GBs": round(step_gbs, 1), "step_hbm_frac": round(step_gbs / HBM_PEAK_GBS, 4),
         "target": {"step_hbm_frac": STEP_TARGET, "met": bool(step_gbs / HBM_PEAK_GBS >= STEP_TARGET)}, "by_live_rows": buckets,

@@ -49,12 +49,17 @@ typedef struct flover_config {
                               entry weighted by its cached rows + 1 (the listing sums arr[i], so it already allows
                               weights): the window that leaves the fewest cached rows outside, i.e. fewest bytes moved */
   int32_t async_preprocess; /* 0: flover_add_request returns when the context cache is complete (pre-processing runs on
-                               `stream`).  Non-zero: the library creates a second stream (default priority) and a second set
-                               of row buffers for the context decoder, as the paper runs pre-processing beside the inference
-                               stream (Section V-B): flover_add_request returns once the passes are enqueued, the request
-                               joins the first flover_step that finds its cache complete, and flover_add_request may be
-                               called from another thread while flover_step / flover_reorder_evict run.  Tokens and logits
-                               of every request are the same in both modes; only the iteration a request joins differs. */
+                               `stream`).  Non-zero: the library creates two more streams (default priority), each with
+                               its own set of row buffers for the context decoder, as the paper runs pre-processing beside
+                               the inference stream (Section V-B); arriving requests take them in turn, so the context
+                               passes of two requests run side by side; flover_add_request returns once the passes are
+                               enqueued and may be called from another thread while flover_step / flover_reorder_evict run.
+                               1: the request joins the first flover_step that finds its cache complete (the iterations
+                               overlap with pre-processing; which iteration a request joins depends on timing).
+                               2: the next flover_step waits, on its stream, for the caches of the requests it admits, so
+                               every request joins exactly where it would with 0 (same schedule, same results); only the
+                               context passes of requests that arrive together overlap.  Tokens and logits of every
+                               request are the same in all three modes. */
   float norm_eps;
   float rope_theta;
   void* stream;            /* hipStream_t the library enqueues on; NULL = the null stream */
@@ -119,9 +124,9 @@ const char* flover_last_error(const flover_ctx* ctx);
  * 0..prompt_len-2 -- and put the request into the inference queue.  It joins the fused stream at the next
  * flover_step, which feeds prompt[prompt_len-1].  If no adjacent slot is free the request waits in the
  * request queue (FIFO) and is pre-processed by a later flover_step; *out_slot = -1 then.
- * With async_preprocess the context passes are only enqueued (on the library's second stream) and the request joins
- * the first flover_step that finds them complete; a flover_step with nothing else to generate waits for the oldest
- * one.  Threads: every call takes the context's scheduler lock; with async_preprocess flover_step releases it while
+ * With async_preprocess the context passes are only enqueued (on one of the library's pre-processing streams) and the
+ * request joins the first flover_step that finds them complete (mode 1; a flover_step with nothing else to generate
+ * waits for the oldest one) or the next flover_step, which waits for them (mode 2).  Threads: every call takes the context's scheduler lock; with async_preprocess flover_step releases it while
  * the GPU works, so ONE other thread may call flover_add_request beside the thread that drives flover_step /
  * flover_reorder_evict (the paper's pre-processing and inference threads, Section V-A).  Without async_preprocess
  * calls from several threads are serialised.

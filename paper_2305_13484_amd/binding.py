@@ -152,12 +152,12 @@ class Flover:
     weights: dict of device tensors (names of flover_weights), each [out][in] / stacked over layers."""
 
     def __init__(self, cfg, weights: Dict[str, torch.Tensor], shuffle_off: bool = False, by_length: bool = False,
-                 async_preprocess: bool = False):
+                 async_preprocess: int = 0):   # 0 | 1 | 2 as in flover_config (True counts as 1)
         L = load_library()
         self.cfg = cfg
         self._ctx = None
         c = _Config(cfg.arch, cfg.dtype, cfg.L, cfg.H, cfg.nh, cfg.d, cfg.F, cfg.V, cfg.S, cfg.C, cfg.eos_id,
-                    1 if shuffle_off else 2 if by_length else 0, 1 if async_preprocess else 0, cfg.ln_eps, cfg.rope_theta, None, None, 0)
+                    1 if shuffle_off else 2 if by_length else 0, int(async_preprocess), cfg.ln_eps, cfg.rope_theta, None, None, 0)
         need = C.c_uint64(0)
         _check(L.flover_query_arena_bytes(C.byref(c), C.byref(need)))
         self.arena = torch.empty(int(need.value) + 256, dtype=torch.uint8, device="cuda")
@@ -304,10 +304,10 @@ def k_gemm_plan(dtype: int, N: int, K: int, context_rows: int = 0) -> Tuple[int,
     return s.value, kbs.value
 
 
-def arena_bytes(cfg, async_preprocess: bool = False) -> int:
+def arena_bytes(cfg, async_preprocess: int = 0) -> int:
     """flover_query_arena_bytes for a config object (fields as for Flover)."""
     c = _Config(cfg.arch, cfg.dtype, cfg.L, cfg.H, cfg.nh, cfg.d, cfg.F, cfg.V, cfg.S, cfg.C, cfg.eos_id, 0,
-                1 if async_preprocess else 0, cfg.ln_eps, cfg.rope_theta, None, None, 0)
+                int(async_preprocess), cfg.ln_eps, cfg.rope_theta, None, None, 0)
     need = C.c_uint64(0)
     _check(load_library().flover_query_arena_bytes(C.byref(c), C.byref(need)))
     return int(need.value)

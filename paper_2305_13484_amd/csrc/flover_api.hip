@@ -103,8 +103,13 @@ struct flover_ctx {
   size_t kv_bytes, slot_bytes, plane_bytes;
   // per-pass buffers
   int rows_cap, max_items;
-  Lane step_lane, prep_lane_own;
-  Lane* prep_lane = nullptr;   // == &step_lane unless pre-processing is asynchronous
+  Lane step_lane;
+  // asynchronous pre-processing: two lanes (stream + row buffers each), taken in turn by arriving requests, so that the
+  // context passes of two requests run side by side -- a pass's GEMM launches leave a quarter to a third of the compute
+  // units idle (172-192 blocks on 256), which the other request's launches fill
+  static constexpr int kPrepLanes = 2;
+  Lane prep_lanes[kPrepLanes];
+  int prep_next = 0;
   int4* d_moves;
   size_t stage_ints;
   size_t part_floats = 0;      // capacity of a lane's split-K partial-sum buffer
@@ -227,8 +232,8 @@ size_t layout(flover_ctx* c, char* base) {
   for (const flk::GemmPlan* p : {&c->p_qkv, &c->p_o, &c->p_1, &c->p_2, &c->p_lm}) pw = std::max(pw, (size_t)p->S * p->ldc);
   c->stage_ints = (size_t)6 * R + (size_t)8 * c->max_items;   // row arrays, (row, chunk, slot, len) items, context-pass blocks
   c->act_off = align_up(b.off, 256);
-  for (Lane* ln : {&c->step_lane, &c->prep_lane_own}) {
-    if (ln == &c->prep_lane_own && !f.async_preprocess) break;
+  for (Lane* ln : {&c->step_lane, &c->prep_lanes[0], &c->prep_lanes[1]}) {
+    if (ln != &c->step_lane && !f.async_preprocess) break;
     ln->x = (float*)b.take((size_t)R * H * 4);
     ln->h = b.take((size_t)R * H * e);
     ln->q = b.take((size_t)R * H * e);
@@ -465,7 +470,7 @@ int preprocess(flover_ctx* c, int slot, const Waiting& r) {
   s.ev = -1;
   s.dev_row = -1;
   const bool async = c->cfg.async_preprocess != 0;
-  Lane& ln = *c->prep_lane;
+  Lane& ln = async ? c->prep_lanes[c->prep_next++ % flover_ctx::kPrepLanes] : c->step_lane;
   const int P = (int)r.prompt.size();
   if (async && !c->inflight.empty())   // a submitted iteration may still read the slot's previous tenant
     HIPCHK(c, hipStreamWaitEvent(ln.st, c->step_lane.done[c->inflight.back().ring], 0));
@@ -582,7 +587,7 @@ int load_layer(flover_ctx* c, int l, const flover_weights* w, int src_l) {
 
 // Frees what the context owns outside the arena (pinned staging, events, the pre-processing stream).
 void release(flover_ctx* c) {
-  for (Lane* ln : {&c->step_lane, &c->prep_lane_own}) {
+  for (Lane* ln : {&c->step_lane, &c->prep_lanes[0], &c->prep_lanes[1]}) {
     for (int i = 0; i < kStageRing; ++i) {
       if (ln->h_stage[i]) (void)hipHostFree(ln->h_stage[i]);
       if (ln->staged[i]) (void)hipEventDestroy(ln->staged[i]);
@@ -598,13 +603,15 @@ void release(flover_ctx* c) {
   for (hipEvent_t e : c->prep_ev)
     if (e) (void)hipEventDestroy(e);
   for (hipEvent_t e : c->ev) (void)hipEventDestroy(e);
-  if (c->prep_lane_own.st) (void)hipStreamDestroy(c->prep_lane_own.st);
+  for (Lane& pl : c->prep_lanes)
+    if (pl.st) (void)hipStreamDestroy(pl.st);
 }
 
 // True once the slot's context cache is complete; makes the iteration's stream wait for it.
 bool context_ready(flover_ctx* c, Slot& s) {
   if (!s.pending) return true;
-  if (hipEventQuery(c->prep_ev[s.ev]) != hipSuccess) return false;
+  // mode 2 never skips a request: the iteration's stream waits for the cache, however far the passes have got
+  if (c->cfg.async_preprocess != 2 && hipEventQuery(c->prep_ev[s.ev]) != hipSuccess) return false;
   (void)hipStreamWaitEvent(c->st, c->prep_ev[s.ev], 0);
   s.pending = false;
   return true;
@@ -664,7 +671,6 @@ int32_t flover_init(const flover_config* cfg, const flover_weights* w, flover_ct
     }                                                                                 \
   } while (0)
   c->step_lane.st = c->st;
-  c->prep_lane = cfg->async_preprocess ? &c->prep_lane_own : &c->step_lane;
   c->step_lane.ring = kStageRing;
   for (int i = 0; i < kStageRing; ++i) {
     HIPTRY(hipHostMalloc((void**)&c->step_lane.h_stage[i], c->stage_ints * 4, hipHostMallocDefault));
@@ -675,12 +681,13 @@ int32_t flover_init(const flover_config* cfg, const flover_weights* w, flover_ct
   }
   HIPTRY(hipHostMalloc((void**)&c->step_lane.h_tok, (size_t)kStageRing * c->rows_cap * 4, hipHostMallocDefault));
   if (cfg->async_preprocess) {
-    Lane& pl = c->prep_lane_own;
-    HIPTRY(hipStreamCreateWithFlags(&pl.st, hipStreamNonBlocking));   // default priority
-    pl.ring = kStageRing;
-    for (int i = 0; i < kStageRing; ++i) {
-      HIPTRY(hipHostMalloc((void**)&pl.h_stage[i], c->stage_ints * 4, hipHostMallocDefault));
-      HIPTRY(hipEventCreateWithFlags(&pl.staged[i], hipEventDisableTiming));
+    for (Lane& pl : c->prep_lanes) {
+      HIPTRY(hipStreamCreateWithFlags(&pl.st, hipStreamNonBlocking));   // default priority
+      pl.ring = kStageRing;
+      for (int i = 0; i < kStageRing; ++i) {
+        HIPTRY(hipHostMalloc((void**)&pl.h_stage[i], c->stage_ints * 4, hipHostMallocDefault));
+        HIPTRY(hipEventCreateWithFlags(&pl.staged[i], hipEventDisableTiming));
+      }
     }
     HIPTRY(hipEventCreateWithFlags(&c->compact_ev, hipEventDisableTiming));
     c->prep_ev.assign(cfg->max_concurrency, nullptr);
@@ -746,7 +753,8 @@ int32_t flover_set_layer_weights(flover_ctx* c, int32_t layer, const flover_weig
 int32_t flover_destroy(flover_ctx* ctx) {
   if (!ctx) return FLOVER_OK;
   (void)hipStreamSynchronize(ctx->st);
-  if (ctx->prep_lane_own.st) (void)hipStreamSynchronize(ctx->prep_lane_own.st);
+  for (Lane& pl : ctx->prep_lanes)
+    if (pl.st) (void)hipStreamSynchronize(pl.st);
   release(ctx);
   delete ctx;
   return FLOVER_OK;

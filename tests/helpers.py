@@ -15,10 +15,15 @@ def to_device(weights):
 class Lockstep:
     """Feeds the same stream to both sides, compares every step, re-synchronises after a near tie."""
 
-    def __init__(self, cfg, weights, shuffle_off=False, by_length=False):
+    def __init__(self, cfg, weights, shuffle_off=False, by_length=False, overlapped_contexts=False):
+        """overlapped_contexts: the library pre-processes on its own two streams (async_preprocess = 2), so the context
+        passes of requests that arrive together run side by side and the next iteration waits for them on its stream:
+        every request joins at the iteration the oracle admits it in."""
         import paper_2305_13484_amd as fl
         self.cfg = cfg
-        self.gpu = fl.Flover(cfg, to_device(weights), shuffle_off=shuffle_off, by_length=by_length)
+        self.overlapped = overlapped_contexts
+        self.gpu = fl.Flover(cfg, to_device(weights), shuffle_off=shuffle_off, by_length=by_length,
+                             async_preprocess=2 if overlapped_contexts else 0)
         self.cpu = orc.OracleServer(cfg, weights, shuffle_off=shuffle_off, by_length=by_length)
         self.tol = TOL[cfg.dtype]
         self.max_err = 0.0
@@ -180,8 +185,9 @@ class LockstepPipelined(Lockstep):
     compared then with what the oracle's step of the same number produced.  There is no teacher forcing here (the next
     iteration already runs on the device-resident token), so a near tie fails the run: use it where tokens are exact."""
 
-    def __init__(self, cfg, weights, depth=2, shuffle_off=False, by_length=False):
-        super().__init__(cfg, weights, shuffle_off=shuffle_off, by_length=by_length)
+    def __init__(self, cfg, weights, depth=2, shuffle_off=False, by_length=False, overlapped_contexts=False):
+        super().__init__(cfg, weights, shuffle_off=shuffle_off, by_length=by_length,
+                         overlapped_contexts=overlapped_contexts)
         import collections
         self.depth = depth
         self.queue = collections.deque()          # (oracle step result, logits buffer) of submitted iterations

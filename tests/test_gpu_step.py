@@ -805,6 +805,28 @@ def test_pipelined_iterations_in_lockstep_with_the_oracle(make, depth, shuffle_o
     ls.close()
 
 
+@pytest.mark.parametrize("name,pipelined", [("tiny_gpt", False), ("small_llama16", False), ("tiny_gpt", True)])
+def test_overlapped_context_passes_in_lockstep_with_the_oracle(name, pipelined):
+    """Pre-processing on the library's two streams with the next iteration waiting for it on its own stream
+    (async_preprocess = 2): requests that arrive together have their context passes run side by side (several arrive
+    per step here, with prompts long enough for the 256-row blocks, and more than fit, so that some are admitted from
+    the waiting queue inside flover_step), every request joins at the iteration the oracle admits it in, and slot
+    assignment, window, evictions, move lists, tokens and logits are compared at every step as in the synchronous
+    mode."""
+    cfg = dataclasses.replace(getattr(synth, name)(), C=8, S=400)
+    w = synth.make_weights(cfg, 93)
+    reqs = synth.stream_small(94, cfg.V, n=24, arrive_hi=8, p_lo=1, p_hi=330, g_lo=2, g_hi=14)
+    ls = (LockstepPipelined(cfg, w, depth=2, overlapped_contexts=True) if pipelined
+          else Lockstep(cfg, w, overlapped_contexts=True))
+    ls.run(reqs)
+    print("overlapped contexts", cfg.name, "pipelined" if pipelined else "synchronous", "iterations", ls.steps, "rows",
+          ls.compared_rows, "max rel err", ls.max_err, "ties", ls.ties, "moves", ls.moves)
+    assert ls.moves > 0 and ls.max_err <= TOL[cfg.dtype]
+    for r in reqs:
+        assert len(ls.tokens[r.req_id]) == r.gen_len
+    ls.close()
+
+
 @pytest.mark.parametrize("name,pipelined", [("tiny_gpt", False), ("tiny_gpt", True), ("small_llama16", False),
                                             ("small_llama16", True)])
 def test_async_preprocess_matches_the_oracle_per_request(name, pipelined):
