@@ -447,13 +447,37 @@ __global__ __launch_bounds__(512) void gemm16_rows_kernel(const uint16_t* __rest
   store_a(0);
   __syncthreads();
   // Chunks as in the kernel above: branch-free steady state, refills pinned where they are written.
-  auto chunk = [&](auto cc_, auto tail_, int c) {
+  auto chunk = [&](auto cc_, auto tail_, auto full_, int c) {
     constexpr int cc = decltype(cc_)::value;
     constexpr bool tail = decltype(tail_)::value;
+    constexpr bool full = decltype(full_)::value;
     const bool more = !tail || c + 1 < nchunks;
     if (more) load_a(c + 1);
     __builtin_amdgcn_sched_barrier(0);
     const u32x4_t* la = lds[c & 1];
+    if constexpr (full && !tail) {
+      // Every row tile live and every k-block of the chunk inside the slice (all but a ragged last row block and a
+      // slice's last chunk): no branches, and a row tile's fragment is read from LDS two tiles ahead of its MFMAs.
+      const u32x4_t* lw = la + (half * MTW) * 64 + lane;
+      constexpr int T = KC * MTW;
+      auto frag = [&](int q) { return lw[((q / MTW) * MTB + (q % MTW)) * 64]; };
+      u32x4_t af[3];
+      af[0] = frag(0);
+      af[1] = frag(1);
+#pragma unroll
+      for (int q = 0; q < T; ++q) {
+        const int kc = q / MTW, i = q % MTW;
+        if (q + 2 < T) af[(q + 2) % 3] = frag(q + 2);
+#pragma unroll
+        for (int t = 0; t < NT; ++t) acc[i][t] = mfma16<DT>(bq[cc * KC + kc][t], af[q % 3], acc[i][t]);
+        if (i == MTW - 1) {
+          const int kk = min(kb0 + c * KC + kc + PF, kb1 - 1);
+#pragma unroll
+          for (int t = 0; t < NT; ++t) bq[cc * KC + kc][t] = wp[woff(kk, t)];
+          __builtin_amdgcn_sched_barrier(0);
+        }
+      }
+    } else
 #pragma unroll
     for (int kc = 0; kc < KC; ++kc) {
       const int kb = kb0 + c * KC + kc;
@@ -475,15 +499,20 @@ __global__ __launch_bounds__(512) void gemm16_rows_kernel(const uint16_t* __rest
     __syncthreads();
   };
   static_assert(CPR <= 2, "ring turns of one or two chunks");
-  int c = 0;
-  for (; c + CPR < nchunks; c += CPR) {
-    chunk(std::integral_constant<int, 0>{}, std::false_type{}, c);
-    if constexpr (CPR >= 2) chunk(std::integral_constant<int, 1>{}, std::false_type{}, c + 1);
-  }
-  for (; c < nchunks; c += CPR) {
-    chunk(std::integral_constant<int, 0>{}, std::true_type{}, c);
-    if constexpr (CPR >= 2) if (c + 1 < nchunks) chunk(std::integral_constant<int, 1>{}, std::true_type{}, c + 1);
-  }
+  // Two copies of the loop, chosen per wave (the accumulators stay in place in each; both pass the same barriers).
+  auto loops = [&](auto full_) {
+    int c = 0;
+    for (; c + CPR < nchunks; c += CPR) {
+      chunk(std::integral_constant<int, 0>{}, std::false_type{}, full_, c);
+      if constexpr (CPR >= 2) chunk(std::integral_constant<int, 1>{}, std::false_type{}, full_, c + 1);
+    }
+    for (; c < nchunks; c += CPR) {
+      chunk(std::integral_constant<int, 0>{}, std::true_type{}, full_, c);
+      if constexpr (CPR >= 2) if (c + 1 < nchunks) chunk(std::integral_constant<int, 1>{}, std::true_type{}, full_, c + 1);
+    }
+  };
+  if (live_tiles == MTW) loops(std::true_type{});
+  else loops(std::false_type{});
   if (g >= ngroups) return;
   if constexpr (GATED) {
     const int F = N >> 1;
