@@ -618,7 +618,9 @@ size_t gemm_tiled_bytes(int dtype, int N, int K) {
 
 // Context passes: the slice count that minimises a simple cost model of the 256 x 256 blocks on 256 compute units:
 // rounds of blocks x k-blocks per slice (about 1 us per k-block step of a block, measured), plus the fp32 partial sums
-// written by this kernel and re-read by the next one (about 5 TB/s) -- at hundreds of rows those outweigh the weights
+// written by this kernel and re-read by the next one (about 2 TB/s in effect: the stores are a burst at the kernel's
+// end that nothing overlaps; the divisor is the one that minimises the context passes' time on a stream of prompts of
+// 32 to 1024 rows, flat between 1.7 and 2.5) -- at hundreds of rows those outweigh the weights
 // when the iteration's slicing is kept, while a single slice leaves most of the chip idle for the 4096-column matrices.
 GemmPlan context_plan(const GemmPlan& p, int dtype, int M, int max_slices) {
   GemmPlan q = p;
@@ -633,7 +635,7 @@ GemmPlan context_plan(const GemmPlan& p, int dtype, int M, int max_slices) {
     if ((p.KB + kbs - 1) / kbs != S) continue;                       // slice counts that leave an empty last slice
     const double rounds = (double)((units * S + 255) / 256);
     // a paired gate|up matrix in one slice writes the activation instead of partial sums (gemm_gated)
-    const double sums = (p.paired && S == 1) ? (double)M * p.N / 5.0e6 : (double)S * M * p.N * 8.0 / 5.0e6;
+    const double sums = (p.paired && S == 1) ? (double)M * p.N / 2.0e6 : (double)S * M * p.N * 8.0 / 2.0e6;
     const double cost = rounds * kbs * 1.0 + sums;   // microseconds
     if (S == 1 || cost < best) {
       best = cost;
