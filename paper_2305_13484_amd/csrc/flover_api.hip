@@ -479,6 +479,9 @@ int preprocess(flover_ctx* c, int slot, const Waiting& r) {
   // ... and so may a shuffle copy enqueued after that iteration: the slot handed out here is often the one a move has
   // just vacated, and with iterations outstanding flover_reorder_evict does not wait for its copy
   if (async && c->compact_pending) HIPCHK(c, hipStreamWaitEvent(ln.st, c->compact_ev, 0));
+  // ... and so may the context pass of a previous tenant that was marked finished before it ever joined: with two
+  // pre-processing streams it need not be on this one (an event not yet recorded counts as complete)
+  if (async) HIPCHK(c, hipStreamWaitEvent(ln.st, c->prep_ev[slot], 0));
   std::vector<Row> rows;
   for (int p0 = 0; p0 + 1 < P; p0 += c->rows_cap) {
     const int n = std::min(c->rows_cap, P - 1 - p0);

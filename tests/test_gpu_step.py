@@ -778,6 +778,59 @@ def test_context_pass_waits_for_the_shuffle_copy_that_vacated_its_slot():
     _same_results(ref, (toks, logits), reqs)
 
 
+def test_context_pass_waits_for_the_pass_of_a_tenant_that_never_joined():
+    """Two pre-processing streams: a request is marked finished while its context pass is still queued, its slot is
+    freed and handed to the next request, whose pass goes to the other stream.  Both passes are held back behind the
+    same shuffle copy (itself behind tens of milliseconds of work), so they start together; the long stale pass would
+    overwrite the rows the short new pass has just written unless the new one orders itself behind it.  Every
+    surviving request is compared bit for bit with a plain synchronous run that never saw the cancelled one."""
+    import paper_2305_13484_amd as fl
+    cfg = dataclasses.replace(synth.small_llama16(synth.DT_BF16), C=4)
+    w = to_device(synth.make_weights(cfg, 73))
+    rng = np.random.default_rng(74)
+    mk = lambda rid, at, P, G: synth.Request(rid, at, rng.integers(0, cfg.V, size=P).astype(np.int32), G)
+    reqs = [mk(0, 0, 10, 12), mk(1, 0, 10, 2), mk(2, 0, 10, 12), mk(3, 0, 120, 12), mk(5, 2, 30, 5)]
+    stale = mk(4, 2, 150, 4)
+    ref = gpu_run_stream(cfg, w, reqs)
+    srv = fl.Flover(cfg, w, async_preprocess=2)
+    bufs = [torch.empty((cfg.C, cfg.V), dtype=torch.float32, device="cuda") for _ in range(3)]
+    big = torch.randn((6144, 6144), device="cuda")
+    toks, logits = {}, {}
+
+    def collect(buf):
+        out = srv.step_collect()
+        for j in range(out.n_live):
+            rid = int(out.req_id[j])
+            toks.setdefault(rid, []).append(int(out.token[j]))
+            logits.setdefault(rid, []).append(buf[j].clone())
+        return int(out.finished.sum())
+
+    for r in reqs[:4]:
+        srv.add_request(r.req_id, r.prompt, r.gen_len)
+    assert srv.step_submit(bufs[0]) == 4
+    assert srv.reorder_evict().moves == []
+    assert srv.step_submit(bufs[1]) == 4             # request 1 ends with this iteration
+    for _ in range(6):                                # tens of milliseconds of work ahead of the shuffle copy
+        big = (big @ big) * 1e-4
+    assert srv.reorder_evict().moves == [(3, 1)]      # slot 3 is vacated; its copy is still far from running
+    assert srv.add_request(4, stale.prompt, stale.gen_len) == 3           # long pass, queued behind the copy
+    srv.mark_finished(4)
+    rr = srv.reorder_evict()                          # frees slot 3 again
+    assert rr.moves == [] and list(rr.evicted) == [4]
+    assert srv.add_request(5, reqs[4].prompt, reqs[4].gen_len) == 3       # short pass on the other stream
+    done = collect(bufs[0]) + collect(bufs[1])
+    k = 2
+    while done < len(reqs):
+        n = srv.step_submit(bufs[k % 3])
+        srv.reorder_evict()
+        if n:
+            done += collect(bufs[k % 3])
+            k += 1
+    srv.close()
+    assert 4 not in toks
+    _same_results(ref, (toks, logits), reqs)
+
+
 @pytest.mark.parametrize("make,depth,shuffle_off,seed", [
     (lambda: synth.tiny_gpt(C=5, S=96), 2, False, 81),
     (lambda: synth.tiny_gpt(C=5, S=96), 3, False, 82),
