@@ -584,9 +584,12 @@ def test_async_preprocess_gives_the_same_tokens_and_logits_bitwise(name):
     assert st_s["moves"] > 0 and st_a["moves"] > 0
 
 
-def test_add_request_from_a_second_thread_while_steps_run():
+@pytest.mark.parametrize("mode", [1, 2])
+def test_add_request_from_a_second_thread_while_steps_run(mode):
     """The paper's pre-processing thread beside its inference thread (Section V-A): one thread submits requests while
-    another drives the fused iterations; results equal the single-threaded synchronous run bit for bit."""
+    another drives the fused iterations; results equal the single-threaded synchronous run bit for bit.  mode 1: a
+    request joins the first iteration that finds its cache complete; mode 2: two pre-processing streams, the next
+    iteration waits for the caches."""
     import threading
     import time
     import paper_2305_13484_amd as fl
@@ -594,7 +597,7 @@ def test_add_request_from_a_second_thread_while_steps_run():
     w = to_device(synth.make_weights(cfg, 32))
     reqs = synth.stream_small(43, cfg.V, n=14, arrive_hi=10, p_lo=2, p_hi=min(80, cfg.S - 20), g_lo=3, g_hi=14)
     ref = gpu_run_stream(cfg, w, reqs)
-    srv = fl.Flover(cfg, w, async_preprocess=True)
+    srv = fl.Flover(cfg, w, async_preprocess=mode)
     errors = []
 
     def producer():
