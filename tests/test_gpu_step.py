@@ -166,6 +166,26 @@ def test_llama7b_shape_reduced_depth():
     ls.close()
 
 
+def test_llama7b_shape_overlapped_context_passes_of_long_prompts():
+    """The benchmark's default pre-processing mode at the 7B layer shape (2 layers): prompts of hundreds of rows that
+    arrive together go through the 256-row-block GEMMs (with the fused gate|up epilogue where the plan takes one
+    slice), the matrix-core context attention and the chunk merge on the library's two pre-processing streams side by
+    side; a short and a 130-row prompt take the iteration's GEMM variants beside them.  Slots, window, tokens and
+    logits in lockstep with the oracle."""
+    cfg = synth.llama_7b(L=2, C=6, S=700)
+    w = synth.make_weights(cfg, 14)
+    rng = np.random.default_rng(15)
+    mk = lambda rid, at, P, G: synth.Request(rid, at, rng.integers(0, cfg.V, size=P).astype(np.int32), G)
+    reqs = [mk(0, 0, 300, 4), mk(1, 0, 520, 3), mk(2, 1, 40, 5), mk(3, 1, 130, 3), mk(4, 3, 600, 3)]
+    ls = Lockstep(cfg, w, overlapped_contexts=True)
+    ls.run(reqs)
+    print("7b-shape, overlapped context passes: steps", ls.steps, "max rel err", ls.max_err, "ties", ls.ties)
+    assert ls.max_err <= 2e-2
+    for r in reqs:
+        assert len(ls.tokens[r.req_id]) == r.gen_len
+    ls.close()
+
+
 STATED_TOL = 2e-2          # the logits tolerance the target states for 16-bit models
 
 
