@@ -1033,3 +1033,25 @@ def test_a_single_slot_serves_requests_one_after_the_other():
     for r in reqs:
         assert len(ls.tokens[r.req_id]) == r.gen_len
     ls.close()
+
+
+def test_benchmark_stream_at_full_size_gives_the_same_tokens_in_every_mode():
+    """The benchmark's own workload and arena (LLaMA-7B shape, 32 layers, 128 slots of 2048 positions, the whole
+    128-request stream) in the three ways the library can run it: synchronous steps with pre-processing inside
+    flover_add_request; the benchmark's default (pipelined token return, depth 2, context passes overlapped on two
+    pre-processing streams); and pipelined with asynchronous pre-processing, where requests join whichever iteration
+    finds their cache complete, i.e. in other batch compositions.  Every request's tokens are the same in all three:
+    the fused step is batch-invariant and none of the modes' orderings lets a kernel read a row too early."""
+    cfg = synth.llama_7b()
+    w = synth.make_weights(cfg, 4, device="cuda")
+    reqs = synth.stream_c4(4, cfg.V)
+    ref, _ = gpu_run_stream(cfg, w, reqs, want_logits=False)
+    print("synchronous run done", flush=True)
+    for depth, mode in ((2, 2), (2, 1)):
+        st = {}
+        got, _ = gpu_run_stream_pipelined(cfg, w, reqs, depth=depth, async_preprocess=mode, want_logits=False, stats=st)
+        print("pipelined depth", depth, "async_preprocess", mode, "moves", st["moves"], flush=True)
+        assert st["moves"] > 0
+        for r in reqs:
+            assert len(ref[r.req_id]) == r.gen_len
+            assert got[r.req_id] == ref[r.req_id], (mode, r.req_id)
