@@ -701,14 +701,29 @@ static void dispatch16(const void* x, const void* wt, float* part, int M, const 
     // 32-column groups above 32 rows: two waves per group, one n-tile each (8 waves per 128-column block); measured
     // 0.6 us (33-64 rows) and 1.5 us (65-128 rows) faster per launch than one wave per group.  For these groups chunks
     // of 4 k-blocks (half the barriers) are 0.2-1.5 us faster per launch at every row count; for the 64-column ones not.
-    if (M <= 64) launch_lds<DT, 4, NT, 1, 4, 4, 4>(x, wt, part, M, p, ss, xmtt, st, ev0, ev1);
-    else launch_lds<DT, 8, NT, 1, 4, 4, 4>(x, wt, part, M, p, ss, xmtt, st, ev0, ev1);
+    // one variant per count of 16-row tiles: a block stages and multiplies exactly the live tiles
+    switch ((M + 15) / 16) {
+      case 3: launch_lds<DT, 3, NT, 1, 4, 4, 4>(x, wt, part, M, p, ss, xmtt, st, ev0, ev1); break;
+      case 4: launch_lds<DT, 4, NT, 1, 4, 4, 4>(x, wt, part, M, p, ss, xmtt, st, ev0, ev1); break;
+      case 5: launch_lds<DT, 5, NT, 1, 4, 4, 4>(x, wt, part, M, p, ss, xmtt, st, ev0, ev1); break;
+      case 6: launch_lds<DT, 6, NT, 1, 4, 4, 4>(x, wt, part, M, p, ss, xmtt, st, ev0, ev1); break;
+      case 7: launch_lds<DT, 7, NT, 1, 4, 4, 4>(x, wt, part, M, p, ss, xmtt, st, ev0, ev1); break;
+      default: launch_lds<DT, 8, NT, 1, 4, 4, 4>(x, wt, part, M, p, ss, xmtt, st, ev0, ev1);
+    }
   }
-  else if (M <= 64) launch_lds<DT, 4, NT, 2, 4>(x, wt, part, M, p, ss, xmtt, st, ev0, ev1);      // 8 waves, two per column group
-  else if (M <= 128) {
-    if (NT == 2 && p.paired) launch_lds<DT, 8, NT, 2, 4, 8>(x, wt, part, M, p, ss, xmtt, st, ev0, ev1);   // 8 groups: 256 columns
-    else launch_lds<DT, 8, NT, 2, 4>(x, wt, part, M, p, ss, xmtt, st, ev0, ev1);
-  } else launch_rows<DT, NT>(x, wt, part, M, p, ss, xmtt, st, ev0, ev1);             // row blocks of 256
+  else if (M <= 128 && !(NT == 2 && p.paired)) {
+    switch ((M + 15) / 16) {                                                                  // 8 waves, two per column group
+      case 3: launch_lds<DT, 3, NT, 2, 4>(x, wt, part, M, p, ss, xmtt, st, ev0, ev1); break;
+      case 4: launch_lds<DT, 4, NT, 2, 4>(x, wt, part, M, p, ss, xmtt, st, ev0, ev1); break;
+      case 5: launch_lds<DT, 5, NT, 2, 4>(x, wt, part, M, p, ss, xmtt, st, ev0, ev1); break;
+      case 6: launch_lds<DT, 6, NT, 2, 4>(x, wt, part, M, p, ss, xmtt, st, ev0, ev1); break;
+      case 7: launch_lds<DT, 7, NT, 2, 4>(x, wt, part, M, p, ss, xmtt, st, ev0, ev1); break;
+      default: launch_lds<DT, 8, NT, 2, 4>(x, wt, part, M, p, ss, xmtt, st, ev0, ev1);
+    }
+  }
+  else if (M <= 64) launch_lds<DT, 4, NT, 2, 4>(x, wt, part, M, p, ss, xmtt, st, ev0, ev1);
+  else if (M <= 128) launch_lds<DT, 8, NT, 2, 4, 8>(x, wt, part, M, p, ss, xmtt, st, ev0, ev1);   // paired: 8 groups, 256 columns
+  else launch_rows<DT, NT>(x, wt, part, M, p, ss, xmtt, st, ev0, ev1);             // row blocks of 256
 }
 
 template <int DT>
@@ -729,8 +744,14 @@ static void dispatch_gated(const void* x, const void* wt, void* act, int M, cons
   }
   else if (M <= 16) launch_timed(gated_lds_kernel<DT, 1, 4, 8>, dim3(nx), dim3(512), st, ev0, ev1, xx, ww, act, M, F, ngroups, p.KB, xmtt);
   else if (M <= 32) launch_timed(gated_lds_kernel<DT, 2, 2, 8>, dim3(nx), dim3(512), st, ev0, ev1, xx, ww, act, M, F, ngroups, p.KB, xmtt);
-  else if (M <= 64) launch_timed(gated_lds_kernel<DT, 4, 2, 8>, dim3(nx), dim3(512), st, ev0, ev1, xx, ww, act, M, F, ngroups, p.KB, xmtt);
-  else launch_timed(gated_lds_kernel<DT, 8, 2, 4>, dim3(nx), dim3(512), st, ev0, ev1, xx, ww, act, M, F, ngroups, p.KB, xmtt);   // M <= 128
+  else switch ((M + 15) / 16) {     // M <= 128: one variant per count of 16-row tiles
+    case 3: launch_timed(gated_lds_kernel<DT, 3, 2, 8>, dim3(nx), dim3(512), st, ev0, ev1, xx, ww, act, M, F, ngroups, p.KB, xmtt); break;
+    case 4: launch_timed(gated_lds_kernel<DT, 4, 2, 8>, dim3(nx), dim3(512), st, ev0, ev1, xx, ww, act, M, F, ngroups, p.KB, xmtt); break;
+    case 5: launch_timed(gated_lds_kernel<DT, 5, 2, 4>, dim3(nx), dim3(512), st, ev0, ev1, xx, ww, act, M, F, ngroups, p.KB, xmtt); break;
+    case 6: launch_timed(gated_lds_kernel<DT, 6, 2, 4>, dim3(nx), dim3(512), st, ev0, ev1, xx, ww, act, M, F, ngroups, p.KB, xmtt); break;
+    case 7: launch_timed(gated_lds_kernel<DT, 7, 2, 4>, dim3(nx), dim3(512), st, ev0, ev1, xx, ww, act, M, F, ngroups, p.KB, xmtt); break;
+    default: launch_timed(gated_lds_kernel<DT, 8, 2, 4>, dim3(nx), dim3(512), st, ev0, ev1, xx, ww, act, M, F, ngroups, p.KB, xmtt);
+  }
 }
 
 // The iteration's plan (two K halves): up to gated_fused_rows(p) rows one launch; above that gemm() with the two K
