@@ -26,7 +26,7 @@ def kernels(db_path: str) -> str:
     out = ["kernel time total %.2f ms over a span of %.2f ms (GPU busy %.1f%%)"
            % (tot / 1e6, (span[1] - span[0]) / 1e6, 100.0 * tot / (span[1] - span[0])),
            "%-72s %8s %10s %6s %9s %9s %9s" % ("kernel", "calls", "total ms", "%", "avg us", "min us", "max us")]
-    for n, c, s, a, mn, mx in rows[:24]:
+    for n, c, s, a, mn, mx in rows[:40]:
         out.append("%-72s %8d %10.2f %6.1f %9.2f %9.2f %9.2f" % (short(n), c, s / 1e6, 100.0 * s / tot, a / 1e3,
                                                               mn / 1e3, mx / 1e3))
     return "\n".join(out)
