@@ -28,7 +28,7 @@ TDT = synth.TORCH_DTYPE
 @pytest.mark.parametrize("dtype", [synth.DT_BF16, synth.DT_F16, synth.DT_F32])
 @pytest.mark.parametrize("M,N,K", [(1, 64, 64), (5, 100, 96), (16, 256, 512), (17, 1000, 256), (33, 130, 1024),
                                    (70, 320, 2048), (128, 192, 4096), (200, 64, 160), (300, 320, 1024),
-                                   (513, 130, 512)])
+                                   (513, 130, 512), (48, 200, 512), (90, 130, 1024), (100, 320, 512)])
 def test_gemm_matches_oracle(dtype, M, N, K):
     print("gemm", dtype, M, N, K, flush=True)
     g = torch.Generator().manual_seed(100 + M + N)
@@ -48,14 +48,14 @@ def test_gemm_row_result_does_not_depend_on_other_rows(dtype):
     W = (torch.randn((N, K), generator=g) * 0.05).to(TDT[dtype]).cuda()
     tw = fl.binding.TiledWeight(W)
     full = fl.k_gemm(x, tw)
-    for M in (1, 16, 17, 32, 64, 65, 128, 129, 256, 257, 400, 513):
+    for M in (1, 16, 17, 32, 48, 64, 65, 81, 96, 100, 112, 128, 129, 256, 257, 400, 513):   # every count of 16-row tiles up to 8
         part = fl.k_gemm(x[:M].contiguous(), tw)
         assert torch.equal(part, full[:M]), M
     alone = fl.k_gemm(x[77:78].contiguous(), tw)
     assert torch.equal(alone[0], full[77])
 
 
-@pytest.mark.parametrize("M", [8, 24, 48, 128, 600])
+@pytest.mark.parametrize("M", [8, 24, 48, 72, 96, 112, 128, 600])
 def test_gemm_full_size_sampled_columns(M):
     """The 7B shapes the benchmark runs, at row counts that select each kernel variant (<=16 direct, <=32 / <=64 / <=128
     LDS-staged with 4 or 8 waves, above that the 256-row blocks of a context pass with a ragged last block); sampled
@@ -99,7 +99,7 @@ def _gated_check(dtype, got, ref, slack):
 @pytest.mark.parametrize("dtype", [synth.DT_BF16, synth.DT_F16])
 @pytest.mark.parametrize("M,F,K", [(1, 32, 512), (7, 96, 512), (16, 352, 1024), (17, 64, 1024), (32, 160, 512),
                                    (33, 96, 2048), (64, 224, 512), (65, 128, 1024), (128, 96, 512), (129, 64, 512),
-                                   (300, 160, 1024)])
+                                   (300, 160, 1024), (48, 96, 512), (90, 160, 1024), (110, 64, 512)])
 def test_gated_mlp_matches_oracle(dtype, M, F, K):
     print("gated", dtype, M, F, K, flush=True)
     g = torch.Generator().manual_seed(300 + M + F)
@@ -120,7 +120,7 @@ def test_gated_mlp_row_result_does_not_depend_on_other_rows(dtype):
     gw = fl.binding.GatedWeight((torch.randn((F, K), generator=g) * 0.05).to(TDT[dtype]).cuda(),
                                 (torch.randn((F, K), generator=g) * 0.05).to(TDT[dtype]).cuda())
     full = fl.k_gated_mlp(x, gw)
-    for M in (1, 16, 17, 32, 33, 64, 65, 128, 129, 200, 257):
+    for M in (1, 16, 17, 32, 33, 48, 64, 65, 81, 96, 100, 112, 128, 129, 200, 257):   # every count of 16-row tiles up to 8
         part = fl.k_gated_mlp(x[:M].contiguous(), gw)
         assert torch.equal(part, full[:M]), M
     alone = fl.k_gated_mlp(x[77:78].contiguous(), gw)
@@ -140,10 +140,10 @@ def test_gated_mlp_of_a_context_pass_matches_oracle(dtype, M, F, K):
     _gated_check(dtype, got, ref, slack)
 
 
-@pytest.mark.parametrize("M,context", [(8, False), (24, False), (48, False), (128, False), (300, True), (513, True),
-                                       (1024, True)])
+@pytest.mark.parametrize("M,context", [(8, False), (24, False), (48, False), (64, False), (72, False), (96, False),
+                                       (112, False), (128, False), (300, True), (513, True), (1024, True)])
 def test_gated_mlp_full_size_sampled_columns(M, context):
-    """The 7B gate|up shape at row counts that select each variant of the one-launch form (1, 2, 4 and 8 row tiles); as a
+    """The 7B gate|up shape at row counts that select each variant of the one-launch form (1 to 8 row tiles); as a
     context pass: one slice with the activation as the 256-row-block kernel's epilogue (300, 513 and
     1024 rows, incl. ragged last blocks) -- sampled MLP columns from the oracle."""
     dtype, F, K = synth.DT_BF16, 11008, 4096
