@@ -194,7 +194,10 @@ int32_t flover_reorder_evict(flover_ctx* ctx, flover_reorder_out* out);
  * Read-only views of the scheduler and the cache, and two hooks that let a test steer a stream. */
 
 /* End a request as if it had produced EOS; overwrite the token a live request feeds in the next iteration
- * (teacher forcing, to re-synchronise a comparison after a near tie). */
+ * (teacher forcing, to re-synchronise a comparison after a near tie).  A request may be ended before it has joined an
+ * iteration, also while its context passes are still queued (async_preprocess): the next flover_reorder_evict frees
+ * the slot, and whatever is enqueued for that slot afterwards -- a shuffle copy into it, the context passes of its
+ * next tenant on either pre-processing stream -- is ordered behind the passes already queued for it. */
 int32_t flover_mark_finished(flover_ctx* ctx, uint64_t req_id);
 int32_t flover_set_next_token(flover_ctx* ctx, uint64_t req_id, int32_t token);
 
